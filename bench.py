@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the DLRM sparse hot path on one MI355X.
+
+One step = one pass of the whole hot path over one mini-batch that is already in
+HBM: dense placement, pooled embedding lookup, dot interaction forward, dot
+interaction backward, embedding backward with the fused sparse SGD update.
+Prints ONE JSON line (metric, roofline of the dominant kernel, CPU-oracle
+baseline).  Inputs are seeded and synthetic (workloads/gen.py)."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "emb-bag fwd+bwd lookups/s & HBM GB/s (% of peak); samples/s at batch 2048"
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = multi-hot bandwidth)")
+    ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
+    ap.add_argument("--nbatches", type=int, default=0, help="distinct batches cycled (0 = pick)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def algorithmic_bytes(w, batch, elem_bytes):
+    """Minimum HBM traffic of the embedding forward / backward for this batch (ideal cache:
+    each touched row once, each index, offset, pooled vector and gradient once)."""
+    import numpy as np
+    U = sum(len(np.unique(batch.indices_of(k))) for k in range(w.K))
+    nnz = batch.nnz
+    csr = nnz * 8 + w.K * (w.B + 1) * 8
+    pooled = w.K * w.B * w.d * 4
+    fwd = U * w.d * elem_bytes + csr + pooled
+    bwd = pooled + csr + 2 * U * w.d * elem_bytes
+    int_fwd = w.B * (w.F * w.d + w.d + w.P) * 4
+    int_bwd = w.B * (2 * w.F * w.d + w.d + w.P) * 4
+    return dict(U=U, nnz=nnz, fwd=fwd, bwd=bwd, int_fwd=int_fwd, int_bwd=int_bwd,
+                fwd_logical=nnz * w.d * elem_bytes + csr + pooled)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "re-run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_1906_00091_amd as hot
+    from workloads import gen
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = gen.WORKLOADS[args.config]
+    eb = gen.ELEM_BYTES[w.dtype]
+    algo = {"auto": hot.BWD_AUTO, "sort": hot.BWD_SORT, "atomic": hot.BWD_ATOMIC}[args.algo]
+    B, F, d, P, K = w.B, w.F, w.d, w.P, w.K
+
+    # ---- inputs, resident in HBM before anything is timed
+    rows = gen.table_rows(w)
+    first = gen.make_batch(w, rows=rows)
+    ab0 = algorithmic_bytes(w, first, eb)
+    nb = args.nbatches
+    if nb <= 0:  # enough distinct batches that one batch's rows are out of the 256 MB cache again
+        nb = int(min(32, max(2, -(-(1 << 30) // max(ab0["fwd"], 1)))))
+    batches = [first] + [gen.make_batch(w, batch_id=i, rows=rows) for i in range(1, nb)]
+    abytes = [ab0] + [algorithmic_bytes(w, b, eb) for b in batches[1:]]
+    tdt = {gen.F32: torch.float32, gen.F16: torch.float16, gen.BF16: torch.bfloat16}[w.dtype]
+    tables = []
+    for k in range(K):
+        t = torch.empty((int(rows[k]), d), dtype=tdt, device=dev)
+        hot.dlrm_table_init_hash(t, w.dtype, gen.table_key(w.seed, k), float(gen.table_scale(int(rows[k]))))
+        tables.append(t)
+    dev_batches = []
+    for b in batches:
+        sb = hot.SparseBatch(tables, w.dtype, torch.from_numpy(b.indices).to(dev),
+                             torch.from_numpy(np.ascontiguousarray(b.offsets)).to(dev),
+                             torch.from_numpy(b.tbl_off).to(dev), b.nnz, max_rows=int(rows.max()))
+        dev_batches.append((sb, torch.from_numpy(b.x).to(dev), torch.from_numpy(b.dR).to(dev)))
+    max_nnz = max(b.nnz for b in batches)
+    ws_bytes = hot.dlrm_emb_bag_bwd_workspace_bytes(K, B, d, max_nnz, int(rows.max()), w.dtype)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    T = torch.empty((B, F, d), dtype=torch.float32, device=dev)
+    R = torch.empty((B, d + P), dtype=torch.float32, device=dev)
+    dT = torch.empty((B, F, d), dtype=torch.float32, device=dev)
+    lr = float(np.float32(w.lr))
+
+    stages = ["place_dense", "emb_bag_fwd", "interact_dot_fwd", "interact_dot_bwd", "emb_bag_bwd_sgd"]
+
+    def step(i, ev=None):
+        sb, x, dR = dev_batches[i % nb]
+        if ev is not None:
+            ev[0].record()
+        hot.dlrm_place_dense(x, T)
+        if ev is not None:
+            ev[1].record()
+        hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+        if ev is not None:
+            ev[2].record()
+        hot.dlrm_interact_dot_fwd(T, R)
+        if ev is not None:
+            ev[3].record()
+        hot.dlrm_interact_dot_bwd(T, dR, dT)
+        if ev is not None:
+            ev[4].record()
+        hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo, dS_offset=d)
+        if ev is not None:
+            ev[5].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # ---- timed region: exactly --steps steps, events on the launch stream around every call
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    stage_ms = {s: 0.0 for s in stages}
+    for ev in events:
+        for j, s in enumerate(stages):
+            stage_ms[s] += ev[j].elapsed_time(ev[j + 1])
+    for s in stages:
+        stage_ms[s] /= args.steps
+
+    ids = [(args.warmup + i) % nb for i in range(args.steps)]
+    mean = lambda key: float(np.mean([abytes[i][key] for i in ids]))
+    nnz_mean = mean("nnz")
+    lookups_per_s = nnz_mean / (ms_per_step * 1e-3)
+    emb_ms = stage_ms["emb_bag_fwd"] + stage_ms["emb_bag_bwd_sgd"]
+    emb_bytes = mean("fwd") + mean("bwd")
+
+    # ---- roofline of the dominant kernel (the embedding forward and backward are HBM-bound)
+    if stage_ms["emb_bag_fwd"] >= stage_ms["emb_bag_bwd_sgd"] or True:
+        dom, dom_bytes, dom_ms = "emb_bag_fwd", mean("fwd"), stage_ms["emb_bag_fwd"]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_ms": round(dom_ms, 5)}
+
+    out = {
+        "metric": METRIC, "value": round(lookups_per_s, 1), "unit": "lookups/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": gen.DTYPE_NAMES[w.dtype] if w.dtype != gen.F16 else "f16 tables, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "%d:%s" % (args.config, w.name), "tables": K, "batch": B, "dim": d,
+                   "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
+                   "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
+                   "bwd_algo": args.algo, "lr": w.lr},
+        "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
+        "emb_fwd_bwd": {"ms": round(emb_ms, 5), "lookups_per_s": round(nnz_mean / (emb_ms * 1e-3), 1),
+                        "algorithmic_GBps": round(emb_bytes / (emb_ms * 1e-3) / 1e9, 1),
+                        "frac_of_hbm_peak": round(emb_bytes / (emb_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
+        "stage_algorithmic_GBps": {
+            "emb_bag_fwd": round(mean("fwd") / (stage_ms["emb_bag_fwd"] * 1e-3) / 1e9, 1),
+            "emb_bag_bwd_sgd": round(mean("bwd") / (stage_ms["emb_bag_bwd_sgd"] * 1e-3) / 1e9, 1),
+            "interact_dot_fwd": round(mean("int_fwd") / (stage_ms["interact_dot_fwd"] * 1e-3) / 1e9, 1),
+            "interact_dot_bwd": round(mean("int_bwd") / (stage_ms["interact_dot_bwd"] * 1e-3) / 1e9, 1)},
+        "roofline": roofline,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on this machine's host cores, same workload
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        b = batches[0]
+        host_tables = []
+        full = sum(int(r) for r in rows) * d * eb <= 8 << 30
+        if full:
+            for t in tables:
+                a = t.cpu()
+                host_tables.append(a.view(torch.int16).numpy().view(np.uint16) if w.dtype == gen.BF16
+                                   else a.numpy())
+            idx = b.indices
+            sample = "whole steps of workload %d on full-size host tables copied from the device" % args.config
+        else:  # tables too large for the host: touched rows only (flatters the CPU's caches)
+            idx = np.empty_like(b.indices)
+            for k in range(K):
+                u = np.unique(b.indices_of(k))
+                sel = torch.from_numpy(u).to(dev)
+                a = tables[k].index_select(0, sel).cpu()
+                host_tables.append(a.view(torch.int16).numpy().view(np.uint16) if w.dtype == gen.BF16
+                                   else a.numpy())
+                idx[b.tbl_off[k]:b.tbl_off[k + 1]] = np.searchsorted(u, b.indices_of(k))
+            sample = "whole steps of workload %d on the touched rows only (compacted tables)" % args.config
+        nsteps, t_cpu = 0, 0.0
+        while t_cpu < args.cpu_seconds and nsteps < 1000:
+            c0 = time.perf_counter()
+            S = oracle.emb_bag_fwd(host_tables, w.dtype, idx, b.offsets, b.tbl_off)
+            Th = np.concatenate([b.x[:, None, :], S.astype(np.float32)], axis=1)
+            oracle.interact_dot_fwd(Th)
+            dTh = oracle.interact_dot_bwd(Th, b.dR)
+            oracle.emb_bag_bwd_sgd(host_tables, w.dtype, idx, b.offsets, b.tbl_off,
+                                   np.ascontiguousarray(dTh[:, 1:, :], dtype=np.float32), lr)
+            t_cpu += time.perf_counter() - c0
+            nsteps += 1
+        out["cpu_baseline"] = {"value": round(b.nnz * nsteps / t_cpu, 1), "unit": "lookups/s",
+                               "cores": oracle.get_threads(), "kind": "oracle",
+                               "sample": "%d %s, %.1f s" % (nsteps, sample, t_cpu)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,202 @@
+/*
+ * dlrm_hot -- the sparse-feature hot path of DLRM on one MI355X (gfx950).
+ *
+ * C ABI.  Every pointer is a DEVICE pointer owned by the caller unless a
+ * comment says "host".  The library allocates nothing, keeps no state between
+ * calls, and only enqueues work on the HIP stream passed as `stream`
+ * (a hipStream_t cast to void*; NULL = the default stream).  No call
+ * synchronises with the host.
+ *
+ * Every function returns a status: DLRM_OK, or a negative DLRM_ERR_* value.
+ * Argument errors are detected on the host BEFORE anything is launched; a
+ * failed launch is reported as DLRM_ERR_HIP.
+ *
+ * Notation (follows the paper): K embedding tables, table k is
+ * W_k in R^{m_k x d} stored row-major and contiguous; mini-batch size B; the
+ * lookups of table k form B "bags" given in the CSR-like encoding of Sec. 4.1
+ * (indices + offsets); F = K + 1 vectors enter the interaction (the processed
+ * dense vector x and the K pooled vectors); P = F(F-1)/2 distinct pairs.
+ */
+#ifndef DLRM_HOT_H_
+#define DLRM_HOT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define DLRM_OK 0
+#define DLRM_ERR_NULL (-1)      /* a required pointer is NULL */
+#define DLRM_ERR_BAD_SHAPE (-2) /* K, B, d, F, strides, nnz or max_rows outside the supported range */
+#define DLRM_ERR_BAD_DTYPE (-3) /* unknown table dtype, or dtype not supported by the chosen algo */
+#define DLRM_ERR_WORKSPACE (-4) /* workspace NULL, misaligned or smaller than the query says */
+#define DLRM_ERR_BAD_ALGO (-5)  /* unknown backward algorithm */
+#define DLRM_ERR_HIP (-6)       /* a HIP call / kernel launch failed */
+
+/* table storage types.  The paper uses fp32 parameters (Sec. 5); fp16/bf16
+ * storage is an extension: rows are widened exactly, all sums are fp32, and a
+ * row is rounded to nearest-even once when it is written back. */
+#define DLRM_F32 0
+#define DLRM_F16 1
+#define DLRM_BF16 2
+
+/* backward algorithms */
+#define DLRM_BWD_AUTO 0   /* library's measured choice for the shape */
+#define DLRM_BWD_SORT 1   /* group (row, bag) pairs by row, reduce, one update per row; deterministic */
+#define DLRM_BWD_ATOMIC 2 /* fp32 tables only: one hardware fp32 atomic add per looked-up element */
+
+/* supported ranges */
+#define DLRM_MAX_ROW_BYTES 1024         /* d * sizeof(element) <= 1024, multiple of 16 */
+#define DLRM_MAX_ROWS 2147483647LL      /* m_k < 2^31 */
+#define DLRM_MAX_NNZ 2147483647LL       /* total lookups per batch < 2^31 */
+#define DLRM_MAX_INTERACT_F 128         /* F <= 128 */
+
+/*
+ * One mini-batch of sparse lookups for all K tables (Sec. 2.1.1, Eq. (2);
+ * encoding of Sec. 4.1: concatenated indices delineated by offsets).
+ * The struct itself lives in HOST memory; the arrays it points to are DEVICE
+ * arrays.  Indices are 0-based, 0 <= index < rows[k] (the paper's example uses
+ * index 0).  The hot calls do NOT range-check indices: an out-of-range index is
+ * undefined behaviour; dlrm_validate_csr is the checked path.
+ */
+typedef struct dlrm_sparse_batch {
+  int32_t K;               /* number of tables, >= 1 */
+  int32_t B;               /* bags per table (mini-batch size), >= 1 */
+  int32_t d;               /* embedding dimension; d*elem_size a multiple of 16, <= DLRM_MAX_ROW_BYTES */
+  int32_t table_dtype;     /* DLRM_F32 | DLRM_F16 | DLRM_BF16 */
+  int64_t nnz_total;       /* host copy of tbl_off[K]: total lookups, 0 <= nnz_total <= DLRM_MAX_NNZ */
+  int64_t max_rows;        /* host upper bound on rows[k] over all k, 1 <= max_rows <= DLRM_MAX_ROWS */
+  void* const* tables;     /* [K] base pointer of table k: [rows[k], d] row-major, 16-byte aligned */
+  const int64_t* rows;     /* [K] m_k */
+  const int64_t* indices;  /* [nnz_total] table-major: table k owns [tbl_off[k], tbl_off[k+1]) */
+  const int64_t* offsets;  /* [K*(B+1)] per-table local offsets; bag b of table k = positions
+                              [offsets[k*(B+1)+b], offsets[k*(B+1)+b+1]); offsets[k*(B+1)+B] = nnz_k */
+  const int64_t* tbl_off;  /* [K+1] start of table k's slice in `indices` */
+} dlrm_sparse_batch;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t dlrm_version(void);
+
+/* Static, host-side text for a status code. */
+const char* dlrm_status_string(int32_t status);
+
+/*
+ * CSR helper (Sec. 4.1 footnote: lengths, as SparseLengthsSum takes them, vs
+ * offsets, as EmbeddingBag takes them).  Exclusive scan per table:
+ *   offsets[k*(B+1)+0] = 0, offsets[k*(B+1)+b+1] = offsets[k*(B+1)+b] + lengths[k*B+b]
+ *   tbl_off[0] = 0, tbl_off[k+1] = tbl_off[k] + offsets[k*(B+1)+B]
+ * lengths: [K*B] int32, each >= 0.  Integer work, exact.
+ */
+int32_t dlrm_lengths_to_offsets(const int32_t* lengths, int32_t K, int32_t B, int64_t* offsets,
+                                int64_t* tbl_off, void* stream);
+
+/*
+ * Checked path for a batch: writes to *n_bad (device int64 scalar) the number of
+ * violations: offsets[k][0] != 0, decreasing offsets, offsets[k][B] != nnz_k,
+ * tbl_off not matching, index < 0 or >= rows[k].  Reads only inside the arrays'
+ * stated extents whatever their contents.
+ */
+int32_t dlrm_validate_csr(const dlrm_sparse_batch* batch, int64_t* n_bad, void* stream);
+
+/*
+ * Sum-pooled embedding lookup, Eq. (2) with unit weights (Eq. (1) when a bag has
+ * one index):  out[b*stride_b + k*stride_k + c] = sum over the bag's positions p
+ * of W_k[indices[p], c], c < d.  An index repeated inside a bag counts once per
+ * occurrence; an empty bag gives zeros.  Sums are fp32, positions in ascending
+ * order per lane group; a one-index bag is an exact copy of the row (widened).
+ * out: fp32, strides in elements, stride_k >= d, 16-byte aligned rows
+ * (stride_b, stride_k multiples of 4).  Writing straight into rows 1..K of the
+ * interaction input T[B,F,d] is: out = T + d, stride_b = F*d, stride_k = d.
+ */
+int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* batch, float* out, int64_t stride_b,
+                         int64_t stride_k, void* stream);
+
+/*
+ * Places the processed dense vector (the bottom MLP's output, same length as the
+ * embedding vectors, Sec. 2.2) as row 0 of the interaction input:
+ * T[b,0,:] = x[b,:].  x: [B,d] fp32; T: [B,F,d] fp32.  Exact copy.  d multiple of 4.
+ */
+int32_t dlrm_place_dense(const float* x, int32_t B, int32_t d, float* T, int32_t F, void* stream);
+
+/*
+ * Dot-product feature interaction (Sec. 2.2: dot products between all pairs of
+ * the F vectors, concatenated with the processed dense vector; distinct pairs
+ * only, as the strict triangle in Eq. (4)).
+ *   R[b, 0:d]                    = T[b,0,:]                       (exact copy)
+ *   R[b, d + i(i-1)/2 + j]       = <T[b,i,:], T[b,j,:]>,  1 <= i < F, 0 <= j < i
+ * T: [B,F,d] fp32 contiguous; R: [B, d + P] fp32 contiguous.  fp32 FMA.
+ * Requires d a multiple of 4, 1 <= F <= DLRM_MAX_INTERACT_F.
+ */
+int32_t dlrm_interact_dot_fwd(const float* T, int32_t B, int32_t F, int32_t d, float* R,
+                              void* stream);
+
+/*
+ * Backward of the above by the chain rule (the paper prints none).  With
+ * g_ij = dR[b, d + i(i-1)/2 + j]:
+ *   dT[b,i,:] = sum_{j<i} g_ij T[b,j,:] + sum_{j>i} g_ji T[b,j,:]  (+ dR[b,0:d] for i = 0)
+ * dT: [B,F,d] fp32; row 0 is the gradient of the dense vector, rows 1..K are dS,
+ * the gradients of the pooled vectors.
+ */
+int32_t dlrm_interact_dot_bwd(const float* T, const float* dR, int32_t B, int32_t F, int32_t d,
+                              float* dT, void* stream);
+
+/*
+ * Bytes of workspace dlrm_emb_bag_bwd_sgd / dlrm_emb_bag_bwd_export_groups need
+ * for this shape (enough for every algo).  Returns 0 for an unsupported shape.
+ */
+size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t nnz_total,
+                                        int64_t max_rows, int32_t table_dtype);
+
+/*
+ * Embedding backward fused with the sparse SGD update (transpose of Eq. (2);
+ * SGD without regularisation, Sec. 5.1).  For every distinct row r that table k
+ * looks up in this batch:
+ *   g = sum over positions p with indices[p] == r of dS[bag(p)*stride_b + k*stride_k + :]
+ *   W_k[r,:] <- W_k[r,:] - lr * g
+ * Rows that are not looked up keep their bits.  Tables are updated in place.
+ * DLRM_BWD_SORT: duplicates are summed first (fp32, ascending position) and
+ * the row is written once (one rounding for fp16/bf16); bitwise reproducible.
+ * DLRM_BWD_ATOMIC: fp32 tables only; each occurrence is applied with a hardware
+ * fp32 atomic add of -lr*dS, so the rounding order varies from run to run.
+ * dS: fp32, strides in elements (rows 1..K of dT: dS = dT + d, stride_b = F*d,
+ * stride_k = d); 16-byte aligned rows.
+ * workspace: device memory, 256-byte aligned, at least
+ * dlrm_emb_bag_bwd_workspace_bytes(...) bytes; contents are scratch.
+ */
+int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
+                             int64_t stride_k, float lr, void* workspace, size_t workspace_bytes,
+                             int32_t algo, void* stream);
+
+/*
+ * Runs only the grouping stage of DLRM_BWD_SORT and exports it in canonical
+ * form, for checking index handling bit for bit.  Per table k, in that table's
+ * slice [tbl_off[k], tbl_off[k+1]) of each output array:
+ *   uniq_rows  (int64) : distinct rows ascending, first n_uniq[k] entries
+ *   seg_start  (int64) : start of each row's run in sorted_bag, local to the slice
+ *   sorted_bag (int32) : bag of every position, ordered by (row asc, position asc)
+ *   n_uniq     (int64) : [K]
+ * Entries of uniq_rows / seg_start past n_uniq[k] are left untouched.
+ */
+int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* batch, void* workspace,
+                                       size_t workspace_bytes, int64_t* uniq_rows,
+                                       int64_t* seg_start, int32_t* sorted_bag, int64_t* n_uniq,
+                                       void* stream);
+
+/*
+ * Synthetic-input helper (not part of the method): fills a table with the
+ * counter-based uniform initialiser U(-scale, scale):
+ *   h = mix(key + row*d + col); u = h >> 40; x = (2u + 1 - 2^24) / 2^24;
+ *   W[row,col] = fp32(x) * scale, rounded once to the table dtype,
+ * mix = the splitmix64 output function.  Lets a table of tens of GB be created
+ * on the device and any row be re-derived on the host.
+ */
+int32_t dlrm_table_init_hash(void* table, int64_t rows, int32_t d, int32_t table_dtype,
+                             uint64_t key, float scale, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DLRM_HOT_H_ */

@@ -1,0 +1,208 @@
+// Sum-pooled embedding lookup (Sec. 2.1.1, Eq. (1)-(2) with unit weights):
+// S_k[b,:] = sum over the positions of bag (k,b) of W_k[idx,:].
+//
+// HBM-bound gather.  A table row is d*e bytes; a lane moves 16 bytes
+// (global_load_dwordx4), so a row occupies a "lane group" of G = pow2(d*e/16)
+// lanes and a 64-wide wavefront carries S = 64/G rows per load instruction.
+//   * group kernel: every lane group owns one bag and walks it with U loads in
+//     flight (one-hot and short bags: a pure gather).
+//   * wave kernel : the whole wavefront owns one bag; its 64 indices per chunk are
+//     fetched with one coalesced load and handed to the lane groups through
+//     cross-lane reads; group s takes positions s, s+S, ...; the S partial sums
+//     meet in an xor butterfly over the lane groups.
+// All K tables go in one launch (grid over table x bag).
+#include "common.h"
+
+namespace dlrm {
+
+struct FwdArgs {
+  void* const* tables;
+  const int64_t* indices;
+  const int64_t* offsets;
+  const int64_t* tbl_off;
+  float* out;
+  int64_t stride_b, stride_k;
+  int32_t K, B, d;
+  int32_t chunks;  // 16-byte chunks per table row
+};
+
+template <int DT>
+__device__ inline void write_pooled(float* o, const float* acc) {
+  constexpr int E = Tab<DT>::ELEMS;
+#pragma unroll
+  for (int i = 0; i < E; i += 4) storef4(o + i, f32x4{acc[i], acc[i + 1], acc[i + 2], acc[i + 3]});
+}
+
+// ---------------------------------------------------------------------------
+template <int DT, int G, int U>
+__global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
+  constexpr int E = Tab<DT>::ELEMS;
+  constexpr int S = DLRM_WAVE / G;
+  const int lane = lane_id();
+  const int slot = lane / G, chunk = lane % G;
+  // K*(B+1) < 2^31 is checked on the host, so 32-bit bag arithmetic is exact
+  const uint32_t bag = (blockIdx.x * (blockDim.x >> 6) + wave_id()) * S + slot;
+  if (bag >= (uint32_t)a.K * (uint32_t)a.B || chunk >= a.chunks) return;  // no cross-lane ops below
+  const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
+  const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
+  const int64_t p0 = off[b], p1 = off[b + 1];
+  const int64_t* idx = a.indices + a.tbl_off[k];
+  const char* W = static_cast<const char*>(a.tables[k]) + chunk * 16;
+  const int64_t row_bytes = (int64_t)a.chunks * 16;
+
+  float acc[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) acc[i] = -0.0f;
+
+  for (int64_t p = p0; p < p1; p += U) {
+    // all U index loads, then all U row loads, are issued before anything is consumed; the
+    // tail re-reads the bag's last position (in cache) and is replaced by the identity
+    int64_t r[U];
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) r[u] = idx[p + u < p1 ? p + u : p1 - 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = load16(W + r[u] * row_bytes);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (p + u >= p1) v[u] = Tab<DT>::ident();
+      float f[E];
+      Tab<DT>::widen(v[u], f);
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] += f[i];
+    }
+  }
+  if (p1 <= p0) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+  }
+  write_pooled<DT>(a.out + (int64_t)b * a.stride_b + (int64_t)k * a.stride_k + chunk * E, acc);
+}
+
+// ---------------------------------------------------------------------------
+template <int DT, int G, int U>
+__global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
+  constexpr int E = Tab<DT>::ELEMS;
+  constexpr int S = DLRM_WAVE / G;
+  const int lane = lane_id();
+  const int slot = lane / G, chunk = lane % G;
+  const uint32_t bag = blockIdx.x * (blockDim.x >> 6) + wave_id();
+  if (bag >= (uint32_t)a.K * (uint32_t)a.B) return;  // wave-uniform
+  const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
+  const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
+  const int64_t p0 = off[b], p1 = off[b + 1];
+  const int64_t* idx = a.indices + a.tbl_off[k] + p0;
+  const bool col_ok = chunk < a.chunks;
+  // lanes past the row's last chunk shadow chunk 0 (same address, no extra traffic) and never write
+  const char* W = static_cast<const char*>(a.tables[k]) + (col_ok ? chunk : 0) * 16;
+  const int64_t row_bytes = (int64_t)a.chunks * 16;
+  const int64_t len = p1 - p0;
+
+  float acc[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) acc[i] = -0.0f;
+
+  for (int64_t base = 0; base < len; base += DLRM_WAVE) {
+    const int n = (int)((len - base) < DLRM_WAVE ? (len - base) : DLRM_WAVE);
+    // one coalesced fetch of this chunk's indices; rows are < 2^31
+    const uint32_t my_row = (uint32_t)idx[base + (lane < n ? lane : n - 1)];
+    const int iters = (n + S - 1) / S;
+    for (int j = 0; j < iters; j += U) {
+      u32x4 v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int e = (j + u) * S + slot;
+        const uint32_t r = __shfl(my_row, e < n ? e : n - 1, DLRM_WAVE);
+        v[u] = load16(W + (int64_t)r * row_bytes);   // branch-free: the tail re-reads position n-1
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if ((j + u) * S + slot >= n) v[u] = Tab<DT>::ident();
+        float f[E];
+        Tab<DT>::widen(v[u], f);
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] += f[i];
+      }
+    }
+  }
+  // combine the S lane groups: xor butterfly, identical result in every group
+#pragma unroll
+  for (int o = G; o < DLRM_WAVE; o <<= 1) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] += __shfl_xor(acc[i], o, DLRM_WAVE);
+  }
+  if (slot != 0 || !col_ok) return;
+  if (len <= 0) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+  }
+  write_pooled<DT>(a.out + (int64_t)b * a.stride_b + (int64_t)k * a.stride_k + chunk * E, acc);
+}
+
+// ---------------------------------------------------------------------------
+template <int DT, int G>
+static int launch_fwd(const FwdArgs& a, bool wave_mode, hipStream_t st) {
+  constexpr int S = DLRM_WAVE / G;
+  const int64_t bags = (int64_t)a.K * a.B;
+  if (wave_mode) {
+    const unsigned grid = div_up(bags, 4);
+    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4>), dim3(grid), dim3(256), 0, st, a);
+  } else {
+    const unsigned grid = div_up(bags, 4 * S);
+    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4>), dim3(grid), dim3(256), 0, st, a);
+  }
+  DLRM_CHECK_LAUNCH();
+  return DLRM_OK;
+}
+
+template <int DT>
+static int dispatch_g(const FwdArgs& a, int G, bool wave_mode, hipStream_t st) {
+  switch (G) {
+    case 1: return launch_fwd<DT, 1>(a, wave_mode, st);
+    case 2: return launch_fwd<DT, 2>(a, wave_mode, st);
+    case 4: return launch_fwd<DT, 4>(a, wave_mode, st);
+    case 8: return launch_fwd<DT, 8>(a, wave_mode, st);
+    case 16: return launch_fwd<DT, 16>(a, wave_mode, st);
+    case 32: return launch_fwd<DT, 32>(a, wave_mode, st);
+    case 64: return launch_fwd<DT, 64>(a, wave_mode, st);
+  }
+  return DLRM_ERR_BAD_SHAPE;
+}
+
+int check_batch(const dlrm_sparse_batch* s);  // util.hip
+
+}  // namespace dlrm
+
+extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int64_t stride_b,
+                                    int64_t stride_k, void* stream) {
+  using namespace dlrm;
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  if (!out) return DLRM_ERR_NULL;
+  if (stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0) return DLRM_ERR_BAD_SHAPE;
+  if ((reinterpret_cast<uintptr_t>(out) & 15) != 0) return DLRM_ERR_BAD_SHAPE;
+  FwdArgs a;
+  a.tables = s->tables;
+  a.indices = s->indices;
+  a.offsets = s->offsets;
+  a.tbl_off = s->tbl_off;
+  a.out = out;
+  a.stride_b = stride_b;
+  a.stride_k = stride_k;
+  a.K = s->K;
+  a.B = s->B;
+  a.d = s->d;
+  a.chunks = s->d * elem_bytes(s->table_dtype) / 16;
+  const int G = pow2_ceil(a.chunks);
+  const int S = DLRM_WAVE / G;
+  // a wavefront per bag pays off once a bag keeps all S lane groups busy for a few rounds
+  const double mean_len = (double)s->nnz_total / ((double)s->K * s->B);
+  const bool wave_mode = S > 1 ? mean_len >= 2.0 * S : mean_len >= 1e30;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  switch (s->table_dtype) {
+    case DLRM_F32: return dispatch_g<DLRM_F32>(a, G, wave_mode, hs);
+    case DLRM_F16: return dispatch_g<DLRM_F16>(a, G, wave_mode, hs);
+    case DLRM_BF16: return dispatch_g<DLRM_BF16>(a, G, wave_mode, hs);
+  }
+  return DLRM_ERR_BAD_DTYPE;
+}

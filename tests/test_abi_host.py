@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_1906_00091_amd as hot
+from paper_1906_00091_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "dlrm_hot.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dlrm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert len(names) >= 11
+    L = hot.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert hot.version() >= 100
+    assert hot.status_string(0) == "ok" and "NULL" in hot.status_string(-1)
+
+
+def _batch(**kw):
+    base = dict(K=2, B=4, d=16, table_dtype=0, nnz_total=8, max_rows=100, tables=0x1000,
+                rows=0x1000, indices=0x1000, offsets=0x1000, tbl_off=0x1000)
+    base.update(kw)
+    return binding._SparseBatchC(**base)
+
+
+def test_forward_rejects_bad_arguments_on_the_host():
+    L = hot.lib()
+    out = C.c_void_p(0x1000)
+    call = lambda b, o=out, sb=64, sk=16: L.dlrm_emb_bag_fwd(C.byref(b), o, sb, sk, None)
+    assert call(_batch(tables=None)) == -1
+    assert call(_batch(), o=None) == -1
+    assert call(_batch(K=0)) == -2
+    assert call(_batch(d=6)) == -2                  # 24-byte rows: not a multiple of 16
+    assert call(_batch(d=512)) == -2                # 2 KB rows: above the supported row size
+    assert call(_batch(table_dtype=7)) == -3
+    assert call(_batch(max_rows=1 << 31)) == -2
+    assert call(_batch(nnz_total=-1)) == -2
+    assert call(_batch(), sk=8) == -2               # stride_k < d
+    assert call(_batch(), o=C.c_void_p(0x1004)) == -2
+    assert L.dlrm_emb_bag_fwd(None, out, 64, 16, None) == -1
+
+
+def test_backward_rejects_bad_arguments_on_the_host():
+    L = hot.lib()
+    ds = C.c_void_p(0x1000)
+    need = hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 8, 100, 0)
+    assert need > 0 and need % 256 == 0
+    call = lambda b, ws, n, algo: L.dlrm_emb_bag_bwd_sgd(C.byref(b), ds, 64, 16, C.c_float(0.01), ws,
+                                                         n, algo, None)
+    assert call(_batch(), None, 0, hot.BWD_SORT) == -4
+    assert call(_batch(), C.c_void_p(0x1000), need - 1, hot.BWD_SORT) == -4
+    assert call(_batch(), C.c_void_p(0x1010), need, hot.BWD_SORT) == -4      # misaligned
+    assert call(_batch(), C.c_void_p(0x1000), need, 9) == -5
+    assert call(_batch(table_dtype=1), C.c_void_p(0x1000), need, hot.BWD_ATOMIC) == -3
+    assert hot.dlrm_emb_bag_bwd_workspace_bytes(0, 4, 16, 8, 100, 0) == 0
+    assert hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 8, 100, 5) == 0
+    # workspace grows with the number of lookups
+    assert hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 1 << 20, 100, 0) > need
+
+
+def test_interaction_and_helpers_reject_bad_arguments_on_the_host():
+    L = hot.lib()
+    p = C.c_void_p(0x1000)
+    assert L.dlrm_interact_dot_fwd(None, 4, 3, 16, p, None) == -1
+    assert L.dlrm_interact_dot_fwd(p, 4, 3, 6, p, None) == -2
+    assert L.dlrm_interact_dot_fwd(p, 0, 3, 16, p, None) == -2
+    assert L.dlrm_interact_dot_fwd(p, 4, 500, 16, p, None) == -2
+    assert L.dlrm_interact_dot_bwd(p, p, 4, 3, 16, None, None) == -1
+    assert L.dlrm_place_dense(p, 4, 16, None, 3, None) == -1
+    assert L.dlrm_lengths_to_offsets(p, 0, 4, p, p, None) == -2
+    assert L.dlrm_validate_csr(C.byref(_batch()), None, None) == -1
+    assert L.dlrm_table_init_hash(p, 10, 6, 0, C.c_uint64(1), C.c_float(1.0), None) == -2
+
+
+def test_binding_raises_instead_of_falling_back():
+    with pytest.raises(hot.DlrmError):
+        binding._check("dlrm_emb_bag_fwd", -2)
+    src = open(os.path.join(ROOT, "paper_1906_00091_amd", "binding.py")).read()
+    assert "oracle" not in src.replace("no fallback", "")

@@ -1,0 +1,150 @@
+"""The five benchmark workloads at full size, through the C ABI in the same launch
+configuration the benchmark times (the library picks kernels from the shape, so
+same shape = same launches).  Tables are created on the device by the
+counter-based initialiser; the oracle runs on the touched rows only, which are
+re-derived on the host, and every stage is checked against the oracle fed with
+that stage's actual inputs."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import paper_1906_00091_amd as hot
+from oracle import oracle
+from workloads import gen
+
+from hotpath_util import (DEV, TOL, Compact, device_hash_tables, make_sparse_batch, rel_err,
+                          scale_emb_fwd, scale_interact_bwd, scale_interact_fwd, scale_sgd,
+                          table_to_numpy, widen_host)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[cfg] " + msg, flush=True)
+
+
+def _check_config(cfg_id, algo=hot.BWD_AUTO, sample_untouched=20000):
+    w = gen.WORKLOADS[cfg_id]
+    t0 = time.time()
+    b = gen.make_batch(w)
+    _say("%s: K=%d B=%d d=%d nnz=%d rows=%d  (generated in %.1fs)" %
+         (w.name, w.K, w.B, w.d, b.nnz, int(b.rows.sum()), time.time() - t0))
+    tables = device_hash_tables(b)
+    sb = make_sparse_batch(b, tables)
+    n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    hot.dlrm_validate_csr(sb, n_bad)
+    assert int(n_bad.item()) == 0
+    F, P, B, d, K = w.F, w.P, w.B, w.d, w.K
+    T = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+    R = torch.empty((B, d + P), dtype=torch.float32, device=DEV)
+    dT = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+    dR = torch.from_numpy(b.dR).to(DEV)
+    ws = hot.alloc_workspace(sb)
+    lr = float(np.float32(w.lr))
+    _say("forward")
+    hot.dlrm_place_dense(torch.from_numpy(b.x).to(DEV), T)
+    hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+    hot.dlrm_interact_dot_fwd(T, R)
+    _say("backward")
+    hot.dlrm_interact_dot_bwd(T, dR, dT)
+    hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo, dS_offset=d)
+    torch.cuda.synchronize()
+    _say("device done; oracle on touched rows")
+    comp = Compact(b)
+    T_h = T.cpu().numpy()
+    # a2: pooled lookup
+    S_ref = oracle.emb_bag_fwd(comp.tables, w.dtype, comp.indices, b.offsets, b.tbl_off)
+    assert np.array_equal(T_h[:, 0, :].view(np.uint32), b.x.view(np.uint32))        # a3: exact copy
+    e = rel_err(T_h[:, 1:, :], S_ref,
+                scale_emb_fwd(comp.tables, w.dtype, comp.indices, b.offsets, b.tbl_off))
+    _say("emb fwd rel err %.2e" % e)
+    assert e <= min(TOL[w.dtype], 1e-5)
+    if w.bag == ("fixed", 1):
+        assert np.array_equal(T_h[:, 1:, :].view(np.uint32), S_ref.astype(np.float32).view(np.uint32))
+    del S_ref
+    # a4: interaction forward, from the T the device produced
+    R_h = R.cpu().numpy()
+    R_ref = oracle.interact_dot_fwd(T_h)
+    e = rel_err(R_h, R_ref, scale_interact_fwd(T_h))
+    _say("interact fwd rel err %.2e" % e)
+    assert e <= 1e-5
+    assert np.array_equal(R_h[:, :d].view(np.uint32), b.x.view(np.uint32))
+    del R_ref, R_h
+    # a5: interaction backward
+    dT_h = dT.cpu().numpy()
+    dT_ref = oracle.interact_dot_bwd(T_h, b.dR)
+    e = rel_err(dT_h, dT_ref, scale_interact_bwd(T_h, b.dR))
+    _say("interact bwd rel err %.2e" % e)
+    assert e <= 1e-5
+    del dT_ref, T_h
+    # a6: grouping, bit exact (distinct rows and their counts)
+    n = max(b.nnz, 1)
+    uniq = torch.empty(n, dtype=torch.int64, device=DEV)
+    seg = torch.empty(n, dtype=torch.int64, device=DEV)
+    sbag = torch.empty(n, dtype=torch.int32, device=DEV)
+    nu = torch.empty(K, dtype=torch.int64, device=DEV)
+    hot.dlrm_emb_bag_bwd_export_groups(sb, ws, uniq, seg, sbag, nu)
+    uniq_h, seg_h, sbag_h, nu_h = uniq.cpu().numpy(), seg.cpu().numpy(), sbag.cpu().numpy(), nu.cpu().numpy()
+    for k in range(K):
+        a0, a1 = int(b.tbl_off[k]), int(b.tbl_off[k + 1])
+        u, cnt = np.unique(b.indices_of(k), return_counts=True)
+        assert int(nu_h[k]) == len(u)
+        assert np.array_equal(uniq_h[a0:a0 + len(u)], u)
+        assert np.array_equal(seg_h[a0:a0 + len(u)], np.concatenate([[0], np.cumsum(cnt)[:-1]]))
+    want_groups = oracle.group_rows(b.indices, b.offsets, b.tbl_off)
+    for k in range(K):
+        a0, a1 = int(b.tbl_off[k]), int(b.tbl_off[k + 1])
+        assert np.array_equal(sbag_h[a0:a1], want_groups[k][3])
+    del want_groups
+    # a7: scatter-reduce + SGD, from the dS the device produced
+    dS_h = np.ascontiguousarray(dT_h[:, 1:, :])
+    ref_tables = [t.copy() for t in comp.tables]
+    oracle.emb_bag_bwd_sgd(ref_tables, w.dtype, comp.indices, b.offsets, b.tbl_off, dS_h, lr)
+    got_rows = comp.gather_device(tables, w.dtype)
+    scale = scale_sgd(comp.tables, w.dtype, comp.indices, b.offsets, b.tbl_off, dS_h, lr)
+    worst = 0.0
+    for k in range(K):
+        worst = max(worst, rel_err(widen_host(got_rows[k], w.dtype), widen_host(ref_tables[k], w.dtype),
+                                   scale[k]))
+        changed = np.any(got_rows[k] != comp.tables[k], axis=1)
+        assert changed.mean() > 0.99                     # touched rows did move
+    _say("tables after SGD rel err %.2e" % worst)
+    assert worst <= TOL[w.dtype]
+    # rows nobody looked up keep their bits (sampled)
+    rng = np.random.default_rng(99)
+    for k in range(K):
+        m = int(b.rows[k])
+        cand = np.unique(rng.integers(0, m, size=min(sample_untouched, m)))
+        cand = np.setdiff1d(cand, comp.uniq[k])
+        if len(cand) == 0:
+            continue
+        got = table_to_numpy(tables[k].index_select(0, torch.from_numpy(cand).to(DEV)), w.dtype)
+        want = gen.init_rows(b.seed, k, m, w.d, w.dtype, cand)
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
+    _say("ok")
+
+
+def test_config1_tiny():
+    _check_config(1)
+
+
+def test_config2_clicklog_onehot():
+    _check_config(2)
+
+
+def test_config3_multihot_bandwidth():
+    _check_config(3)
+
+
+def test_config3_multihot_bandwidth_atomic_backward():
+    _check_config(3, algo=hot.BWD_ATOMIC)
+
+
+def test_config4_large_onehot():
+    _check_config(4)
+
+
+def test_config5_hotrow_stress():
+    _check_config(5)

@@ -1,0 +1,315 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded
+inputs.  Integer / index work must match bit for bit; floating point within
+1e-5 (fp32 tables) or 1e-2 (fp16/bf16 tables) max relative error with the
+denominator floored at 1e-3 of the tensor's peak magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1906_00091_amd as hot
+from oracle import oracle
+from workloads import gen
+
+from hotpath_util import (DEV, TOL, make_sparse_batch, rel_err, scale_emb_fwd, scale_interact_bwd,
+                          scale_interact_fwd, scale_sgd, table_to_numpy, upload_tables, widen_host)
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def _host_tables(batch, scale=1.0):
+    w = batch.workload
+    return [gen.init_table(batch.seed, k, int(batch.rows[k]), w.d, w.dtype) for k in range(w.K)]
+
+
+# ------------------------------------------------------------------ helpers around the path
+def test_lengths_to_offsets_bit_exact():
+    rng = np.random.default_rng(0)
+    for K, B, hi in [(1, 3, 4), (8, 128, 5), (3, 5000, 300), (26, 2048, 2)]:
+        _say("lengths_to_offsets K=%d B=%d" % (K, B))
+        lengths = rng.integers(0, hi, size=(K, B)).astype(np.int32)
+        if K == 1:
+            lengths = np.array([[2, 3, 1]], dtype=np.int32)       # the example of Sec. 4.1
+        want_off, want_tbl = oracle.lengths_to_offsets(lengths)
+        off = torch.full((K, B + 1), -7, dtype=torch.int64, device=DEV)
+        tbl = torch.full((K + 1,), -7, dtype=torch.int64, device=DEV)
+        hot.dlrm_lengths_to_offsets(torch.from_numpy(lengths).to(DEV), off, tbl)
+        assert np.array_equal(off.cpu().numpy(), want_off)
+        assert np.array_equal(tbl.cpu().numpy(), want_tbl)
+
+
+def test_validate_csr_counts_like_the_oracle():
+    b = gen.make_batch(gen.WORKLOADS[1])
+    tables = upload_tables(_host_tables(b), gen.F32)
+    n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    sb = make_sparse_batch(b, tables)
+    hot.dlrm_validate_csr(sb, n_bad)
+    assert int(n_bad.item()) == 0
+    idx = b.indices.copy()
+    idx[[3, 500, 900]] = [-1, 1000, 1 << 40]
+    off = b.offsets.copy()
+    off[2, 5], off[2, 6] = off[2, 6] + 1, off[2, 5]
+    want = oracle.validate_csr(b.rows, idx, off, b.tbl_off)
+    bad = gen.Batch(b.workload, b.rows, b.lengths, off, b.tbl_off, idx, b.x, b.dR)
+    hot.dlrm_validate_csr(make_sparse_batch(bad, tables), n_bad)
+    assert int(n_bad.item()) == want and want >= 4
+
+
+@pytest.mark.parametrize("dtype", [gen.F32, gen.F16, gen.BF16])
+def test_table_init_hash_matches_host_generator_bitwise(dtype):
+    m, d = 3001, 24
+    t = torch.empty((m, d), dtype={0: torch.float32, 1: torch.float16, 2: torch.bfloat16}[dtype],
+                    device=DEV)
+    hot.dlrm_table_init_hash(t, dtype, gen.table_key(5, 3), float(gen.table_scale(m)))
+    got = table_to_numpy(t, dtype)
+    want = gen.init_table(5, 3, m, d, dtype)
+    assert np.array_equal(got.view(np.uint8), want.view(np.uint8))
+
+
+# ------------------------------------------------------------------ embedding forward
+FWD_CASES = [
+    # name, K, B, d, dtype, rows, bag, dist
+    ("tiny-shape", 8, 128, 16, gen.F32, 1000, ("uniform", 1, 4), ("uniform",)),
+    ("d4-group", 3, 70, 4, gen.F32, 50, ("uniform", 0, 3), ("uniform",)),
+    ("d4-wave", 2, 33, 4, gen.F32, 50, ("uniform", 0, 150), ("uniform",)),
+    ("d64-long-bags", 3, 67, 64, gen.F32, 5000, ("uniform", 0, 300), ("uniform",)),
+    ("d64-short-bags", 3, 67, 64, gen.F32, 5000, ("uniform", 0, 5), ("uniform",)),
+    ("d128-onehot", 5, 257, 128, gen.F32, 3000, ("fixed", 1), ("zipf", 1.05)),
+    ("d128-medium", 2, 40, 128, gen.F32, 3000, ("uniform", 0, 40), ("zipf", 1.05)),
+    ("d48-nonpow2", 2, 31, 48, gen.F32, 100, ("uniform", 0, 40), ("uniform",)),
+    ("d256-fullwave", 2, 19, 256, gen.F32, 100, ("uniform", 0, 9), ("uniform",)),
+    ("f16-d128-fixed32", 4, 200, 128, gen.F16, 20000, ("fixed", 32), ("zipf", 1.2)),
+    ("f16-d8", 2, 50, 8, gen.F16, 64, ("uniform", 0, 6), ("uniform",)),
+    ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
+    ("one-row-table", 2, 20, 16, gen.F32, 1, ("uniform", 0, 5), ("uniform",)),
+    ("single-bag", 1, 1, 32, gen.F32, 10, ("fixed", 7), ("uniform",)),
+]
+
+
+@pytest.mark.parametrize("case", FWD_CASES, ids=[c[0] for c in FWD_CASES])
+def test_emb_bag_fwd_matches_oracle(case):
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("emb_bag_fwd " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=3)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    sb = make_sparse_batch(b, tables)
+    F = K + 1
+    T = torch.full((B, F, d), 123.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+    torch.cuda.synchronize()
+    got = T.cpu().numpy()
+    want = oracle.emb_bag_fwd(host, dtype, b.indices, b.offsets, b.tbl_off)
+    assert np.all(got[:, 0, :] == 123.0)                 # row 0 belongs to the dense vector
+    scale = scale_emb_fwd(host, dtype, b.indices, b.offsets, b.tbl_off)
+    assert rel_err(got[:, 1:, :], want, scale) <= 1e-5   # the sums are fp32 whatever the storage type
+    if bag == ("fixed", 1):
+        assert np.array_equal(got[:, 1:, :].view(np.uint32), want.astype(np.float32).view(np.uint32))
+    empty = np.argwhere(b.lengths == 0)
+    for k, bb in empty:
+        assert np.all(got[bb, k + 1, :].view(np.uint32) == 0)     # +0.0 exactly
+
+
+def test_emb_bag_fwd_single_index_bags_copy_rows_bitwise_even_in_the_long_bag_kernel():
+    # mean bag length is large (wavefront-per-bag kernel) but some bags hold one index
+    lists = [[[5], list(range(40)) * 8, [], [7], [7, 7, 7]], ]
+    b = gen.batch_from_lists([64], lists, d=16)
+    host = [gen.init_table(0, 0, 64, 16, gen.F32)]
+    host[0][5, 3] = -0.0
+    tables = upload_tables(host, gen.F32)
+    out = torch.empty((5, 1, 16), dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(make_sparse_batch(b, tables), out, 16, 16)
+    got = out.cpu().numpy()
+    assert np.array_equal(got[0, 0].view(np.uint32), host[0][5].view(np.uint32))
+    assert np.array_equal(got[3, 0].view(np.uint32), host[0][7].view(np.uint32))
+    assert np.all(got[2, 0].view(np.uint32) == 0)
+    want = oracle.emb_bag_fwd(host, gen.F32, b.indices, b.offsets, b.tbl_off)
+    assert rel_err(got, want, scale_emb_fwd(host, gen.F32, b.indices, b.offsets, b.tbl_off)) <= 1e-5
+
+
+# ------------------------------------------------------------------ interaction
+INT_CASES = [(1, 2, 4), (37, 2, 16), (128, 9, 16), (300, 9, 64), (77, 27, 16), (41, 27, 128),
+             (19, 65, 128), (5, 3, 256), (1030, 5, 8)]
+
+
+@pytest.mark.parametrize("B,F,d", INT_CASES)
+def test_interact_dot_fwd_bwd_match_oracle(B, F, d):
+    _say("interact B=%d F=%d d=%d" % (B, F, d))
+    rng = np.random.default_rng(B * 1000 + F)
+    P = F * (F - 1) // 2
+    T = rng.standard_normal((B, F, d)).astype(np.float32)
+    dR = rng.standard_normal((B, d + P)).astype(np.float32)
+    Td = torch.from_numpy(T).to(DEV)
+    R = torch.full((B, d + P), -5.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_interact_dot_fwd(Td, R)
+    got = R.cpu().numpy()
+    want = oracle.interact_dot_fwd(T)
+    assert np.array_equal(got[:, :d].view(np.uint32), T[:, 0, :].view(np.uint32))   # exact copy of x
+    assert rel_err(got, want, scale_interact_fwd(T)) <= 1e-5
+    dT = torch.full((B, F, d), -5.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_interact_dot_bwd(Td, torch.from_numpy(dR).to(DEV), dT)
+    assert rel_err(dT.cpu().numpy(), oracle.interact_dot_bwd(T, dR), scale_interact_bwd(T, dR)) <= 1e-5
+
+
+def test_place_dense_is_an_exact_copy():
+    rng = np.random.default_rng(1)
+    B, F, d = 333, 9, 64
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    T = torch.full((B, F, d), 9.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_place_dense(torch.from_numpy(x).to(DEV), T)
+    got = T.cpu().numpy()
+    assert np.array_equal(got[:, 0, :].view(np.uint32), x.view(np.uint32))
+    assert np.all(got[:, 1:, :] == 9.0)
+
+
+# ------------------------------------------------------------------ grouping + backward
+BWD_CASES = [
+    ("tiny-shape", 8, 128, 16, gen.F32, 1000, ("uniform", 1, 4), ("uniform",)),
+    ("multi-tile-ragged", 3, 700, 64, gen.F32, 100000, ("uniform", 0, 40), ("uniform",)),
+    ("hot-rows", 2, 600, 32, gen.F32, 50000, ("fixed", 16), ("zipf", 1.4)),
+    ("onehot-zipf", 5, 2048, 16, gen.F32, 3000000, ("fixed", 1), ("zipf", 1.05)),
+    ("d128-onehot", 3, 999, 128, gen.F32, 70000, ("fixed", 1), ("zipf", 1.05)),
+    ("d4", 2, 100, 4, gen.F32, 37, ("uniform", 0, 6), ("uniform",)),
+    ("d48-nonpow2", 2, 64, 48, gen.F32, 300, ("uniform", 0, 10), ("uniform",)),
+    ("f16-d128-fixed32", 4, 300, 128, gen.F16, 20000, ("fixed", 32), ("zipf", 1.2)),
+    ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
+    ("one-row-table", 2, 5000, 16, gen.F32, 1, ("fixed", 1), ("uniform",)),
+]
+
+
+def _run_export(sb, nnz, K):
+    ws = hot.alloc_workspace(sb)
+    n = max(nnz, 1)
+    uniq = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    seg = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    sbag = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+    nu = torch.full((K,), -1, dtype=torch.int64, device=DEV)
+    hot.dlrm_emb_bag_bwd_export_groups(sb, ws, uniq, seg, sbag, nu)
+    torch.cuda.synchronize()
+    return uniq.cpu().numpy(), seg.cpu().numpy(), sbag.cpu().numpy(), nu.cpu().numpy()
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=[c[0] for c in BWD_CASES])
+def test_grouping_is_bit_exact(case):
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("export_groups " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=4)
+    b = gen.make_batch(w)
+    tables = [torch.zeros((int(m), d), dtype=torch.float32, device=DEV) for m in b.rows[:1]] * K
+    sb = hot.SparseBatch(tables, gen.F32, torch.from_numpy(b.indices).to(DEV),
+                         torch.from_numpy(b.offsets).to(DEV), torch.from_numpy(b.tbl_off).to(DEV),
+                         b.nnz, max_rows=int(b.rows.max()))
+    uniq, seg, sbag, nu = _run_export(sb, b.nnz, K)
+    want = oracle.group_rows(b.indices, b.offsets, b.tbl_off)
+    for k in range(K):
+        a0, a1 = int(b.tbl_off[k]), int(b.tbl_off[k + 1])
+        wu, wseg, wpos, wbag = want[k]
+        assert int(nu[k]) == len(wu)
+        assert np.array_equal(uniq[a0:a0 + len(wu)], wu)
+        assert np.array_equal(seg[a0:a0 + len(wu)], wseg)
+        assert np.array_equal(sbag[a0:a1], wbag)
+
+
+@pytest.mark.parametrize("algo", ["sort", "atomic"])
+@pytest.mark.parametrize("case", BWD_CASES, ids=[c[0] for c in BWD_CASES])
+def test_emb_bag_bwd_sgd_matches_oracle(case, algo):
+    name, K, B, d, dtype, rows, bag, dist = case
+    if algo == "atomic" and dtype != gen.F32:
+        pytest.skip("atomic path is defined for fp32 tables only")
+    _say("emb_bag_bwd_sgd %s %s" % (name, algo))
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=4)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    before = [t.clone() for t in tables]
+    sb = make_sparse_batch(b, tables)
+    F = K + 1
+    dS = b.dS()
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+    ws = hot.alloc_workspace(sb)
+    lr = float(np.float32(w.lr))
+    code = hot.BWD_SORT if algo == "sort" else hot.BWD_ATOMIC
+    hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=code, dS_offset=d)
+    torch.cuda.synchronize()
+    ref = [t.copy() for t in host]
+    uniq, grad = oracle.emb_bag_bwd_sgd(ref, dtype, b.indices, b.offsets, b.tbl_off, dS,
+                                        float(np.float32(lr)), want_grad=True)
+    scale = scale_sgd(host, dtype, b.indices, b.offsets, b.tbl_off, dS, float(np.float32(lr)))
+    for k in range(K):
+        got = table_to_numpy(tables[k], dtype)
+        # rows nobody looked up keep their bits
+        mask = np.ones(int(b.rows[k]), dtype=bool)
+        mask[uniq[k]] = False
+        assert np.array_equal(got[mask].view(np.uint8), host[k][mask].view(np.uint8))
+        if len(uniq[k]) == 0:
+            continue
+        g_rows, r_rows, h_rows = got[uniq[k]], ref[k][uniq[k]], host[k][uniq[k]]
+        assert rel_err(widen_host(g_rows, dtype), widen_host(r_rows, dtype), scale[k][uniq[k]]) <= TOL[dtype]
+        if dtype == gen.F32:
+            # the applied step W_before - W_after against lr*g, allowing the rounding of W:
+            # once per row for the sort path, once per occurrence for the atomic path
+            step_got = h_rows.astype(np.float64) - g_rows.astype(np.float64)
+            ulp = max(np.abs(h_rows).max(), np.abs(g_rows).max()) * 2.0 ** -23
+            n_round = 2 if algo == "sort" else 2 + int(np.bincount(b.indices_of(k)).max())
+            bound = 1e-5 * np.abs(lr * grad[k]).max() + n_round * ulp
+            assert np.max(np.abs(step_got - lr * grad[k])) <= bound
+        else:
+            # low-precision tables: fp32 arithmetic + one rounding lands within one unit in the
+            # last place of the fp64-then-rounded reference
+            a, r = widen_host(g_rows, dtype), widen_host(r_rows, dtype)
+            mant = 10 if dtype == gen.F16 else 7
+            emin = -14 if dtype == gen.F16 else -126
+            expo = np.maximum(np.floor(np.log2(np.maximum(np.abs(r), 2.0 ** emin))), emin)
+            assert np.all(np.abs(a - r) <= 2.0 ** (expo - mant))
+    if algo == "sort":
+        # bitwise reproducible: same inputs, same bits
+        tables2 = [t.clone() for t in before]
+        sb2 = make_sparse_batch(b, tables2)
+        hot.dlrm_emb_bag_bwd_sgd(sb2, dT, F * d, d, lr, ws, algo=code, dS_offset=d)
+        torch.cuda.synchronize()
+        for k in range(K):
+            assert torch.equal(tables2[k].view(torch.uint8), tables[k].view(torch.uint8))
+
+
+def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
+    lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
+    b = gen.batch_from_lists([8, 8, 8], lists, d=8)
+    host = [gen.init_table(1, k, 8, 8, gen.F32) for k in range(3)]
+    for algo in (hot.BWD_SORT, hot.BWD_ATOMIC):
+        tables = upload_tables(host, gen.F32)
+        sb = make_sparse_batch(b, tables)
+        dS = torch.from_numpy(b.dS()).to(DEV)
+        ws = hot.alloc_workspace(sb)
+        hot.dlrm_emb_bag_bwd_sgd(sb, dS, 3 * 8, 8, 0.0, ws, algo=algo)
+        for k in range(3):
+            assert np.array_equal(tables[k].cpu().numpy().view(np.uint32), host[k].view(np.uint32))
+        hot.dlrm_emb_bag_bwd_sgd(sb, dS, 3 * 8, 8, 0.5, ws, algo=algo)
+        ref = [t.copy() for t in host]
+        oracle.emb_bag_bwd_sgd(ref, gen.F32, b.indices, b.offsets, b.tbl_off, b.dS(), 0.5)
+        scale = scale_sgd(host, gen.F32, b.indices, b.offsets, b.tbl_off, b.dS(), 0.5)
+        for k in range(3):
+            assert rel_err(tables[k].cpu().numpy(), ref[k], scale[k]) <= 1e-5
+        assert np.array_equal(tables[1].cpu().numpy(), host[1])
+    uniq, seg, sbag, nu = _run_export(sb, b.nnz, 3)
+    assert nu.tolist() == [2, 0, 1]
+
+
+def test_empty_batch_is_a_no_op():
+    lists = [[[], []], [[], []]]
+    b = gen.batch_from_lists([4, 4], lists, d=4)
+    host = [gen.init_table(1, k, 4, 4, gen.F32) for k in range(2)]
+    tables = upload_tables(host, gen.F32)
+    sb = make_sparse_batch(b, tables)
+    out = torch.full((2, 2, 4), 3.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(sb, out, 8, 4)
+    assert np.all(out.cpu().numpy() == 0.0)
+    ws = hot.alloc_workspace(sb)
+    hot.dlrm_emb_bag_bwd_sgd(sb, out, 8, 4, 0.1, ws, algo=hot.BWD_SORT)
+    hot.dlrm_emb_bag_bwd_sgd(sb, out, 8, 4, 0.1, ws, algo=hot.BWD_ATOMIC)
+    for k in range(2):
+        assert np.array_equal(tables[k].cpu().numpy(), host[k])
