@@ -23,10 +23,15 @@ _TORCH_DT = {gen.F32: torch.float32, gen.F16: torch.float16, gen.BF16: torch.bfl
 TOL = {gen.F32: 1e-5, gen.F16: 1e-2, gen.BF16: 1e-2}
 
 
-def rel_err(got: np.ndarray, ref: np.ndarray, scale: np.ndarray) -> float:
+# Below the smallest normal number of the storage type a rounding is an absolute, not a
+# relative, perturbation: the scale of a stored low-precision value is floored there.
+SCALE_FLOOR = {gen.F32: 0.0, gen.F16: 2.0 ** -14, gen.BF16: 2.0 ** -126}
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray, scale: np.ndarray, floor: float = 0.0) -> float:
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
-    scale = np.asarray(scale, dtype=np.float64)
+    scale = np.maximum(np.asarray(scale, dtype=np.float64), floor)
     assert got.shape == ref.shape == scale.shape
     if ref.size == 0:
         return 0.0

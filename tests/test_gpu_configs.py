@@ -14,7 +14,7 @@ import paper_1906_00091_amd as hot
 from oracle import oracle
 from workloads import gen
 
-from hotpath_util import (DEV, TOL, Compact, device_hash_tables, make_sparse_batch, rel_err,
+from hotpath_util import (DEV, SCALE_FLOOR, TOL, Compact, device_hash_tables, make_sparse_batch, rel_err,
                           scale_emb_fwd, scale_interact_bwd, scale_interact_fwd, scale_sgd,
                           table_to_numpy, widen_host)
 
@@ -107,7 +107,7 @@ def _check_config(cfg_id, algo=hot.BWD_AUTO, sample_untouched=20000):
     worst = 0.0
     for k in range(K):
         worst = max(worst, rel_err(widen_host(got_rows[k], w.dtype), widen_host(ref_tables[k], w.dtype),
-                                   scale[k]))
+                                   scale[k], SCALE_FLOOR[w.dtype]))
         changed = np.any(got_rows[k] != comp.tables[k], axis=1)
         assert changed.mean() > 0.99                     # touched rows did move
     _say("tables after SGD rel err %.2e" % worst)

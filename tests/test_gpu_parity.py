@@ -10,7 +10,7 @@ import paper_1906_00091_amd as hot
 from oracle import oracle
 from workloads import gen
 
-from hotpath_util import (DEV, TOL, make_sparse_batch, rel_err, scale_emb_fwd, scale_interact_bwd,
+from hotpath_util import (DEV, SCALE_FLOOR, TOL, make_sparse_batch, rel_err, scale_emb_fwd, scale_interact_bwd,
                           scale_interact_fwd, scale_sgd, table_to_numpy, upload_tables, widen_host)
 
 pytestmark = pytest.mark.gpu
@@ -249,7 +249,8 @@ def test_emb_bag_bwd_sgd_matches_oracle(case, algo):
         if len(uniq[k]) == 0:
             continue
         g_rows, r_rows, h_rows = got[uniq[k]], ref[k][uniq[k]], host[k][uniq[k]]
-        assert rel_err(widen_host(g_rows, dtype), widen_host(r_rows, dtype), scale[k][uniq[k]]) <= TOL[dtype]
+        assert rel_err(widen_host(g_rows, dtype), widen_host(r_rows, dtype), scale[k][uniq[k]],
+                       SCALE_FLOOR[dtype]) <= TOL[dtype]
         if dtype == gen.F32:
             # the applied step W_before - W_after against lr*g, allowing the rounding of W:
             # once per row for the sort path, once per occurrence for the atomic path
