@@ -2,56 +2,85 @@
 // SGD of Sec. 5.1):  for every distinct row r looked up in table k,
 //   g = sum_{p : idx_k[p] = r} dS[bag(p), k, :],   W_k[r,:] <- W_k[r,:] - lr * g.
 //
-// SORT path (deterministic, any table dtype):
-//   1. expand      : (row, bag) pair for every lookup position
-//   2. radix sort  : least-significant-digit passes over the row id, per table
-//                    (tiles never straddle two tables, so every table is sorted
-//                    inside its own slice); each pass = tile histograms, a scan
-//                    per table, and a stable scatter staged through LDS
-//   3. run heads   : positions where the row changes -> one segment per distinct row
-//   4. reduce+SGD  : a lane group per segment sums its dS rows in ascending
-//                    position order (fp32) and read-modify-writes the table row once
-// ATOMIC path (fp32 tables): a lane group per bag adds -lr*dS[b,k,:] to every row
-// of the bag with hardware fp32 atomics; no workspace, one launch.
+// SORT path (deterministic, any table dtype) -- a most-significant-digit partition
+// followed by a bucket-local sort, so that one workgroup owns all lookups of a row:
+//   1. bucket_hist    : per 4096-position tile, histogram of the top digit of the row id
+//                       (tiles never straddle two tables)
+//   2. scan           : (digit, tile) counts -> destination offsets inside the table's slice
+//                       (folded into step 3 when the batch has few tiles)
+//   3. bucket_scatter : derives the bag of every position from the offsets, then moves the
+//                       (row, bag) pairs to their bucket, stably, staged through LDS
+//   4. bucket_reduce  : one workgroup per (table, top digit): stable LSD radix sort of the
+//                       bucket on the remaining low bits (in LDS when it fits), run heads,
+//                       then a lane group per run sums its dS rows in ascending position
+//                       order (fp32) and read-modify-writes the table row once.  Runs longer
+//                       than 32 are summed by the whole workgroup; runs longer than 2048 are
+//                       queued for step 5.
+//   5. huge_runs      : 1024-entry chunks of the queued runs are summed by separate
+//                       workgroups; the last chunk to finish adds the partials in chunk order
+//                       and updates the row (no waiting on other workgroups).
+// ATOMIC path (fp32 tables): a lane group per bag adds -lr*dS[b,k,:] to every row of the bag
+// with hardware fp32 atomics; no workspace, one launch.  Measured 3.8x slower than SORT on the
+// 8 x 1M x 64 multi-hot workload, so AUTO always takes SORT.
 #include "common.h"
 
 namespace dlrm {
 
-constexpr int kTileThreads = 256;
-constexpr int kItems = 16;                       // items per thread in a sort tile
-constexpr int kTile = kTileThreads * kItems;     // 4096 positions per tile
-constexpr int kMaxDigitBits = 8;
-constexpr int kMaxBuckets = 1 << kMaxDigitBits;
+constexpr int kThreads = 256;
+constexpr int kNW = kThreads / DLRM_WAVE;       // wavefronts per workgroup
+constexpr int kItems = 16;                      // positions per thread in a partition tile
+constexpr int kTile = kThreads * kItems;        // 4096 positions per tile
+constexpr int kMaxTopBits = 8;
+constexpr int kMaxBuckets = 1 << kMaxTopBits;
+constexpr int kBktItems = 8;                    // positions per thread in a bucket-sort tile
+constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size are sorted in LDS
+constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
+constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
+constexpr int kHugeChunk = 1024;
+constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatter below this
 
 // ---------------------------------------------------------------------------
 // Workspace layout (all offsets 256-byte aligned)
 struct WsLayout {
   size_t keys[2], vals[2];   // uint32[nnz] ping-pong: row ids / bag ids
-  size_t tile_prefix;        // int32[K+1]: first tile of every table
-  size_t hist;               // uint32[kMaxBuckets * nt_max]: per-tile digit counts, then offsets
-  size_t tile_heads;         // uint32[nt_max + 1]: run heads per tile, then exclusive prefix
-  size_t seg_start;          // uint32[nnz + 1]: position of every run head (+ sentinel)
-  size_t seg_tbl;            // uint32[nnz]: table of every run
-  size_t n_seg;              // uint32[4]: total number of runs
+  size_t hist;               // uint32[kMaxBuckets * nt_max]: per-tile digit counts / offsets
+  size_t bucket_start;       // uint32[K * kMaxBuckets + 1]
+  size_t tile_heads;         // uint32[nt_max + 1]   (export only)
+  size_t seg_start;          // uint32[nnz + 1]      (export only)
+  size_t seg_tbl;            // uint32[nnz]          (export only)
+  size_t n_seg;              // uint32[4]            (export only)
+  size_t huge_ctr;           // uint64[2]: packed (runs << 32 | chunks) counter
+  size_t huge_runs;          // HugeRun[nnz / kHugeRun + 1]
+  size_t huge_part;          // float[(nnz / kHugeChunk + max_runs) * d]
   size_t total;
   int64_t nt_max;            // upper bound on the number of tiles
+  int64_t max_huge;          // upper bound on the number of queued runs
+};
+
+struct HugeRun {
+  uint32_t k, row, start, len;   // start: global position of the run's first sorted entry
+  uint32_t chunk_base, nchunks, done, src;
 };
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-static WsLayout ws_layout(int32_t K, int64_t nnz) {
+static WsLayout ws_layout(int32_t K, int32_t d, int64_t nnz) {
   WsLayout L;
   size_t o = 0;
   const size_t n = (size_t)(nnz > 0 ? nnz : 1);
   L.nt_max = nnz / kTile + K;
+  L.max_huge = nnz / kHugeRun + 1;
   for (int i = 0; i < 2; ++i) { L.keys[i] = o; o = align256(o + n * 4); }
   for (int i = 0; i < 2; ++i) { L.vals[i] = o; o = align256(o + n * 4); }
-  L.tile_prefix = o; o = align256(o + (size_t)(K + 1) * 4);
-  L.hist = o;        o = align256(o + (size_t)kMaxBuckets * (size_t)L.nt_max * 4);
-  L.tile_heads = o;  o = align256(o + (size_t)(L.nt_max + 1) * 4);
-  L.seg_start = o;   o = align256(o + (n + 1) * 4);
-  L.seg_tbl = o;     o = align256(o + n * 4);
-  L.n_seg = o;       o = align256(o + 16);
+  L.hist = o;         o = align256(o + (size_t)kMaxBuckets * (size_t)L.nt_max * 4);
+  L.bucket_start = o; o = align256(o + ((size_t)K * kMaxBuckets + 1) * 4);
+  L.tile_heads = o;   o = align256(o + (size_t)(L.nt_max + 1) * 4);
+  L.seg_start = o;    o = align256(o + (n + 1) * 4);
+  L.seg_tbl = o;      o = align256(o + n * 4);
+  L.n_seg = o;        o = align256(o + 16);
+  L.huge_ctr = o;     o = align256(o + 16);
+  L.huge_runs = o;    o = align256(o + (size_t)L.max_huge * sizeof(HugeRun));
+  L.huge_part = o;    o = align256(o + ((size_t)(nnz / kHugeChunk) + (size_t)L.max_huge) * (size_t)d * 4);
   L.total = o;
   return L;
 }
@@ -61,208 +90,324 @@ struct GroupArgs {            // everything the grouping kernels need
   const int64_t* indices;
   const int64_t* offsets;
   const int64_t* tbl_off;
+  const int64_t* rows;
   int32_t K, B;
   int32_t nt_max;
+  int32_t top_bits;           // bits of the partition digit (0..kMaxTopBits)
+  int32_t fused_scan;         // 1: the scatter derives its offsets from the raw tile counts
   uint32_t* keys[2];
   uint32_t* vals[2];
-  int32_t* tile_prefix;
   uint32_t* hist;
+  uint32_t* bucket_start;
   uint32_t* tile_heads;
   uint32_t* seg_start;
   uint32_t* seg_tbl;
   uint32_t* n_seg;
+  unsigned long long* huge_ctr;
+  HugeRun* huge_runs;
+  float* huge_part;
 };
 
-// Which table and which positions a tile covers.  Wave-uniform.
+// bits needed to index m rows; the partition digit of table k is row >> top_shift(k)
+__device__ inline int key_bits(int64_t m) { return m <= 1 ? 0 : 64 - __clzll((unsigned long long)(m - 1)); }
+__device__ inline int top_shift(const GroupArgs& a, int k) {
+  const int s = key_bits(a.rows[k]) - a.top_bits;
+  return s > 0 ? s : 0;
+}
+
+// Which table and which positions a tile covers.  Workgroup-uniform.
 struct TileInfo {
   int k;
+  int t;           // tile index inside the table
+  int t0;          // global index of the table's first tile
+  int nt;          // tiles of the table
   int64_t start;   // global position of the tile's first item
   int count;       // items in the tile (1..kTile)
   int64_t tbl_start;
 };
 
-__device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti) {
-  if (tile >= a.tile_prefix[a.K]) return false;
-  int lo = 0, hi = a.K;  // tile_prefix[lo] <= tile < tile_prefix[hi]
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.tile_prefix[mid] <= tile) lo = mid; else hi = mid;
-  }
-  // tables without lookups own no tiles: tile_prefix[lo] == tile_prefix[lo+1] is skipped by
-  // the search because it keeps the LAST k with tile_prefix[k] <= tile
-  ti.k = lo;
-  ti.tbl_start = a.tbl_off[lo];
-  const int64_t tbl_end = a.tbl_off[lo + 1];
-  ti.start = ti.tbl_start + (int64_t)(tile - a.tile_prefix[lo]) * kTile;
-  const int64_t rem = tbl_end - ti.start;
-  ti.count = (int)(rem < kTile ? rem : kTile);
-  return ti.count > 0;
-}
-
-// --- 0. tile map -------------------------------------------------------------
-__global__ __launch_bounds__(256) void tile_map_kernel(GroupArgs a) {
-  __shared__ uint32_t smem[256 / DLRM_WAVE + 1];
+// Every workgroup rebuilds the tile map from tbl_off (K is small): tables own
+// ceil(nnz_k / kTile) consecutive tiles.  All threads must call this (it synchronises).
+__device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti, uint32_t* smem) {
+  __shared__ int res[4];
+  if (threadIdx.x == 0) res[0] = -1;
   uint32_t carry = 0;
-  if (threadIdx.x == 0) a.tile_prefix[0] = 0;
-  for (int k0 = 0; k0 < a.K; k0 += 256) {
+  for (int k0 = 0; k0 < a.K; k0 += kThreads) {
     const int k = k0 + threadIdx.x;
     uint32_t nt = 0;
     if (k < a.K) nt = (uint32_t)((a.tbl_off[k + 1] - a.tbl_off[k] + kTile - 1) / kTile);
     uint32_t total;
-    const uint32_t ex = block_exclusive_scan<256>(nt, smem, &total);
-    if (k < a.K) a.tile_prefix[k + 1] = (int32_t)(carry + ex + nt);
+    const uint32_t first = carry + block_exclusive_scan<kThreads>(nt, smem, &total);
+    if (k < a.K && (uint32_t)tile >= first && (uint32_t)tile < first + nt) {
+      res[0] = k;
+      res[1] = (int)first;
+      res[2] = (int)nt;
+    }
     carry += total;
+    if ((uint32_t)tile < carry) break;  // uniform
   }
+  __syncthreads();
+  if (res[0] < 0) return false;
+  ti.k = res[0];
+  ti.t0 = res[1];
+  ti.nt = res[2];
+  ti.t = tile - ti.t0;
+  ti.tbl_start = a.tbl_off[ti.k];
+  ti.start = ti.tbl_start + (int64_t)ti.t * kTile;
+  const int64_t rem = a.tbl_off[ti.k + 1] - ti.start;
+  ti.count = (int)(rem < kTile ? rem : kTile);
+  return true;
 }
 
-// --- 1. expand ----------------------------------------------------------------
-// 2^lg lanes per bag walk the bag's positions; writes the 32-bit row id and the bag id.
-__global__ __launch_bounds__(256) void expand_kernel(GroupArgs a, int lg) {
-  const int64_t gid = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> lg;
-  const int sub = threadIdx.x & ((1 << lg) - 1);
-  if (gid >= (int64_t)a.K * a.B) return;
-  const int k = (int)(gid / a.B), b = (int)(gid - (int64_t)k * a.B);
-  const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
-  const int64_t base = a.tbl_off[k];
-  const int64_t p1 = base + off[b + 1];
-  for (int64_t p = base + off[b] + sub; p < p1; p += (1 << lg)) {
-    a.keys[0][p] = (uint32_t)a.indices[p];
-    a.vals[0][p] = (uint32_t)b;
-  }
-}
-
-// --- 2a. per-tile digit histogram ----------------------------------------------
-__global__ __launch_bounds__(kTileThreads) void sort_hist_kernel(GroupArgs a, int src, int shift,
-                                                                  int bits) {
+// --- 1. per-tile histogram of the partition digit ----------------------------------
+__global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
   __shared__ uint32_t h[kMaxBuckets];
+  __shared__ uint32_t smem[kNW + 1];
   TileInfo ti;
-  if (!find_tile(a, blockIdx.x, ti)) return;
-  const int nb = 1 << bits;
-  for (int i = threadIdx.x; i < nb; i += kTileThreads) h[i] = 0;
+  if (!find_tile(a, blockIdx.x, ti, smem)) return;
+  const int nb = 1 << a.top_bits;
+  for (int i = threadIdx.x; i < nb; i += kThreads) h[i] = 0;
   __syncthreads();
-  const uint32_t* keys = a.keys[src] + ti.start;
+  const int64_t* idx = a.indices + ti.start;
+  const int shift = top_shift(a, ti.k);
   const uint32_t mask = (uint32_t)nb - 1;
-  for (int i = threadIdx.x; i < ti.count; i += kTileThreads)
-    atomicAdd(&h[(keys[i] >> shift) & mask], 1u);
+  for (int i = threadIdx.x; i < ti.count; i += kThreads)
+    atomicAdd(&h[((uint32_t)idx[i] >> shift) & mask], 1u);
   __syncthreads();
-  for (int i = threadIdx.x; i < nb; i += kTileThreads)
-    a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
+  for (int i = threadIdx.x; i < nb; i += kThreads) a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) a.huge_ctr[0] = 0ull;  // consumed two launches later
 }
 
-// --- 2b. per-table scan: counts -> destination offsets ---------------------------
+// --- 2. per-table scan (large batches only): counts -> destination offsets ------------
 // One workgroup per table walks (digit, tile) in digit-major order with a running carry
 // that starts at the table's slice, so every table is scattered inside its own slice.
-__global__ __launch_bounds__(1024) void sort_scan_kernel(GroupArgs a, int bits) {
+__global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
   __shared__ uint32_t smem[1024 / DLRM_WAVE + 1];
   const int k = blockIdx.x;
-  const int t0 = a.tile_prefix[k], nt = a.tile_prefix[k + 1] - t0;
-  if (nt <= 0) return;
-  const int64_t n = (int64_t)nt << bits;
+  // first tile of table k = tiles of all earlier tables
+  uint32_t t0 = 0;
+  for (int j = 0; j < k; ++j) t0 += (uint32_t)((a.tbl_off[j + 1] - a.tbl_off[j] + kTile - 1) / kTile);
+  const int nt = (int)((a.tbl_off[k + 1] - a.tbl_off[k] + kTile - 1) / kTile);
+  const int nb = 1 << a.top_bits;
   uint32_t carry = (uint32_t)a.tbl_off[k];
+  if (nt <= 0) {
+    for (int i = threadIdx.x; i < nb; i += 1024) a.bucket_start[(size_t)k * nb + i] = carry;
+    return;
+  }
+  const int64_t n = (int64_t)nt * nb;
   for (int64_t e0 = 0; e0 < n; e0 += 1024) {
     const int64_t e = e0 + threadIdx.x;
     uint32_t v = 0;
     size_t addr = 0;
+    int digit = 0, t = 0;
     if (e < n) {
-      const int digit = (int)(e / nt), t = (int)(e - (int64_t)digit * nt);
+      digit = (int)(e / nt);
+      t = (int)(e - (int64_t)digit * nt);
       addr = (size_t)digit * a.nt_max + t0 + t;
       v = a.hist[addr];
     }
     uint32_t total;
     const uint32_t ex = block_exclusive_scan<1024>(v, smem, &total);
-    if (e < n) a.hist[addr] = carry + ex;
+    if (e < n) {
+      a.hist[addr] = carry + ex;
+      if (t == 0) a.bucket_start[(size_t)k * nb + digit] = carry + ex;
+    }
     carry += total;
   }
 }
 
-// --- 2c. stable scatter ---------------------------------------------------------
-// Wave w of the workgroup owns the contiguous positions [w*64*kItems, (w+1)*64*kItems)
-// of the tile, item j of lane l being position w*64*kItems + j*64 + l.  Ranks inside a
-// wave come from ballot matching; per-wave digit counters in LDS give the order across
-// waves.  Items are first placed in LDS in sorted order so that the global writes of
-// one digit are contiguous.
-__global__ __launch_bounds__(kTileThreads) void sort_scatter_kernel(GroupArgs a, int src, int shift,
-                                                                     int bits) {
-  constexpr int NW = kTileThreads / DLRM_WAVE;
-  __shared__ uint32_t wcnt[NW][kMaxBuckets];
-  __shared__ uint32_t gofs[kMaxBuckets];
-  __shared__ uint32_t skey[kTile];
-  __shared__ uint32_t sval[kTile];
-  __shared__ uint32_t scan_smem[kTileThreads / DLRM_WAVE + 1];
-  TileInfo ti;
-  if (!find_tile(a, blockIdx.x, ti)) return;
-  const int nb = 1 << bits;
-  const uint32_t mask = (uint32_t)nb - 1;
+// --- shared by steps 3 and 4: stable ranking of a tile by a digit ---------------------
+// Wave w of the workgroup owns the contiguous positions [w*64*ITEMS, (w+1)*64*ITEMS) of
+// the tile, item j of lane l being position w*64*ITEMS + j*64 + l.  Ranks inside a wave
+// come from ballot matching; per-wave digit counters in LDS give the order across waves.
+// On return rnk[j] is the item's rank among the items of its wave with the same digit that
+// precede it, and wcnt[w][digit] the wave's count.  wcnt must be zero on entry.
+template <int ITEMS>
+__device__ inline void rank_items(const uint32_t* dg, const bool* ok, int bits,
+                                  uint32_t (*wcnt)[kMaxBuckets], uint32_t* rnk) {
   const int lane = lane_id(), w = wave_id();
-  for (int i = threadIdx.x; i < NW * kMaxBuckets; i += kTileThreads) (&wcnt[0][0])[i] = 0;
-  __syncthreads();
-
-  const uint32_t* kin = a.keys[src] + ti.start;
-  const uint32_t* vin = a.vals[src] + ti.start;
-  uint32_t key[kItems], val[kItems], rnk[kItems];
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
-    const bool ok = li < ti.count;
-    key[j] = ok ? kin[li] : 0xFFFFFFFFu;
-    val[j] = ok ? vin[li] : 0u;
-  }
   const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
-    const bool ok = li < ti.count;
-    const uint32_t dg = (key[j] >> shift) & mask;
-    unsigned long long m = __ballot(ok);
+  for (int j = 0; j < ITEMS; ++j) {
+    unsigned long long m = __ballot(ok[j]);
     for (int bit = 0; bit < bits; ++bit) {
-      const bool one = (dg >> bit) & 1u;
+      const bool one = (dg[j] >> bit) & 1u;
       const unsigned long long bal = __ballot(one);
       m &= one ? bal : ~bal;
     }
     // m: valid lanes of this wave holding the same digit in item j (meaningful where ok)
     uint32_t prev = 0;
-    const int leader = ok ? (__ffsll((long long)m) - 1) : lane;
-    if (ok && lane == leader) prev = atomicAdd(&wcnt[w][dg], (uint32_t)__popcll(m));
+    const int leader = ok[j] ? (__ffsll((long long)m) - 1) : lane;
+    if (ok[j] && lane == leader) prev = atomicAdd(&wcnt[w][dg[j]], (uint32_t)__popcll(m));
     prev = __shfl(prev, leader, DLRM_WAVE);
     rnk[j] = prev + (uint32_t)__popcll(m & lt);
   }
-  __syncthreads();
-  // per digit: totals, exclusive prefix over waves, exclusive prefix over digits
-  {
-    uint32_t c[NW], tot = 0;
-    const int dg = threadIdx.x;  // kTileThreads >= kMaxBuckets
+}
+
+// After rank_items + a barrier: turns wcnt[w][digit] into the tile-local sorted position of
+// wave w's first item with that digit, and returns (for thread == digit) the tile-local
+// offset of the digit and its count.  All threads must call it.
+__device__ inline void digit_offsets(int nb, uint32_t (*wcnt)[kMaxBuckets], uint32_t* scan_smem,
+                                     uint32_t* lofs_out, uint32_t* tot_out) {
+  uint32_t c[kNW], tot = 0;
+  const int dg = threadIdx.x;  // kThreads >= kMaxBuckets
 #pragma unroll
-    for (int i = 0; i < NW; ++i) {
-      c[i] = dg < nb ? wcnt[i][dg] : 0u;
-      tot += c[i];
-    }
-    uint32_t total_all;
-    const uint32_t lofs = block_exclusive_scan<kTileThreads>(tot, scan_smem, &total_all);
-    if (dg < nb) {
-      uint32_t run = lofs;
+  for (int i = 0; i < kNW; ++i) {
+    c[i] = dg < nb ? wcnt[i][dg] : 0u;
+    tot += c[i];
+  }
+  uint32_t total_all;
+  const uint32_t lofs = block_exclusive_scan<kThreads>(tot, scan_smem, &total_all);
+  if (dg < nb) {
+    uint32_t run = lofs;
 #pragma unroll
-      for (int i = 0; i < NW; ++i) {
-        wcnt[i][dg] = run;  // local sorted position of wave i's first item with this digit
-        run += c[i];
-      }
-      gofs[dg] = a.hist[(size_t)dg * a.nt_max + blockIdx.x] - lofs;
+    for (int i = 0; i < kNW; ++i) {
+      wcnt[i][dg] = run;
+      run += c[i];
     }
   }
-  __syncthreads();
+  *lofs_out = lofs;
+  *tot_out = tot;
+}
+
+// --- 3. stable scatter into buckets ---------------------------------------------------
+__global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
+  __shared__ uint32_t wcnt[kNW][kMaxBuckets];
+  __shared__ uint32_t gofs[kMaxBuckets];
+  __shared__ uint32_t skey[kTile];
+  __shared__ uint32_t sval[kTile];
+  __shared__ uint32_t smem[kNW + 1];
+  __shared__ int sflag[2];
+  TileInfo ti;
+  if (!find_tile(a, blockIdx.x, ti, smem)) return;
+  const int nb = 1 << a.top_bits;
+  const uint32_t mask = (uint32_t)nb - 1;
+  const int lane = lane_id(), w = wave_id();
+  const int tid = threadIdx.x;
+
+  // ---- requested first so that their latency hides behind the bag search: the tile's row ids
+  // (wave-striped) and, for small batches, this digit's counts in all tiles of the table
+  const int64_t* kin = a.indices + ti.start;
+  const int shift = top_shift(a, ti.k);
+  uint32_t key[kItems], val[kItems], dg[kItems], rnk[kItems];
+  bool ok[kItems];
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
-    if (li < ti.count) {
-      const uint32_t dg = (key[j] >> shift) & mask;
-      const uint32_t lp = wcnt[w][dg] + rnk[j];
+    ok[j] = li < ti.count;
+    key[j] = ok[j] ? (uint32_t)kin[li] : 0xFFFFFFFFu;
+    dg[j] = (key[j] >> shift) & mask;
+  }
+  uint32_t goff = 0, before = 0, total = 0;
+  if (a.fused_scan) {
+    if (tid < nb) {
+      const uint32_t* hrow = a.hist + (size_t)tid * a.nt_max + ti.t0;
+      int t = 0;
+      for (; t + 8 <= ti.nt; t += 8) {
+        uint32_t c[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) c[q] = hrow[t + q];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          total += c[q];
+          before += t + q < ti.t ? c[q] : 0u;
+        }
+      }
+      for (; t < ti.nt; ++t) {
+        const uint32_t c = hrow[t];
+        total += c;
+        before += t < ti.t ? c : 0u;
+      }
+    }
+  } else if (tid < nb) {
+    goff = a.hist[(size_t)tid * a.nt_max + blockIdx.x];
+  }
+
+  // ---- bag of every position of the tile, from the offsets
+  // b0 = the bag holding the tile's first position: last b with off[b] <= P0.
+  const int64_t* off = a.offsets + (int64_t)ti.k * (a.B + 1);
+  const int64_t P0 = ti.start - ti.tbl_start;
+  int lo = 0, hi = a.B;  // off[lo] <= P0 (off[0] = 0); the answer lies in [lo, hi)
+  while (hi - lo > 1) {   // 256-ary search, uniform
+    const int step = (hi - lo + kThreads - 1) / kThreads;
+    const int q = lo + (tid + 1) * step;
+    const int pred = (q < hi && off[q] <= P0) ? 1 : 0;
+    const int cnt = __syncthreads_count(pred);   // offsets are monotone: the first cnt probes pass
+    const int nlo = lo + cnt * step;
+    const int nhi = nlo + step < hi ? nlo + step : hi;
+    lo = nlo;
+    hi = nhi;
+  }
+  const int b0 = lo;
+  for (int i = tid; i < kTile; i += kThreads) skey[i] = 0;  // skey doubles as the bag-start counters
+  for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&wcnt[0][0])[i] = 0;
+  __syncthreads();
+  for (int base = b0 + 1;; base += kThreads) {  // bags that start inside the tile (after P0)
+    const int b = base + tid;
+    if (tid == 0) sflag[0] = (b >= a.B || off[b] >= P0 + ti.count) ? 1 : 0;
+    if (b < a.B) {
+      const int64_t ob = off[b];
+      if (ob < P0 + ti.count) atomicAdd(&skey[(int)(ob - P0)], 1u);
+    }
+    __syncthreads();
+    const int done = sflag[0];
+    __syncthreads();
+    // monotone offsets: once this round's first bag starts past the tile, every later one does;
+    // a round whose first bag is inside may still have later bags inside, so go on
+    if (done) break;
+  }
+  {  // inclusive prefix of the start counters, thread t owning positions [t*kItems, (t+1)*kItems)
+    uint32_t c[kItems], s = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      c[j] = skey[tid * kItems + j];
+      s += c[j];
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan<kThreads>(s, smem, &total);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      run += c[j];
+      sval[tid * kItems + j] = (uint32_t)b0 + run;
+    }
+  }
+  __syncthreads();
+
+  // ---- bags of this thread's (wave-striped) positions, then rank by partition digit
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
+    val[j] = ok[j] ? sval[li] : 0u;
+  }
+  rank_items<kItems>(dg, ok, a.top_bits, wcnt, rnk);
+  __syncthreads();
+
+  // ---- destination offsets of this tile's digits
+  if (a.fused_scan) {
+    // few tiles: the raw counts of the table's tiles were summed above instead of a separate scan
+    uint32_t all;
+    const uint32_t base = block_exclusive_scan<kThreads>(total, smem, &all);
+    goff = (uint32_t)ti.tbl_start + base + before;
+    if (ti.t == 0 && tid < nb) a.bucket_start[(size_t)ti.k * nb + tid] = (uint32_t)ti.tbl_start + base;
+  }
+  uint32_t lofs, tot;
+  digit_offsets(nb, wcnt, smem, &lofs, &tot);
+  if (tid < nb) gofs[tid] = goff - lofs;
+  __syncthreads();
+
+  // ---- stage in LDS in sorted order so that one digit's global writes are contiguous
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (ok[j]) {
+      const uint32_t lp = wcnt[w][dg[j]] + rnk[j];
       skey[lp] = key[j];
       sval[lp] = val[j];
     }
   }
   __syncthreads();
-  uint32_t* kout = a.keys[src ^ 1];
-  uint32_t* vout = a.vals[src ^ 1];
-  for (int lp = threadIdx.x; lp < ti.count; lp += kTileThreads) {
+  uint32_t* kout = a.keys[1];
+  uint32_t* vout = a.vals[1];
+  for (int lp = tid; lp < ti.count; lp += kThreads) {
     const uint32_t kk = skey[lp];
     const uint32_t dst = gofs[(kk >> shift) & mask] + (uint32_t)lp;
     kout[dst] = kk;
@@ -270,150 +415,482 @@ __global__ __launch_bounds__(kTileThreads) void sort_scatter_kernel(GroupArgs a,
   }
 }
 
-// --- 3. run heads ----------------------------------------------------------------
-__device__ inline bool is_head(const uint32_t* keys, int64_t pos, int64_t tbl_start) {
-  return pos == tbl_start || keys[pos] != keys[pos - 1];
+// --- 4. bucket-local sort ----------------------------------------------------------------
+struct Bucket {
+  int k;
+  uint32_t start, n;   // global position of the bucket's first pair, pairs in the bucket
+  int low_bits;        // row-id bits below the partition digit
+};
+
+__device__ inline Bucket bucket_of_block(const GroupArgs& a) {
+  const int nb = 1 << a.top_bits;
+  Bucket b;
+  b.k = blockIdx.x >> a.top_bits;
+  const int dg = blockIdx.x & (nb - 1);
+  b.start = 0;
+  b.n = 0;
+  b.low_bits = 0;
+  if (a.tbl_off[b.k + 1] == a.tbl_off[b.k]) return b;  // no lookups: its bucket_start is never written
+  b.start = a.bucket_start[(size_t)b.k * nb + dg];
+  const uint32_t end = dg + 1 < nb ? a.bucket_start[(size_t)b.k * nb + dg + 1] : (uint32_t)a.tbl_off[b.k + 1];
+  b.n = end - b.start;
+  b.low_bits = top_shift(a, b.k);
+  return b;
 }
 
-__global__ __launch_bounds__(kTileThreads) void heads_count_kernel(GroupArgs a, int src) {
-  __shared__ uint32_t smem[kTileThreads / DLRM_WAVE + 1];
-  TileInfo ti;
-  uint32_t cnt = 0;
-  const bool live = find_tile(a, blockIdx.x, ti);
-  if (live) {
-    const uint32_t* keys = a.keys[src];
-    for (int i = threadIdx.x; i < ti.count; i += kTileThreads)
-      cnt += is_head(keys, ti.start + i, ti.tbl_start) ? 1u : 0u;
-  }
-  uint32_t total;
-  block_exclusive_scan<kTileThreads>(cnt, smem, &total);
-  if (threadIdx.x == 0) a.tile_heads[blockIdx.x] = total;  // dead tiles write 0
-}
+struct SortLds {
+  uint32_t wcnt[kNW][kMaxBuckets];
+  uint32_t skey[kBktCap];
+  uint32_t sval[kBktCap];
+  uint32_t heads[kBktCap + 1];
+  uint32_t base[kMaxBuckets];
+  uint32_t smem[kNW + 1];
+  uint32_t longs[kBktCap / kLongRun + 2];   // runs longer than kLongRun among the current heads
+  uint32_t nlong;
+};
 
-__global__ __launch_bounds__(1024) void heads_scan_kernel(GroupArgs a, int64_t nnz) {
-  __shared__ uint32_t smem[1024 / DLRM_WAVE + 1];
-  uint32_t carry = 0;
-  for (int t0 = 0; t0 < a.nt_max; t0 += 1024) {
-    const int t = t0 + threadIdx.x;
-    const uint32_t v = t < a.nt_max ? a.tile_heads[t] : 0u;
-    uint32_t total;
-    const uint32_t ex = block_exclusive_scan<1024>(v, smem, &total);
-    if (t < a.nt_max) a.tile_heads[t] = carry + ex;
-    carry += total;
-  }
-  if (threadIdx.x == 0) {
-    a.n_seg[0] = carry;
-    a.seg_start[carry] = (uint32_t)nnz;  // sentinel: the last run ends at nnz
-  }
-}
+__device__ inline int pass_bits(int left, int passes_left) { return (left + passes_left - 1) / passes_left; }
 
-__global__ __launch_bounds__(kTileThreads) void heads_write_kernel(GroupArgs a, int src) {
-  __shared__ uint32_t smem[kTileThreads / DLRM_WAVE + 1];
-  TileInfo ti;
-  if (!find_tile(a, blockIdx.x, ti)) return;
-  const uint32_t* keys = a.keys[src];
-  uint32_t base = a.tile_heads[blockIdx.x];
-  // thread t owns the contiguous positions [t*kItems, (t+1)*kItems) so that heads keep their order
-  uint32_t flags = 0, cnt = 0;
+// Buckets of at most kBktCap pairs: stable LSD passes entirely in LDS.  The pairs end up in
+// s.skey / s.sval in (row, position) order.
+__device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, SortLds& s) {
+  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
+  const uint32_t* kin = a.keys[1] + b.start;
+  const uint32_t* vin = a.vals[1] + b.start;
+  const int n = (int)b.n;
+  uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
+  bool ok[kBktItems];
 #pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int li = threadIdx.x * kItems + j;
-    if (li < ti.count && is_head(keys, ti.start + li, ti.tbl_start)) {
-      flags |= 1u << j;
-      ++cnt;
+  for (int j = 0; j < kBktItems; ++j) {
+    const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+    ok[j] = li < n;
+    key[j] = ok[j] ? kin[li] : 0xFFFFFFFFu;
+    val[j] = ok[j] ? vin[li] : 0u;
+  }
+  const int passes = (b.low_bits + kMaxTopBits - 1) / kMaxTopBits;
+  if (passes == 0) {  // a single row per bucket: already in position order
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+      if (ok[j]) {
+        s.skey[li] = key[j];
+        s.sval[li] = val[j];
+      }
+    }
+    __syncthreads();
+    return;
+  }
+  int shift = 0;
+  for (int p = 0; p < passes; ++p) {
+    const int bits = pass_bits(b.low_bits - shift, passes - p);
+    const int nb = 1 << bits;
+    const uint32_t mask = (uint32_t)nb - 1;
+    for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) dg[j] = (key[j] >> shift) & mask;
+    rank_items<kBktItems>(dg, ok, bits, s.wcnt, rnk);
+    __syncthreads();
+    uint32_t lofs, tot;
+    digit_offsets(nb, s.wcnt, s.smem, &lofs, &tot);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      if (ok[j]) {
+        const uint32_t lp = s.wcnt[w][dg[j]] + rnk[j];
+        s.skey[lp] = key[j];
+        s.sval[lp] = val[j];
+      }
+    }
+    __syncthreads();
+    shift += bits;
+    if (p + 1 < passes) {
+#pragma unroll
+      for (int j = 0; j < kBktItems; ++j) {
+        const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+        if (ok[j]) {
+          key[j] = s.skey[li];
+          val[j] = s.sval[li];
+        }
+      }
+      __syncthreads();
     }
   }
-  uint32_t total;
-  uint32_t pos = base + block_exclusive_scan<kTileThreads>(cnt, smem, &total);
-#pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    if (flags & (1u << j)) {
-      a.seg_start[pos] = (uint32_t)(ti.start + threadIdx.x * kItems + j);
-      a.seg_tbl[pos] = (uint32_t)ti.k;
-      ++pos;
-    }
-  }
 }
 
-// --- 4. segment reduce + SGD row update ---------------------------------------------
+// Larger buckets: the same stable passes, one workgroup streaming its bucket through global
+// memory (ping-pong between the two pair buffers).  Returns the buffer holding the result.
+__device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, SortLds& s) {
+  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
+  const int passes = (b.low_bits + kMaxTopBits - 1) / kMaxTopBits;
+  int src = 1, shift = 0;
+  for (int p = 0; p < passes; ++p) {
+    const int bits = pass_bits(b.low_bits - shift, passes - p);
+    const int nb = 1 << bits;
+    const uint32_t mask = (uint32_t)nb - 1;
+    const uint32_t* kin = a.keys[src] + b.start;
+    const uint32_t* vin = a.vals[src] + b.start;
+    uint32_t* kout = a.keys[src ^ 1] + b.start;
+    uint32_t* vout = a.vals[src ^ 1] + b.start;
+    // digit totals over the whole bucket -> running destination of every digit
+    if (tid < kMaxBuckets) s.base[tid] = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < b.n; i += kThreads) atomicAdd(&s.base[(kin[i] >> shift) & mask], 1u);
+    __syncthreads();
+    {
+      const uint32_t c = tid < nb ? s.base[tid] : 0u;
+      uint32_t all;
+      const uint32_t ex = block_exclusive_scan<kThreads>(c, s.smem, &all);
+      __syncthreads();
+      if (tid < nb) s.base[tid] = ex;
+    }
+    __syncthreads();
+    for (uint32_t t0 = 0; t0 < b.n; t0 += kBktCap) {  // tiles in order: stable
+      const int cnt = (int)(b.n - t0 < (uint32_t)kBktCap ? b.n - t0 : (uint32_t)kBktCap);
+      uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
+      bool ok[kBktItems];
+      for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+#pragma unroll
+      for (int j = 0; j < kBktItems; ++j) {
+        const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+        ok[j] = li < cnt;
+        key[j] = ok[j] ? kin[t0 + li] : 0xFFFFFFFFu;
+        val[j] = ok[j] ? vin[t0 + li] : 0u;
+        dg[j] = (key[j] >> shift) & mask;
+      }
+      __syncthreads();
+      rank_items<kBktItems>(dg, ok, bits, s.wcnt, rnk);
+      __syncthreads();
+      uint32_t lofs, tot;
+      digit_offsets(nb, s.wcnt, s.smem, &lofs, &tot);
+      if (tid < nb) s.heads[tid] = lofs;  // s.heads is free during the sort: tile-local digit offsets
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < kBktItems; ++j) {
+        if (ok[j]) {
+          // wcnt[w][dg] = tile-local sorted position of the wave's first item of the digit;
+          // minus the digit's tile-local offset = rank inside the digit within this tile
+          const uint32_t dst = s.base[dg[j]] + (s.wcnt[w][dg[j]] - s.heads[dg[j]]) + rnk[j];
+          kout[dst] = key[j];
+          vout[dst] = val[j];
+        }
+      }
+      __syncthreads();
+      if (tid < nb) s.base[tid] += tot;
+      __syncthreads();
+    }
+    src ^= 1;
+    shift += bits;
+  }
+  return src;
+}
+
+// --- 4b. runs -> row updates ------------------------------------------------------------------
 struct UpdArgs {
   void* const* tables;
   const float* dS;
   int64_t stride_b, stride_k;
   float lr;
   int32_t d;
-  const uint32_t* keys;     // sorted row ids
-  const uint32_t* bags;     // sorted bag ids
-  const uint32_t* seg_start;
-  const uint32_t* seg_tbl;
-  const uint32_t* n_seg;
 };
 
-// G lanes per segment, each lane owns 4 consecutive columns (16 bytes of fp32 gradient).
-template <int DT, int G, int U>
-__global__ __launch_bounds__(256) void reduce_update_kernel(UpdArgs a) {
-  constexpr int S = DLRM_WAVE / G;
-  const int lane = lane_id();
-  const int slot = lane / G, chunk = lane % G;
-  const bool col_ok = chunk * 4 < a.d;
-  const uint32_t nseg = a.n_seg[0];
-  const uint32_t ngroups = gridDim.x * (blockDim.x >> 6) * S;
-  for (uint32_t u = (blockIdx.x * (blockDim.x >> 6) + wave_id()) * S + slot; u < nseg; u += ngroups) {
-    const uint32_t i0 = a.seg_start[u], i1 = a.seg_start[u + 1];
-    const uint32_t k = a.seg_tbl[u];
-    // lanes past the last column shadow column group 0 (same addresses) and never write
-    const float* g = a.dS + (int64_t)k * a.stride_k + (col_ok ? chunk : 0) * 4;
-    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (uint32_t i = i0; i < i1; i += U) {
-      // branch-free: U bag ids, then U gradient rows, in flight together; the tail re-reads
-      // the run's last entry and is dropped
-      uint32_t bg[U];
-      f32x4 v[U];
-#pragma unroll
-      for (int t = 0; t < U; ++t) bg[t] = a.bags[i + t < i1 ? i + t : i1 - 1];
-#pragma unroll
-      for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)bg[t] * a.stride_b);
-#pragma unroll
-      for (int t = 0; t < U; ++t) {
-        const float m = i + t < i1 ? 1.0f : 0.0f;
-        if (m != 0.0f) acc += v[t];
-      }
-    }
-    if (!col_ok) continue;
-    const int64_t r = a.keys[i0];
-    char* W = static_cast<char*>(a.tables[k]);
-    if constexpr (DT == DLRM_F32) {
-      float* w = reinterpret_cast<float*>(W) + r * a.d + chunk * 4;
-      f32x4 x = loadf4(w);
-      x.x = fmaf(-a.lr, acc.x, x.x);
-      x.y = fmaf(-a.lr, acc.y, x.y);
-      x.z = fmaf(-a.lr, acc.z, x.z);
-      x.w = fmaf(-a.lr, acc.w, x.w);
-      storef4(w, x);
+// The 4 columns [chunk*4, chunk*4+4) of a table row: raw load, and update + store
+// (fp32: W - lr*g; fp16/bf16: widen, update in fp32, one round-to-nearest-even).
+// W: base of the table, read from the pointer array ONCE per workgroup -- the row stores below
+// may alias anything as far as the compiler knows, so a per-row read of tables[k] would be
+// re-issued (and waited for) before every row.
+template <int DT>
+__device__ inline char* row_chunk_ptr(char* W, int d, uint32_t row, int chunk) {
+  return W + ((int64_t)row * d + chunk * 4) * Tab<DT>::EB;
+}
+template <int DT>
+__device__ inline u32x4 row_chunk_load(const char* p) {
+  if constexpr (DT == DLRM_F32) {
+    return load16(p);
+  } else {
+    const u32x2 b = *reinterpret_cast<const u32x2*>(p);
+    return u32x4{b.x, b.y, 0u, 0u};
+  }
+}
+template <int DT>
+__device__ inline void row_chunk_update_store(char* p, u32x4 raw, f32x4 g, float lr) {
+  if constexpr (DT == DLRM_F32) {
+    f32x4 x;
+    x.x = fmaf(-lr, g.x, u2f(raw.x));
+    x.y = fmaf(-lr, g.y, u2f(raw.y));
+    x.z = fmaf(-lr, g.z, u2f(raw.z));
+    x.w = fmaf(-lr, g.w, u2f(raw.w));
+    storef4(reinterpret_cast<float*>(p), x);
+  } else {
+    float x0, x1, x2, x3;
+    if constexpr (DT == DLRM_F16) {
+      half2_to_float2(raw.x, x0, x1);
+      half2_to_float2(raw.y, x2, x3);
     } else {
-      u32x2* w = reinterpret_cast<u32x2*>(W + (r * a.d + chunk * 4) * 2);
-      u32x2 bits = *w;
-      float x0, x1, x2, x3;
-      if constexpr (DT == DLRM_F16) {
-        half2_to_float2(bits.x, x0, x1);
-        half2_to_float2(bits.y, x2, x3);
-      } else {
-        bf162_to_float2(bits.x, x0, x1);
-        bf162_to_float2(bits.y, x2, x3);
-      }
-      x0 = fmaf(-a.lr, acc.x, x0);
-      x1 = fmaf(-a.lr, acc.y, x1);
-      x2 = fmaf(-a.lr, acc.z, x2);
-      x3 = fmaf(-a.lr, acc.w, x3);
-      if constexpr (DT == DLRM_F16) {
-        bits.x = float2_to_half2(x0, x1);
-        bits.y = float2_to_half2(x2, x3);
-      } else {
-        bits.x = float2_to_bf162(x0, x1);
-        bits.y = float2_to_bf162(x2, x3);
-      }
-      *w = bits;
+      bf162_to_float2(raw.x, x0, x1);
+      bf162_to_float2(raw.y, x2, x3);
     }
+    x0 = fmaf(-lr, g.x, x0);
+    x1 = fmaf(-lr, g.y, x1);
+    x2 = fmaf(-lr, g.z, x2);
+    x3 = fmaf(-lr, g.w, x3);
+    u32x2 b;
+    if constexpr (DT == DLRM_F16) {
+      b.x = float2_to_half2(x0, x1);
+      b.y = float2_to_half2(x2, x3);
+    } else {
+      b.x = float2_to_bf162(x0, x1);
+      b.y = float2_to_bf162(x2, x3);
+    }
+    *reinterpret_cast<u32x2*>(p) = b;
+  }
+}
+template <int DT>
+__device__ inline void sgd_row_update(char* W, const UpdArgs& u, uint32_t row, int chunk, f32x4 g) {
+  char* p = row_chunk_ptr<DT>(W, u.d, row, chunk);
+  row_chunk_update_store<DT>(p, row_chunk_load<DT>(p), g, u.lr);
+}
+
+// Sum dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from i0 + first;
+// U loads in flight, ascending order.  bags: LDS or global.
+template <int U>
+__device__ inline f32x4 sum_entries(const float* g, int64_t stride_b, const uint32_t* bags, uint32_t i0,
+                                    uint32_t i1, uint32_t first, uint32_t stride) {
+  f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (uint32_t i = i0 + first; i < i1; i += U * stride) {
+    uint32_t bg[U];
+    f32x4 v[U];
+#pragma unroll
+    for (int t = 0; t < U; ++t) bg[t] = bags[i + t * stride < i1 ? i + t * stride : i];
+#pragma unroll
+    for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)bg[t] * stride_b);
+#pragma unroll
+    for (int t = 0; t < U; ++t)
+      if (i + t * stride < i1) acc += v[t];
+  }
+  return acc;
+}
+
+// keys/bags: the bucket's sorted pairs (n of them; LDS or global), heads: LDS list of run starts
+// with heads[nruns] = n.  gpos0: global position of the bucket's first pair.
+template <int DT, int G>
+__device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
+                                   const uint32_t* keys, const uint32_t* bags, const uint32_t* heads,
+                                   uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
+                                   int src, float* part) {
+  constexpr int NG = kThreads / G;
+  const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
+  const bool col_ok = chunk * 4 < u.d;
+  // lanes past the last column shadow column group 0 (same addresses) and never write
+  const float* g = u.dS + (int64_t)b.k * u.stride_k + (col_ok ? chunk : 0) * 4;
+  // short runs: a lane group takes RU runs per round; the table rows and the first gradient
+  // row of all RU runs are requested before any of them is consumed
+  constexpr int RU = 4;
+  const int cchunk = col_ok ? chunk : 0;
+  for (uint32_t r0 = (uint32_t)grp * RU; r0 < nruns; r0 += NG * RU) {
+    uint32_t i0[RU], i1[RU];
+    char* wp[RU];
+    u32x4 wv[RU];
+    f32x4 acc[RU];
+#pragma unroll
+    for (int t = 0; t < RU; ++t) {
+      const uint32_t rr = r0 + t < nruns ? r0 + t : nruns - 1;  // the tail repeats the last run
+      i0[t] = heads[rr] - h0;
+      i1[t] = heads[rr + 1] - h0;
+      wp[t] = row_chunk_ptr<DT>(W, u.d, keys[i0[t]], cchunk);
+    }
+#pragma unroll
+    for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)bags[i0[t]] * u.stride_b);
+#pragma unroll
+    for (int t = 0; t < RU; ++t) wv[t] = row_chunk_load<DT>(wp[t]);
+#pragma unroll
+    for (int t = 0; t < RU; ++t) {
+      const uint32_t len = i1[t] - i0[t];
+      if (r0 + t >= nruns || len > (uint32_t)kLongRun) continue;
+      if (len > 1) acc[t] += sum_entries<4>(g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
+      if (col_ok) row_chunk_update_store<DT>(wp[t], wv[t], acc[t], u.lr);
+    }
+  }
+  // long runs: the whole workgroup per run, lane group s taking entries s, s+NG, ...; the NG
+  // partial sums are added in group order
+  for (uint32_t q = 0; q < nlong; ++q) {  // uniform
+    const uint32_t r = longs[q];
+    const uint32_t i0 = heads[r] - h0, i1 = heads[r + 1] - h0;
+    const uint32_t len = i1 - i0;
+    if (len > (uint32_t)kHugeRun) {  // queue for the multi-workgroup pass
+      if (threadIdx.x == 0) {
+        const uint32_t nch = (len + kHugeChunk - 1) / kHugeChunk;
+        const unsigned long long t = atomicAdd(a.huge_ctr, (1ull << 32) | nch);
+        HugeRun hr;
+        hr.k = (uint32_t)b.k;
+        hr.row = keys[i0];
+        hr.start = b.start + h0 + i0;
+        hr.len = len;
+        hr.chunk_base = (uint32_t)(t & 0xFFFFFFFFull);
+        hr.nchunks = nch;
+        hr.done = 0;
+        hr.src = (uint32_t)src;
+        a.huge_runs[(uint32_t)(t >> 32)] = hr;
+      }
+      continue;
+    }
+    const f32x4 acc = sum_entries<4>(g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
+    __syncthreads();
+    if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
+    __syncthreads();
+    if (grp == 0 && col_ok) {
+      f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int s = 0; s < NG; ++s) tot += loadf4(part + s * (G * 4) + chunk * 4);
+      sgd_row_update<DT>(W, u, keys[i0], chunk, tot);
+    }
+  }
+}
+
+// Run heads of sorted keys[0..n) (LDS) into s.heads (positions, ascending) with the sentinel
+// heads[nruns] = n.  Returns nruns.  All threads call it.
+__device__ inline uint32_t compact_heads_lds(SortLds& s, int n) {
+  const int tid = threadIdx.x;
+  uint32_t flags = 0, cnt = 0;
+#pragma unroll
+  for (int j = 0; j < kBktItems; ++j) {
+    const int li = tid * kBktItems + j;
+    if (li < n && (li == 0 || s.skey[li] != s.skey[li - 1])) {
+      flags |= 1u << j;
+      ++cnt;
+    }
+  }
+  uint32_t total;
+  uint32_t pos = block_exclusive_scan<kThreads>(cnt, s.smem, &total);
+#pragma unroll
+  for (int j = 0; j < kBktItems; ++j) {
+    if (flags & (1u << j)) s.heads[pos++] = (uint32_t)(tid * kBktItems + j);
+  }
+  if (tid == 0) s.heads[total] = (uint32_t)n;
+  __syncthreads();
+  return total;
+}
+
+// Lists the runs longer than kLongRun among s.heads[0..nruns] (any order: each is a different
+// row).  At most kBktCap/kLongRun + 1 of them have their head inside a window of kBktCap positions.
+__device__ inline uint32_t collect_long_runs(SortLds& s, uint32_t nruns) {
+  if (threadIdx.x == 0) s.nlong = 0;
+  __syncthreads();
+  for (uint32_t r = threadIdx.x; r < nruns; r += kThreads) {
+    if (s.heads[r + 1] - s.heads[r] > (uint32_t)kLongRun) s.longs[atomicAdd(&s.nlong, 1u)] = r;
+  }
+  __syncthreads();
+  return s.nlong;
+}
+
+template <int DT, int G>
+__global__ __launch_bounds__(kThreads) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
+  __shared__ SortLds s;
+  __shared__ float part[kThreads * 4];
+  const Bucket b = bucket_of_block(a);
+  if (b.n == 0) return;
+  char* W = static_cast<char*>(u.tables[b.k]);
+  if (b.n <= (uint32_t)kBktCap) {
+    sort_bucket_lds(a, b, s);
+    const uint32_t nruns = compact_heads_lds(s, (int)b.n);
+    const uint32_t nlong = collect_long_runs(s, nruns);
+    reduce_runs<DT, G>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
+    return;
+  }
+  const int src = sort_bucket_global(a, b, s);
+  __syncthreads();
+  // walk the sorted bucket in windows of kBktCap positions; a run belongs to the window that
+  // holds its head and may extend past it (entries are read from global memory)
+  const uint32_t* keys = a.keys[src] + b.start;
+  const uint32_t* bags = a.vals[src] + b.start;
+  for (uint32_t w0 = 0; w0 < b.n; w0 += kBktCap) {
+    const int cnt = (int)(b.n - w0 < (uint32_t)kBktCap ? b.n - w0 : (uint32_t)kBktCap);
+    const int tid = threadIdx.x;
+    uint32_t flags = 0, c = 0;
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      const int li = tid * kBktItems + j;
+      if (li < cnt && (w0 + li == 0 || keys[w0 + li] != keys[w0 + li - 1])) {
+        flags |= 1u << j;
+        ++c;
+      }
+    }
+    uint32_t total;
+    uint32_t pos = block_exclusive_scan<kThreads>(c, s.smem, &total);
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      if (flags & (1u << j)) s.heads[pos++] = w0 + (uint32_t)(tid * kBktItems + j);
+    }
+    __syncthreads();
+    // end of the window's last run: first position >= w0 + cnt whose key differs (uniform walk
+    // in steps of the workgroup), or the end of the bucket
+    if (total > 0) {
+      const uint32_t last_key = keys[s.heads[total - 1]];
+      uint32_t e = w0 + (uint32_t)cnt;
+      while (e < b.n) {
+        const uint32_t q = e + tid;
+        const int same = (q < b.n && keys[q] == last_key) ? 1 : 0;
+        const int ns = __syncthreads_count(same);  // keys are sorted: the first ns probes match
+        e += (uint32_t)ns;
+        if (ns < kThreads) break;
+      }
+      if (tid == 0) s.heads[total] = e;
+      __syncthreads();
+      const uint32_t nlong = collect_long_runs(s, total);
+      reduce_runs<DT, G>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
+    }
+    __syncthreads();
+  }
+}
+
+// --- 5. runs too long for one workgroup ---------------------------------------------------------
+template <int DT, int G>
+__global__ __launch_bounds__(kThreads) void huge_runs_kernel(GroupArgs a, UpdArgs u) {
+  __shared__ float part[kThreads * 4];
+  __shared__ uint32_t ticket;
+  constexpr int NG = kThreads / G;
+  const unsigned long long ctr = a.huge_ctr[0];
+  const uint32_t nruns = (uint32_t)(ctr >> 32), nchunks = (uint32_t)(ctr & 0xFFFFFFFFull);
+  const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
+  const bool col_ok = chunk * 4 < u.d;
+  for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {  // uniform
+    // the run owning chunk c: runs were queued with increasing chunk_base
+    uint32_t lo = 0, hi = nruns;
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (a.huge_runs[mid].chunk_base <= c) lo = mid; else hi = mid;
+    }
+    const HugeRun hr = a.huge_runs[lo];
+    const uint32_t ci = c - hr.chunk_base;
+    const uint32_t i0 = hr.start + ci * kHugeChunk;
+    const uint32_t i1 = (ci + 1) * kHugeChunk < hr.len ? i0 + kHugeChunk : hr.start + hr.len;
+    const float* g = u.dS + (int64_t)hr.k * u.stride_k + (col_ok ? chunk : 0) * 4;
+    const f32x4 acc = sum_entries<4>(g, u.stride_b, a.vals[hr.src], i0, i1, (uint32_t)grp, (uint32_t)NG);
+    __syncthreads();
+    if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
+    __syncthreads();
+    float* slot = a.huge_part + (size_t)c * u.d;
+    if (grp == 0 && col_ok) {
+      f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int s = 0; s < NG; ++s) tot += loadf4(part + s * (G * 4) + chunk * 4);
+      storef4(slot + chunk * 4, tot);
+    }
+    // the chunk that finishes last adds the run's partials in chunk order and updates the row
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) ticket = atomicAdd(&a.huge_runs[lo].done, 1u);
+    __syncthreads();
+    if (ticket == hr.nchunks - 1) {
+      __threadfence();
+      if (grp == 0 && col_ok) {
+        f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
+        const float* p = a.huge_part + (size_t)hr.chunk_base * u.d + chunk * 4;
+        for (uint32_t j = 0; j < hr.nchunks; ++j) tot += loadf4(p + (size_t)j * u.d);
+        sgd_row_update<DT>(static_cast<char*>(u.tables[hr.k]), u, hr.row, chunk, tot);
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -434,9 +911,9 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
   constexpr int S = DLRM_WAVE / G;
   const int lane = lane_id();
   const int slot = lane / G, chunk = lane % G;
-  const int64_t bag = ((int64_t)blockIdx.x * (blockDim.x >> 6) + wave_id()) * S + slot;
-  if (bag >= (int64_t)a.K * a.B || chunk * 4 >= a.d) return;
-  const int k = (int)(bag / a.B), b = (int)(bag - (int64_t)k * a.B);
+  const uint32_t bag = (blockIdx.x * (blockDim.x >> 6) + wave_id()) * S + slot;
+  if (bag >= (uint32_t)a.K * (uint32_t)a.B || chunk * 4 >= a.d) return;
+  const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
   const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
   const int64_t p0 = off[b], p1 = off[b + 1];
   if (p1 <= p0) return;
@@ -453,7 +930,95 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
   }
 }
 
-// --- export (debug / parity) ---------------------------------------------------------
+// --- export (debug / parity): bucket sort written back, then canonical run lists --------------
+__global__ __launch_bounds__(kThreads) void bucket_sort_only_kernel(GroupArgs a) {
+  __shared__ SortLds s;
+  const Bucket b = bucket_of_block(a);
+  if (b.n == 0) return;
+  uint32_t* kout = a.keys[0] + b.start;
+  uint32_t* vout = a.vals[0] + b.start;
+  if (b.n <= (uint32_t)kBktCap) {
+    sort_bucket_lds(a, b, s);
+    for (uint32_t i = threadIdx.x; i < b.n; i += kThreads) {
+      kout[i] = s.skey[i];
+      vout[i] = s.sval[i];
+    }
+    return;
+  }
+  const int src = sort_bucket_global(a, b, s);
+  __syncthreads();
+  if (src != 0) {
+    for (uint32_t i = threadIdx.x; i < b.n; i += kThreads) {
+      kout[i] = a.keys[1][b.start + i];
+      vout[i] = a.vals[1][b.start + i];
+    }
+  }
+}
+
+__device__ inline bool is_head(const uint32_t* keys, int64_t pos, int64_t tbl_start) {
+  return pos == tbl_start || keys[pos] != keys[pos - 1];
+}
+
+__global__ __launch_bounds__(kThreads) void heads_count_kernel(GroupArgs a) {
+  __shared__ uint32_t smem[kNW + 1];
+  TileInfo ti;
+  uint32_t cnt = 0;
+  const bool live = find_tile(a, blockIdx.x, ti, smem);
+  if (live) {
+    const uint32_t* keys = a.keys[0];
+    for (int i = threadIdx.x; i < ti.count; i += kThreads)
+      cnt += is_head(keys, ti.start + i, ti.tbl_start) ? 1u : 0u;
+  }
+  uint32_t total;
+  block_exclusive_scan<kThreads>(cnt, smem, &total);
+  if (threadIdx.x == 0) a.tile_heads[blockIdx.x] = total;  // dead tiles write 0
+}
+
+__global__ __launch_bounds__(1024) void heads_scan_kernel(GroupArgs a, int64_t nnz) {
+  __shared__ uint32_t smem[1024 / DLRM_WAVE + 1];
+  uint32_t carry = 0;
+  for (int t0 = 0; t0 < a.nt_max; t0 += 1024) {
+    const int t = t0 + threadIdx.x;
+    const uint32_t v = t < a.nt_max ? a.tile_heads[t] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan<1024>(v, smem, &total);
+    if (t < a.nt_max) a.tile_heads[t] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0) {
+    a.n_seg[0] = carry;
+    a.seg_start[carry] = (uint32_t)nnz;  // sentinel: the last run ends at nnz
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void heads_write_kernel(GroupArgs a) {
+  __shared__ uint32_t smem[kNW + 1];
+  TileInfo ti;
+  if (!find_tile(a, blockIdx.x, ti, smem)) return;
+  const uint32_t* keys = a.keys[0];
+  const uint32_t base = a.tile_heads[blockIdx.x];
+  // thread t owns the contiguous positions [t*kItems, (t+1)*kItems) so that heads keep their order
+  uint32_t flags = 0, cnt = 0;
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int li = threadIdx.x * kItems + j;
+    if (li < ti.count && is_head(keys, ti.start + li, ti.tbl_start)) {
+      flags |= 1u << j;
+      ++cnt;
+    }
+  }
+  uint32_t total;
+  uint32_t pos = base + block_exclusive_scan<kThreads>(cnt, smem, &total);
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (flags & (1u << j)) {
+      a.seg_start[pos] = (uint32_t)(ti.start + threadIdx.x * kItems + j);
+      a.seg_tbl[pos] = (uint32_t)ti.k;
+      ++pos;
+    }
+  }
+}
+
 struct ExportArgs {
   int64_t* uniq_rows;
   int64_t* seg_start_out;
@@ -462,11 +1027,11 @@ struct ExportArgs {
   int64_t nnz;
 };
 
-__global__ __launch_bounds__(256) void export_kernel(GroupArgs a, int src, ExportArgs e) {
+__global__ __launch_bounds__(256) void export_kernel(GroupArgs a, ExportArgs e) {
   const uint32_t nseg = a.n_seg[0];
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t nth = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t p = tid; p < e.nnz; p += nth) e.sorted_bag[p] = (int32_t)a.vals[src][p];
+  for (int64_t p = tid; p < e.nnz; p += nth) e.sorted_bag[p] = (int32_t)a.vals[0][p];
   for (int64_t u = tid; u < nseg; u += nth) {
     const uint32_t k = a.seg_tbl[u];
     const int64_t tstart = a.tbl_off[k];
@@ -478,7 +1043,7 @@ __global__ __launch_bounds__(256) void export_kernel(GroupArgs a, int src, Expor
     }
     const int64_t local_u = u - lo;
     const uint32_t pos = a.seg_start[u];
-    e.uniq_rows[tstart + local_u] = (int64_t)a.keys[src][pos];
+    e.uniq_rows[tstart + local_u] = (int64_t)a.keys[0][pos];
     e.seg_start_out[tstart + local_u] = (int64_t)pos - tstart;
     const bool last_of_table = (u + 1 == nseg) || a.seg_tbl[u + 1] != k;
     if (last_of_table) e.n_uniq[k] = local_u + 1;
@@ -498,83 +1063,67 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.indices = s->indices;
   g.offsets = s->offsets;
   g.tbl_off = s->tbl_off;
+  g.rows = s->rows;
   g.K = s->K;
   g.B = s->B;
   g.nt_max = (int32_t)L.nt_max;
+  // partition digit: aim at ~1024 pairs per bucket, never more digits than the row ids have
+  const double per_table = (double)s->nnz_total / (double)s->K;
+  int tb = 0;
+  while (tb < kMaxTopBits && per_table / (double)(1 << tb) > 1024.0) ++tb;
+  const int kb = ilog2_ceil(s->max_rows);
+  if (tb > kb) tb = kb;
+  g.top_bits = tb;
+  g.fused_scan = L.nt_max <= kFusedScanMaxTiles ? 1 : 0;
   for (int i = 0; i < 2; ++i) {
     g.keys[i] = reinterpret_cast<uint32_t*>(base + L.keys[i]);
     g.vals[i] = reinterpret_cast<uint32_t*>(base + L.vals[i]);
   }
-  g.tile_prefix = reinterpret_cast<int32_t*>(base + L.tile_prefix);
   g.hist = reinterpret_cast<uint32_t*>(base + L.hist);
+  g.bucket_start = reinterpret_cast<uint32_t*>(base + L.bucket_start);
   g.tile_heads = reinterpret_cast<uint32_t*>(base + L.tile_heads);
   g.seg_start = reinterpret_cast<uint32_t*>(base + L.seg_start);
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
+  g.huge_ctr = reinterpret_cast<unsigned long long*>(base + L.huge_ctr);
+  g.huge_runs = reinterpret_cast<HugeRun*>(base + L.huge_runs);
+  g.huge_part = reinterpret_cast<float*>(base + L.huge_part);
 }
 
-// Enqueues stages 1-3; *final_src receives the index of the ping-pong buffer holding the
-// sorted pairs.
-static int enqueue_grouping(const dlrm_sparse_batch* s, const GroupArgs& g, int* final_src,
-                            hipStream_t st) {
-  const int64_t bags = (int64_t)s->K * s->B;
-  hipLaunchKernelGGL(tile_map_kernel, dim3(1), dim3(256), 0, st, g);
+// Enqueues steps 1-3: afterwards keys[1]/vals[1] hold the pairs partitioned into buckets and
+// bucket_start the bucket boundaries.
+static int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_t st) {
+  hipLaunchKernelGGL(bucket_hist_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
-  {
-    const double mean_len = (double)s->nnz_total / (double)bags;
-    int lg = 0;
-    while (lg < 6 && (double)(1 << (lg + 1)) <= mean_len) ++lg;
-    hipLaunchKernelGGL(expand_kernel, dim3(div_up(bags << lg, 256)), dim3(256), 0, st, g, lg);
+  if (!g.fused_scan) {
+    hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(1024), 0, st, g);
     DLRM_CHECK_LAUNCH();
   }
-  const int key_bits = ilog2_ceil(s->max_rows) > 0 ? ilog2_ceil(s->max_rows) : 1;
-  const int passes = (key_bits + kMaxDigitBits - 1) / kMaxDigitBits;
-  int src = 0, shift = 0;
-  for (int p = 0; p < passes; ++p) {
-    const int left = key_bits - shift;
-    const int bits = (left + (passes - p) - 1) / (passes - p);
-    hipLaunchKernelGGL(sort_hist_kernel, dim3(g.nt_max), dim3(kTileThreads), 0, st, g, src, shift, bits);
-    DLRM_CHECK_LAUNCH();
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(s->K), dim3(1024), 0, st, g, bits);
-    DLRM_CHECK_LAUNCH();
-    hipLaunchKernelGGL(sort_scatter_kernel, dim3(g.nt_max), dim3(kTileThreads), 0, st, g, src, shift, bits);
-    DLRM_CHECK_LAUNCH();
-    src ^= 1;
-    shift += bits;
-  }
-  hipLaunchKernelGGL(heads_count_kernel, dim3(g.nt_max), dim3(kTileThreads), 0, st, g, src);
+  hipLaunchKernelGGL(bucket_scatter_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
-  hipLaunchKernelGGL(heads_scan_kernel, dim3(1), dim3(1024), 0, st, g, s->nnz_total);
-  DLRM_CHECK_LAUNCH();
-  hipLaunchKernelGGL(heads_write_kernel, dim3(g.nt_max), dim3(kTileThreads), 0, st, g, src);
-  DLRM_CHECK_LAUNCH();
-  *final_src = src;
   return DLRM_OK;
 }
 
 template <int DT, int G>
-static int launch_update(const UpdArgs& u, int64_t nnz, hipStream_t st) {
-  constexpr int S = DLRM_WAVE / G;
-  // persistent grid: enough lane groups to cover the machine several times over, never more
-  // than one group per possible segment
-  int64_t blocks = (nnz + 4 * S - 1) / (4 * S);
-  if (blocks > 256 * 16) blocks = 256 * 16;
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL((reduce_update_kernel<DT, G, 4>), dim3((unsigned)blocks), dim3(256), 0, st, u);
+static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
+  const unsigned blocks = (unsigned)K << g.top_bits;
+  hipLaunchKernelGGL((bucket_reduce_kernel<DT, G>), dim3(blocks), dim3(kThreads), 0, st, g, u);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL((huge_runs_kernel<DT, G>), dim3(1024), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
 
 template <int DT>
-static int dispatch_update(const UpdArgs& u, int G, int64_t nnz, hipStream_t st) {
+static int dispatch_reduce(const GroupArgs& g, const UpdArgs& u, int G, int K, hipStream_t st) {
   switch (G) {
-    case 1: return launch_update<DT, 1>(u, nnz, st);
-    case 2: return launch_update<DT, 2>(u, nnz, st);
-    case 4: return launch_update<DT, 4>(u, nnz, st);
-    case 8: return launch_update<DT, 8>(u, nnz, st);
-    case 16: return launch_update<DT, 16>(u, nnz, st);
-    case 32: return launch_update<DT, 32>(u, nnz, st);
-    case 64: return launch_update<DT, 64>(u, nnz, st);
+    case 1: return launch_reduce<DT, 1>(g, u, K, st);
+    case 2: return launch_reduce<DT, 2>(g, u, K, st);
+    case 4: return launch_reduce<DT, 4>(g, u, K, st);
+    case 8: return launch_reduce<DT, 8>(g, u, K, st);
+    case 16: return launch_reduce<DT, 16>(g, u, K, st);
+    case 32: return launch_reduce<DT, 32>(g, u, K, st);
+    case 64: return launch_reduce<DT, 64>(g, u, K, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
@@ -589,9 +1138,9 @@ static int launch_atomic(const AtomArgs& a, hipStream_t st) {
 }
 
 static int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout* L) {
-  *L = ws_layout(s->K, s->nnz_total);
+  *L = ws_layout(s->K, s->d, s->nnz_total);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || bytes < L->total) return DLRM_ERR_WORKSPACE;
-  if (L->nt_max > 0x7FFFFFFF) return DLRM_ERR_BAD_SHAPE;
+  if (L->nt_max > 0x7FFFFFFF || ((int64_t)s->K << kMaxTopBits) > 0x7FFFFFFF) return DLRM_ERR_BAD_SHAPE;
   return DLRM_OK;
 }
 
@@ -604,7 +1153,7 @@ extern "C" size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t
   if (K < 1 || B < 1 || d < 1 || nnz_total < 0 || nnz_total > DLRM_MAX_NNZ || max_rows < 1 ||
       max_rows > DLRM_MAX_ROWS || !dtype_ok(table_dtype))
     return 0;
-  return ws_layout(K, nnz_total).total;
+  return ws_layout(K, d, nnz_total).total;
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
@@ -655,8 +1204,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   if (s->nnz_total == 0) return DLRM_OK;
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
-  int src = 0;
-  st = enqueue_grouping(s, g, &src, hs);
+  st = enqueue_partition(s, g, hs);
   if (st != DLRM_OK) return st;
   UpdArgs u;
   u.tables = s->tables;
@@ -665,15 +1213,10 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   u.stride_k = stride_k;
   u.lr = lr;
   u.d = s->d;
-  u.keys = g.keys[src];
-  u.bags = g.vals[src];
-  u.seg_start = g.seg_start;
-  u.seg_tbl = g.seg_tbl;
-  u.n_seg = g.n_seg;
   switch (s->table_dtype) {
-    case DLRM_F32: return dispatch_update<DLRM_F32>(u, G, s->nnz_total, hs);
-    case DLRM_F16: return dispatch_update<DLRM_F16>(u, G, s->nnz_total, hs);
-    case DLRM_BF16: return dispatch_update<DLRM_BF16>(u, G, s->nnz_total, hs);
+    case DLRM_F32: return dispatch_reduce<DLRM_F32>(g, u, G, s->K, hs);
+    case DLRM_F16: return dispatch_reduce<DLRM_F16>(g, u, G, s->K, hs);
+    case DLRM_BF16: return dispatch_reduce<DLRM_BF16>(g, u, G, s->K, hs);
   }
   return DLRM_ERR_BAD_DTYPE;
 }
@@ -694,9 +1237,16 @@ extern "C" int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* s, vo
   if (s->nnz_total == 0) return DLRM_OK;
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
-  int src = 0;
-  st = enqueue_grouping(s, g, &src, hs);
+  st = enqueue_partition(s, g, hs);
   if (st != DLRM_OK) return st;
+  hipLaunchKernelGGL(bucket_sort_only_kernel, dim3((unsigned)s->K << g.top_bits), dim3(kThreads), 0, hs, g);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL(heads_count_kernel, dim3(g.nt_max), dim3(kThreads), 0, hs, g);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL(heads_scan_kernel, dim3(1), dim3(1024), 0, hs, g, s->nnz_total);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL(heads_write_kernel, dim3(g.nt_max), dim3(kThreads), 0, hs, g);
+  DLRM_CHECK_LAUNCH();
   ExportArgs e;
   e.uniq_rows = uniq_rows;
   e.seg_start_out = seg_start;
@@ -705,7 +1255,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* s, vo
   e.nnz = s->nnz_total;
   unsigned grid = div_up(s->nnz_total, 256);
   if (grid > 2048) grid = 2048;
-  hipLaunchKernelGGL(export_kernel, dim3(grid), dim3(256), 0, hs, g, src, e);
+  hipLaunchKernelGGL(export_kernel, dim3(grid), dim3(256), 0, hs, g, e);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
