@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 METRIC = "emb-bag fwd+bwd lookups/s & HBM GB/s (% of peak); samples/s at batch 2048"
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script scaled by the same counters on the 1 GiB --copy-calib kernel;
+# the summaries are under profiles/.  Keyed by (workload, kernel).
+MEASURED_TRAFFIC = {(3, "bucket_reduce_kernel"): 906.0e6, (3, "emb_fwd_kernel"): 440.0e6}
 
 
 def parse_args():
@@ -32,6 +36,9 @@ def parse_args():
     ap.add_argument("--nbatches", type=int, default=0, help="distinct batches cycled (0 = pick)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="run a 1 GiB plain copy (place_dense with F=1) before the timed region, as the "
+                         "known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
     return ap.parse_args()
 
 
@@ -104,6 +111,26 @@ def main():
 
     stages = ["place_dense", "emb_bag_fwd", "interact_dot_fwd", "interact_dot_bwd", "emb_bag_bwd_sgd"]
 
+    if args.copy_calib:  # 2^22 x 64 fp32 = 1 GiB read + 1 GiB written by a plain copy kernel
+        src = torch.empty((1 << 22, 64), dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty((1 << 22, 1, 64), dtype=torch.float32, device=dev)
+        for _ in range(3):
+            hot.dlrm_place_dense(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # raw HIP events for the kernel inside dlrm_emb_bag_bwd_sgd (recorded by the library on the
+    # launch stream, around its dominant kernel)
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+
+    def hip_event():
+        ev = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(ev)) == 0
+        return ev
+    red_ev = [(hip_event(), hip_event()) for _ in range(args.steps)] if args.algo != "atomic" else None
+
     def step(i, ev=None):
         sb, x, dR = dev_batches[i % nb]
         if ev is not None:
@@ -120,6 +147,8 @@ def main():
         hot.dlrm_interact_dot_bwd(T, dR, dT)
         if ev is not None:
             ev[4].record()
+            if red_ev is not None:
+                hot.dlrm_profile_reduce_kernel(red_ev[i - args.warmup][0], red_ev[i - args.warmup][1])
         hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo, dS_offset=d)
         if ev is not None:
             ev[5].record()
@@ -137,6 +166,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
 
+    ids = [(args.warmup + i) % nb for i in range(args.steps)]
     stage_ms = {s: 0.0 for s in stages}
     for ev in events:
         for j, s in enumerate(stages):
@@ -144,20 +174,40 @@ def main():
     for s in stages:
         stage_ms[s] /= args.steps
 
-    ids = [(args.warmup + i) % nb for i in range(args.steps)]
     mean = lambda key: float(np.mean([abytes[i][key] for i in ids]))
     nnz_mean = mean("nnz")
     lookups_per_s = nnz_mean / (ms_per_step * 1e-3)
     emb_ms = stage_ms["emb_bag_fwd"] + stage_ms["emb_bag_bwd_sgd"]
     emb_bytes = mean("fwd") + mean("bwd")
 
-    # ---- roofline of the dominant kernel (the embedding forward and backward are HBM-bound)
-    if stage_ms["emb_bag_fwd"] >= stage_ms["emb_bag_bwd_sgd"] or True:
-        dom, dom_bytes, dom_ms = "emb_bag_fwd", mean("fwd"), stage_ms["emb_bag_fwd"]
+    # ---- roofline of the dominant kernel.  Both embedding kernels are HBM-bound gathers /
+    # scatters; the forward call is one kernel (its call events time it), the backward's
+    # bucket_reduce kernel is timed by the library's event hook.
+    hot.dlrm_profile_reduce_kernel(None, None)
+    red_ms = 0.0
+    if red_ev is not None:
+        for a, b_ in red_ev:
+            ms = ctypes.c_float()
+            assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b_) == 0
+            red_ms += ms.value
+        red_ms /= args.steps
+    # algorithmic bytes of one bucket_reduce launch: the sorted (row, bag) pairs (8 B per lookup),
+    # every pooled-vector gradient once, every touched row read and written once
+    red_bytes = float(np.mean([abytes[i]["nnz"] * 8 + K * B * d * 4 + 2 * abytes[i]["U"] * d * eb for i in ids]))
+    kernels = {
+        "emb_fwd_kernel": (mean("fwd"), stage_ms["emb_bag_fwd"]),
+        "bucket_reduce_kernel": (red_bytes, red_ms),
+    }
+    dom = max(kernels, key=lambda n: kernels[n][1])
+    dom_bytes, dom_ms = kernels[dom]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_ms": round(dom_ms, 5)}
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC.get((args.config, dom)),
+                "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_ms": round(dom_ms, 5),
+                "other_kernels": {n: {"algorithmic_bytes_per_launch": int(v[0]), "avg_launch_ms": round(v[1], 5),
+                                      "achieved": round(v[0] / (v[1] * 1e-3) / 1e9, 1) if v[1] > 0 else None}
+                                  for n, v in kernels.items() if n != dom}}
 
     out = {
         "metric": METRIC, "value": round(lookups_per_s, 1), "unit": "lookups/s", "n_gpus": 1,

@@ -196,6 +196,16 @@ int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* batch, void* wor
 int32_t dlrm_table_init_hash(void* table, int64_t rows, int32_t d, int32_t table_dtype,
                              uint64_t key, float scale, void* stream);
 
+/*
+ * Profiling aid (not part of the method; the only process-wide state in the library).
+ * While a pair of caller-owned hipEvent_t is set, every DLRM_BWD_SORT call records
+ * ev_start immediately before and ev_stop immediately after the launch of its dominant
+ * kernel (the bucket sort + row reduce + SGD update), on the stream of that call, so a
+ * benchmark can time that one kernel with HIP events.  Pass NULL, NULL to clear.  Both or
+ * neither must be NULL (else DLRM_ERR_NULL).  Not thread-safe.
+ */
+int32_t dlrm_profile_reduce_kernel(void* ev_start, void* ev_stop);
+
 #ifdef __cplusplus
 }
 #endif

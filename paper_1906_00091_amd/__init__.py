@@ -5,5 +5,5 @@ from .binding import (  # noqa: F401
     BF16, BWD_ATOMIC, BWD_AUTO, BWD_SORT, F16, F32, DlrmError, SparseBatch, alloc_workspace,
     dlrm_emb_bag_bwd_export_groups, dlrm_emb_bag_bwd_sgd, dlrm_emb_bag_bwd_workspace_bytes,
     dlrm_emb_bag_fwd, dlrm_interact_dot_bwd, dlrm_interact_dot_fwd, dlrm_lengths_to_offsets,
-    dlrm_place_dense, dlrm_table_init_hash, dlrm_validate_csr, lib, status_string, version,
+    dlrm_place_dense, dlrm_profile_reduce_kernel, dlrm_table_init_hash, dlrm_validate_csr, lib, status_string, version,
 )

@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_sgd.argtypes = [sb, vp, i64, i64, f32, vp, sz, i32, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
         L.dlrm_emb_bag_bwd_export_groups.argtypes = [sb, vp, sz, vp, vp, vp, vp, vp]
+        L.dlrm_profile_reduce_kernel.restype = i32
+        L.dlrm_profile_reduce_kernel.argtypes = [vp, vp]
         L.dlrm_table_init_hash.restype = i32
         L.dlrm_table_init_hash.argtypes = [vp, i64, i32, i32, C.c_uint64, f32, vp]
         _lib = L
@@ -192,6 +194,11 @@ def dlrm_table_init_hash(table: torch.Tensor, table_dtype: int, key: int, scale:
     _check("dlrm_table_init_hash",
            lib().dlrm_table_init_hash(_ptr(table), rows, d, table_dtype, C.c_uint64(key),
                                       C.c_float(scale), _stream()))
+
+
+def dlrm_profile_reduce_kernel(ev_start: Optional[int], ev_stop: Optional[int]):
+    """ev_start / ev_stop: raw hipEvent_t handles (ints) or None, None to clear."""
+    _check("dlrm_profile_reduce_kernel", lib().dlrm_profile_reduce_kernel(ev_start, ev_stop))
 
 
 def alloc_workspace(batch: SparseBatch) -> torch.Tensor:

@@ -1067,10 +1067,14 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.K = s->K;
   g.B = s->B;
   g.nt_max = (int32_t)L.nt_max;
-  // partition digit: aim at ~1024 pairs per bucket, never more digits than the row ids have
+  // partition digit: one workgroup per bucket, so aim at >= ~4096 buckets when the batch is
+  // large enough, with 128..1024 pairs per bucket; never more digits than the row ids have
+  double target = (double)s->nnz_total / 4096.0;
+  if (target < 128.0) target = 128.0;
+  if (target > 1024.0) target = 1024.0;
   const double per_table = (double)s->nnz_total / (double)s->K;
   int tb = 0;
-  while (tb < kMaxTopBits && per_table / (double)(1 << tb) > 1024.0) ++tb;
+  while (tb < kMaxTopBits && per_table / (double)(1 << tb) > target) ++tb;
   const int kb = ilog2_ceil(s->max_rows);
   if (tb > kb) tb = kb;
   g.top_bits = tb;
@@ -1104,11 +1108,16 @@ static int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hip
   return DLRM_OK;
 }
 
+// optional pair of caller-owned HIP events recorded around the bucket_reduce launch
+static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
 template <int DT, int G>
 static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
   const unsigned blocks = (unsigned)K << g.top_bits;
+  if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return DLRM_ERR_HIP;
   hipLaunchKernelGGL((bucket_reduce_kernel<DT, G>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
+  if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
   hipLaunchKernelGGL((huge_runs_kernel<DT, G>), dim3(1024), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
@@ -1147,6 +1156,13 @@ static int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout
 }  // namespace dlrm
 
 using namespace dlrm;
+
+extern "C" int32_t dlrm_profile_reduce_kernel(void* ev_start, void* ev_stop) {
+  if ((ev_start == nullptr) != (ev_stop == nullptr)) return DLRM_ERR_NULL;
+  g_ev_start = static_cast<hipEvent_t>(ev_start);
+  g_ev_stop = static_cast<hipEvent_t>(ev_stop);
+  return DLRM_OK;
+}
 
 extern "C" size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t nnz_total,
                                                    int64_t max_rows, int32_t table_dtype) {
