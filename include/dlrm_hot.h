@@ -3,7 +3,7 @@
  *
  * C ABI.  Every pointer is a DEVICE pointer owned by the caller unless a
  * comment says "host".  The library allocates nothing, keeps no state between
- * calls, and only enqueues work on the HIP stream passed as `stream`
+ * calls (the optional profiling hook at the end of this file aside), and only enqueues work on the HIP stream passed as `stream`
  * (a hipStream_t cast to void*; NULL = the default stream).  No call
  * synchronises with the host.
  *
