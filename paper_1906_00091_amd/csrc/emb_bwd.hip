@@ -30,14 +30,20 @@ constexpr int kThreads = 256;
 constexpr int kNW = kThreads / DLRM_WAVE;       // wavefronts per workgroup
 constexpr int kItems = 16;                      // positions per thread in a partition tile
 constexpr int kTile = kThreads * kItems;        // 4096 positions per tile
-constexpr int kMaxTopBits = 8;
+constexpr int kMaxTopBits = 10;                 // partition digit: up to 1024 buckets per table
 constexpr int kMaxBuckets = 1 << kMaxTopBits;
+constexpr int kDPT = kMaxBuckets / kThreads;    // partition digits owned by one thread
+constexpr int kSortBits = 8;                    // digit of the bucket-local LSD passes
+constexpr int kSortBuckets = 1 << kSortBits;
 constexpr int kBktItems = 8;                    // positions per thread in a bucket-sort tile
 constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size are sorted in LDS
 constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
 constexpr int kHugeChunk = 1024;
 constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatter below this
+constexpr int kSegMaxBits = 13;                 // oversized buckets with at most this many low bits are
+                                                // sorted by many workgroups (per-row counters in LDS)
+constexpr int kSegKeys = 1 << kSegMaxBits;
 
 // ---------------------------------------------------------------------------
 // Workspace layout (all offsets 256-byte aligned)
@@ -49,12 +55,20 @@ struct WsLayout {
   size_t seg_start;          // uint32[nnz + 1]      (export only)
   size_t seg_tbl;            // uint32[nnz]          (export only)
   size_t n_seg;              // uint32[4]            (export only)
-  size_t huge_ctr;           // uint64[2]: packed (runs << 32 | chunks) counter
+  size_t huge_ctr;           // uint64[2]: packed (runs << 32 | chunks) counter; [1] = oversized-bucket count
+  size_t over_list;          // uint32[nnz / kBktCap + 1]: buckets too large for the LDS sort
+  size_t segs;               // SegInfo[nnz / kBktCap + 2]: those of them sorted by many workgroups
+  size_t seg_meta;           // uint32[8]: nseg, ntiles, scatter tickets
   size_t huge_runs;          // HugeRun[nnz / kHugeRun + 1]
   size_t huge_part;          // float[(nnz / kHugeChunk + max_runs) * d]
   size_t total;
   int64_t nt_max;            // upper bound on the number of tiles
   int64_t max_huge;          // upper bound on the number of queued runs
+};
+
+struct SegInfo {
+  uint32_t start, n, k, low_bits;   // an oversized bucket: global position, pairs, table, unsorted bits
+  uint32_t tile0, pad0, pad1, pad2;  // index of its first kBktCap-position tile among all segments
 };
 
 struct HugeRun {
@@ -79,6 +93,9 @@ static WsLayout ws_layout(int32_t K, int32_t d, int64_t nnz) {
   L.seg_tbl = o;      o = align256(o + n * 4);
   L.n_seg = o;        o = align256(o + 16);
   L.huge_ctr = o;     o = align256(o + 16);
+  L.over_list = o;    o = align256(o + ((size_t)(nnz / kBktCap) + 1) * 4);
+  L.segs = o;         o = align256(o + ((size_t)(nnz / kBktCap) + 2) * sizeof(SegInfo));
+  L.seg_meta = o;     o = align256(o + 32);
   L.huge_runs = o;    o = align256(o + (size_t)L.max_huge * sizeof(HugeRun));
   L.huge_part = o;    o = align256(o + ((size_t)(nnz / kHugeChunk) + (size_t)L.max_huge) * (size_t)d * 4);
   L.total = o;
@@ -104,6 +121,12 @@ struct GroupArgs {            // everything the grouping kernels need
   uint32_t* seg_tbl;
   uint32_t* n_seg;
   unsigned long long* huge_ctr;
+  uint32_t* over_cnt;
+  uint32_t* over_list;
+  int32_t max_over;           // workgroups reserved at the front of the bucket grid for oversized buckets
+  SegInfo* segs;
+  int32_t seg_tiles_max;      // upper bound on the number of segment tiles
+  uint32_t* seg_meta;         // [0] nseg, [1] ntiles, [2] scatter-done tickets
   HugeRun* huge_runs;
   float* huge_part;
 };
@@ -124,6 +147,7 @@ struct TileInfo {
   int64_t start;   // global position of the tile's first item
   int count;       // items in the tile (1..kTile)
   int64_t tbl_start;
+  int total_tiles; // tiles of all tables
 };
 
 // Every workgroup rebuilds the tile map from tbl_off (K is small): tables own
@@ -144,9 +168,9 @@ __device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti, uin
       res[2] = (int)nt;
     }
     carry += total;
-    if ((uint32_t)tile < carry) break;  // uniform
   }
   __syncthreads();
+  ti.total_tiles = (int)carry;
   if (res[0] < 0) return false;
   ti.k = res[0];
   ti.t0 = res[1];
@@ -175,7 +199,13 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
     atomicAdd(&h[((uint32_t)idx[i] >> shift) & mask], 1u);
   __syncthreads();
   for (int i = threadIdx.x; i < nb; i += kThreads) a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
-  if (blockIdx.x == 0 && threadIdx.x == 0) a.huge_ctr[0] = 0ull;  // consumed two launches later
+  if (blockIdx.x == 0 && threadIdx.x == 0) {  // consumed by later launches of the same call
+    a.huge_ctr[0] = 0ull;
+    *a.over_cnt = 0u;
+    a.seg_meta[0] = 0u;
+    a.seg_meta[1] = 0u;
+    a.seg_meta[2] = 0u;
+  }
 }
 
 // --- 2. per-table scan (large batches only): counts -> destination offsets ------------
@@ -214,6 +244,12 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
     }
     carry += total;
   }
+  __syncthreads();  // this workgroup's bucket_start writes are visible to it
+  for (int dg = threadIdx.x; dg < nb; dg += 1024) {
+    const uint32_t st = a.bucket_start[(size_t)k * nb + dg];
+    const uint32_t en = dg + 1 < nb ? a.bucket_start[(size_t)k * nb + dg + 1] : (uint32_t)a.tbl_off[k + 1];
+    if (en - st > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(k * nb + dg);
+  }
 }
 
 // --- shared by steps 3 and 4: stable ranking of a tile by a digit ---------------------
@@ -222,9 +258,9 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
 // come from ballot matching; per-wave digit counters in LDS give the order across waves.
 // On return rnk[j] is the item's rank among the items of its wave with the same digit that
 // precede it, and wcnt[w][digit] the wave's count.  wcnt must be zero on entry.
-template <int ITEMS>
+template <int ITEMS, int NBK>
 __device__ inline void rank_items(const uint32_t* dg, const bool* ok, int bits,
-                                  uint32_t (*wcnt)[kMaxBuckets], uint32_t* rnk) {
+                                  uint32_t (*wcnt)[NBK], uint32_t* rnk) {
   const int lane = lane_id(), w = wave_id();
   const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
@@ -245,29 +281,78 @@ __device__ inline void rank_items(const uint32_t* dg, const bool* ok, int bits,
 }
 
 // After rank_items + a barrier: turns wcnt[w][digit] into the tile-local sorted position of
-// wave w's first item with that digit, and returns (for thread == digit) the tile-local
-// offset of the digit and its count.  All threads must call it.
-__device__ inline void digit_offsets(int nb, uint32_t (*wcnt)[kMaxBuckets], uint32_t* scan_smem,
+// wave w's first item with that digit.  Thread t owns the DPT = NBK/256 consecutive digits
+// t*DPT .. t*DPT+DPT-1 and gets their tile-local offsets and counts.  All threads must call it.
+template <int NBK>
+__device__ inline void digit_offsets(int nb, uint32_t (*wcnt)[NBK], uint32_t* scan_smem,
                                      uint32_t* lofs_out, uint32_t* tot_out) {
-  uint32_t c[kNW], tot = 0;
-  const int dg = threadIdx.x;  // kThreads >= kMaxBuckets
+  constexpr int DPT = NBK / kThreads;
+  uint32_t c[DPT][kNW], tot[DPT], sum = 0;
 #pragma unroll
-  for (int i = 0; i < kNW; ++i) {
-    c[i] = dg < nb ? wcnt[i][dg] : 0u;
-    tot += c[i];
-  }
-  uint32_t total_all;
-  const uint32_t lofs = block_exclusive_scan<kThreads>(tot, scan_smem, &total_all);
-  if (dg < nb) {
-    uint32_t run = lofs;
+  for (int q = 0; q < DPT; ++q) {
+    const int dg = threadIdx.x * DPT + q;
+    tot[q] = 0;
 #pragma unroll
     for (int i = 0; i < kNW; ++i) {
-      wcnt[i][dg] = run;
-      run += c[i];
+      c[q][i] = dg < nb ? wcnt[i][dg] : 0u;
+      tot[q] += c[q][i];
+    }
+    sum += tot[q];
+  }
+  uint32_t total_all;
+  uint32_t run = block_exclusive_scan<kThreads>(sum, scan_smem, &total_all);
+#pragma unroll
+  for (int q = 0; q < DPT; ++q) {
+    const int dg = threadIdx.x * DPT + q;
+    lofs_out[q] = run;
+    tot_out[q] = tot[q];
+    if (dg < nb) {
+#pragma unroll
+      for (int i = 0; i < kNW; ++i) {
+        wcnt[i][dg] = run;
+        run += c[q][i];
+      }
     }
   }
-  *lofs_out = lofs;
-  *tot_out = tot;
+}
+
+// Oversized buckets whose unsorted low bits fit per-row counters in LDS become "segments",
+// sorted by one workgroup per kBktCap-position tile (segment_sort_kernel).  One workgroup builds
+// the segment list and its tile map.  All threads call it.
+__device__ inline void prepare_segments(const GroupArgs& a, uint32_t* smem) {
+  const int nb = 1 << a.top_bits;
+  const uint32_t n_over = atomicAdd(a.over_cnt, 0u);
+  uint32_t nseg = 0, ntiles = 0;
+  for (uint32_t e0 = 0; e0 < n_over; e0 += kThreads) {
+    const uint32_t e = e0 + threadIdx.x;
+    SegInfo sg;
+    uint32_t ok = 0, nt = 0;
+    if (e < n_over) {
+      const uint32_t id = a.over_list[e];
+      const int k = (int)(id >> a.top_bits), dg = (int)(id & (uint32_t)(nb - 1));
+      sg.start = a.bucket_start[(size_t)k * nb + dg];
+      const uint32_t end = dg + 1 < nb ? a.bucket_start[(size_t)k * nb + dg + 1] : (uint32_t)a.tbl_off[k + 1];
+      sg.n = end - sg.start;
+      sg.k = (uint32_t)k;
+      sg.low_bits = (uint32_t)top_shift(a, k);
+      ok = sg.low_bits >= 1 && sg.low_bits <= (uint32_t)kSegMaxBits ? 1u : 0u;
+      nt = ok ? (sg.n + kBktCap - 1) / kBktCap : 0u;
+    }
+    uint32_t tot_s, tot_t;
+    const uint32_t slot = block_exclusive_scan<kThreads>(ok, smem, &tot_s);
+    const uint32_t tpos = block_exclusive_scan<kThreads>(nt, smem, &tot_t);
+    if (ok) {
+      sg.tile0 = ntiles + tpos;
+      sg.pad0 = sg.pad1 = sg.pad2 = 0;
+      a.segs[nseg + slot] = sg;
+    }
+    nseg += tot_s;
+    ntiles += tot_t;
+  }
+  if (threadIdx.x == 0) {
+    a.seg_meta[0] = nseg;
+    a.seg_meta[1] = ntiles;
+  }
 }
 
 // --- 3. stable scatter into buckets ---------------------------------------------------
@@ -277,7 +362,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
   __shared__ uint32_t skey[kTile];
   __shared__ uint32_t sval[kTile];
   __shared__ uint32_t smem[kNW + 1];
-  __shared__ int sflag[2];
+  __shared__ int sflag[1];
   TileInfo ti;
   if (!find_tile(a, blockIdx.x, ti, smem)) return;
   const int nb = 1 << a.top_bits;
@@ -298,29 +383,34 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
     key[j] = ok[j] ? (uint32_t)kin[li] : 0xFFFFFFFFu;
     dg[j] = (key[j] >> shift) & mask;
   }
-  uint32_t goff = 0, before = 0, total = 0;
-  if (a.fused_scan) {
-    if (tid < nb) {
-      const uint32_t* hrow = a.hist + (size_t)tid * a.nt_max + ti.t0;
+  // thread t owns the partition digits t*kDPT .. t*kDPT + kDPT-1
+  uint32_t goff[kDPT], before[kDPT], total[kDPT];
+#pragma unroll
+  for (int q = 0; q < kDPT; ++q) {
+    const int dgt = tid * kDPT + q;
+    goff[q] = before[q] = total[q] = 0;
+    if (dgt >= nb) continue;
+    if (a.fused_scan) {
+      const uint32_t* hrow = a.hist + (size_t)dgt * a.nt_max + ti.t0;
       int t = 0;
       for (; t + 8 <= ti.nt; t += 8) {
         uint32_t c[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) c[q] = hrow[t + q];
+        for (int z = 0; z < 8; ++z) c[z] = hrow[t + z];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          total += c[q];
-          before += t + q < ti.t ? c[q] : 0u;
+        for (int z = 0; z < 8; ++z) {
+          total[q] += c[z];
+          before[q] += t + z < ti.t ? c[z] : 0u;
         }
       }
       for (; t < ti.nt; ++t) {
         const uint32_t c = hrow[t];
-        total += c;
-        before += t < ti.t ? c : 0u;
+        total[q] += c;
+        before[q] += t < ti.t ? c : 0u;
       }
+    } else {
+      goff[q] = a.hist[(size_t)dgt * a.nt_max + blockIdx.x];
     }
-  } else if (tid < nb) {
-    goff = a.hist[(size_t)tid * a.nt_max + blockIdx.x];
   }
 
   // ---- bag of every position of the tile, from the offsets
@@ -379,20 +469,34 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
     const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
     val[j] = ok[j] ? sval[li] : 0u;
   }
-  rank_items<kItems>(dg, ok, a.top_bits, wcnt, rnk);
+  rank_items<kItems, kMaxBuckets>(dg, ok, a.top_bits, wcnt, rnk);
   __syncthreads();
 
   // ---- destination offsets of this tile's digits
   if (a.fused_scan) {
     // few tiles: the raw counts of the table's tiles were summed above instead of a separate scan
-    uint32_t all;
-    const uint32_t base = block_exclusive_scan<kThreads>(total, smem, &all);
-    goff = (uint32_t)ti.tbl_start + base + before;
-    if (ti.t == 0 && tid < nb) a.bucket_start[(size_t)ti.k * nb + tid] = (uint32_t)ti.tbl_start + base;
+    uint32_t sum = 0, all;
+#pragma unroll
+    for (int q = 0; q < kDPT; ++q) sum += total[q];
+    uint32_t base = block_exclusive_scan<kThreads>(sum, smem, &all);
+#pragma unroll
+    for (int q = 0; q < kDPT; ++q) {
+      const int dgt = tid * kDPT + q;
+      goff[q] = (uint32_t)ti.tbl_start + base + before[q];
+      if (ti.t == 0 && dgt < nb) {
+        a.bucket_start[(size_t)ti.k * nb + dgt] = (uint32_t)ti.tbl_start + base;
+        if (total[q] > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(ti.k * nb + dgt);
+      }
+      base += total[q];
+    }
   }
-  uint32_t lofs, tot;
-  digit_offsets(nb, wcnt, smem, &lofs, &tot);
-  if (tid < nb) gofs[tid] = goff - lofs;
+  uint32_t lofs[kDPT], tot[kDPT];
+  digit_offsets<kMaxBuckets>(nb, wcnt, smem, lofs, tot);
+#pragma unroll
+  for (int q = 0; q < kDPT; ++q) {
+    const int dgt = tid * kDPT + q;
+    if (dgt < nb) gofs[dgt] = goff[q] - lofs[q];
+  }
   __syncthreads();
 
   // ---- stage in LDS in sorted order so that one digit's global writes are contiguous
@@ -422,11 +526,26 @@ struct Bucket {
   int low_bits;        // row-id bits below the partition digit
 };
 
-__device__ inline Bucket bucket_of_block(const GroupArgs& a) {
+// Buckets larger than the LDS sort take much longer than the rest: they are listed during the
+// partition and handed to the FIRST workgroups of the grid, so that they start early and run
+// beside everything else.  Returns false if this workgroup has nothing to do.
+__device__ inline bool bucket_id_of_block(const GroupArgs& a, uint32_t* id, bool* oversized) {
+  if (blockIdx.x < (uint32_t)a.max_over) {
+    if (blockIdx.x >= *a.over_cnt) return false;
+    *id = a.over_list[blockIdx.x];
+    *oversized = true;
+    return true;
+  }
+  *id = blockIdx.x - (uint32_t)a.max_over;
+  *oversized = false;
+  return true;
+}
+
+__device__ inline Bucket bucket_of_block(const GroupArgs& a, uint32_t id) {
   const int nb = 1 << a.top_bits;
   Bucket b;
-  b.k = blockIdx.x >> a.top_bits;
-  const int dg = blockIdx.x & (nb - 1);
+  b.k = (int)(id >> a.top_bits);
+  const int dg = (int)(id & (uint32_t)(nb - 1));
   b.start = 0;
   b.n = 0;
   b.low_bits = 0;
@@ -439,11 +558,11 @@ __device__ inline Bucket bucket_of_block(const GroupArgs& a) {
 }
 
 struct SortLds {
-  uint32_t wcnt[kNW][kMaxBuckets];
+  uint32_t wcnt[kNW][kSortBuckets];
   uint32_t skey[kBktCap];
   uint32_t sval[kBktCap];
   uint32_t heads[kBktCap + 1];
-  uint32_t base[kMaxBuckets];
+  uint32_t base[kSortBuckets];
   uint32_t smem[kNW + 1];
   uint32_t longs[kBktCap / kLongRun + 2];   // runs longer than kLongRun among the current heads
   uint32_t nlong;
@@ -467,7 +586,7 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
     key[j] = ok[j] ? kin[li] : 0xFFFFFFFFu;
     val[j] = ok[j] ? vin[li] : 0u;
   }
-  const int passes = (b.low_bits + kMaxTopBits - 1) / kMaxTopBits;
+  const int passes = (b.low_bits + kSortBits - 1) / kSortBits;
   if (passes == 0) {  // a single row per bucket: already in position order
 #pragma unroll
     for (int j = 0; j < kBktItems; ++j) {
@@ -485,14 +604,14 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
     const int bits = pass_bits(b.low_bits - shift, passes - p);
     const int nb = 1 << bits;
     const uint32_t mask = (uint32_t)nb - 1;
-    for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+    for (int i = tid; i < kNW * kSortBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kBktItems; ++j) dg[j] = (key[j] >> shift) & mask;
-    rank_items<kBktItems>(dg, ok, bits, s.wcnt, rnk);
+    rank_items<kBktItems, kSortBuckets>(dg, ok, bits, s.wcnt, rnk);
     __syncthreads();
     uint32_t lofs, tot;
-    digit_offsets(nb, s.wcnt, s.smem, &lofs, &tot);
+    digit_offsets<kSortBuckets>(nb, s.wcnt, s.smem, &lofs, &tot);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kBktItems; ++j) {
@@ -522,7 +641,7 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
 // memory (ping-pong between the two pair buffers).  Returns the buffer holding the result.
 __device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, SortLds& s) {
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
-  const int passes = (b.low_bits + kMaxTopBits - 1) / kMaxTopBits;
+  const int passes = (b.low_bits + kSortBits - 1) / kSortBits;
   int src = 1, shift = 0;
   for (int p = 0; p < passes; ++p) {
     const int bits = pass_bits(b.low_bits - shift, passes - p);
@@ -533,7 +652,7 @@ __device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, So
     uint32_t* kout = a.keys[src ^ 1] + b.start;
     uint32_t* vout = a.vals[src ^ 1] + b.start;
     // digit totals over the whole bucket -> running destination of every digit
-    if (tid < kMaxBuckets) s.base[tid] = 0;
+    if (tid < kSortBuckets) s.base[tid] = 0;
     __syncthreads();
     for (uint32_t i = tid; i < b.n; i += kThreads) atomicAdd(&s.base[(kin[i] >> shift) & mask], 1u);
     __syncthreads();
@@ -549,7 +668,7 @@ __device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, So
       const int cnt = (int)(b.n - t0 < (uint32_t)kBktCap ? b.n - t0 : (uint32_t)kBktCap);
       uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
       bool ok[kBktItems];
-      for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+      for (int i = tid; i < kNW * kSortBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
 #pragma unroll
       for (int j = 0; j < kBktItems; ++j) {
         const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
@@ -559,10 +678,10 @@ __device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, So
         dg[j] = (key[j] >> shift) & mask;
       }
       __syncthreads();
-      rank_items<kBktItems>(dg, ok, bits, s.wcnt, rnk);
+      rank_items<kBktItems, kSortBuckets>(dg, ok, bits, s.wcnt, rnk);
       __syncthreads();
       uint32_t lofs, tot;
-      digit_offsets(nb, s.wcnt, s.smem, &lofs, &tot);
+      digit_offsets<kSortBuckets>(nb, s.wcnt, s.smem, &lofs, &tot);
       if (tid < nb) s.heads[tid] = lofs;  // s.heads is free during the sort: tile-local digit offsets
       __syncthreads();
 #pragma unroll
@@ -783,12 +902,68 @@ __device__ inline uint32_t collect_long_runs(SortLds& s, uint32_t nruns) {
   return s.nlong;
 }
 
+// First position in [lo, n) whose key differs from `key`, given that keys are sorted and every
+// position in [.., lo) of the run equals it: 256-ary search, workgroup-uniform.
+__device__ inline uint32_t run_end_search(const uint32_t* keys, uint32_t lo, uint32_t n, uint32_t key) {
+  uint32_t hi = n;  // the answer lies in [lo, hi]
+  while (lo < hi) {
+    const uint32_t step = (hi - lo + kThreads - 1) / kThreads;
+    const uint32_t q = lo + threadIdx.x * step;
+    const int same = (q < hi && keys[q] == key) ? 1 : 0;
+    const uint32_t cnt = (uint32_t)__syncthreads_count(same);  // sorted: the first cnt probes match
+    if (cnt == 0) break;
+    const uint32_t nhi = lo + cnt * step < hi ? lo + cnt * step : hi;
+    lo = lo + (cnt - 1) * step + 1;
+    hi = nhi;
+  }
+  return lo;
+}
+
+// One window of kBktCap positions of a sorted pair list (global memory): the runs whose head
+// lies in the window are reduced and applied; a run may extend past the window.
+template <int DT, int G>
+__device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
+                                     const uint32_t* keys, const uint32_t* bags, uint32_t w0, int src,
+                                     SortLds& s, float* part) {
+  const int cnt = (int)(b.n - w0 < (uint32_t)kBktCap ? b.n - w0 : (uint32_t)kBktCap);
+  const int tid = threadIdx.x;
+  uint32_t flags = 0, c = 0;
+#pragma unroll
+  for (int j = 0; j < kBktItems; ++j) {
+    const int li = tid * kBktItems + j;
+    if (li < cnt && (w0 + li == 0 || keys[w0 + li] != keys[w0 + li - 1])) {
+      flags |= 1u << j;
+      ++c;
+    }
+  }
+  uint32_t total;
+  uint32_t pos = block_exclusive_scan<kThreads>(c, s.smem, &total);
+#pragma unroll
+  for (int j = 0; j < kBktItems; ++j) {
+    if (flags & (1u << j)) s.heads[pos++] = w0 + (uint32_t)(tid * kBktItems + j);
+  }
+  __syncthreads();
+  if (total > 0) {  // uniform
+    const uint32_t e = run_end_search(keys, w0 + (uint32_t)cnt, b.n, keys[s.heads[total - 1]]);
+    if (tid == 0) s.heads[total] = e;
+    __syncthreads();
+    const uint32_t nlong = collect_long_runs(s, total);
+    reduce_runs<DT, G>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
+  }
+  __syncthreads();
+}
+
 template <int DT, int G>
 __global__ __launch_bounds__(kThreads) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ float part[kThreads * 4];
-  const Bucket b = bucket_of_block(a);
-  if (b.n == 0) return;
+  // workgroup 0 (always a front workgroup) also builds the segment list for the next launch
+  if (blockIdx.x == 0) prepare_segments(a, s.smem);
+  uint32_t bid;
+  bool oversized;
+  if (!bucket_id_of_block(a, &bid, &oversized)) return;
+  const Bucket b = bucket_of_block(a, bid);
+  if (b.n == 0 || (!oversized && b.n > (uint32_t)kBktCap)) return;
   char* W = static_cast<char*>(u.tables[b.k]);
   if (b.n <= (uint32_t)kBktCap) {
     sort_bucket_lds(a, b, s);
@@ -797,50 +972,142 @@ __global__ __launch_bounds__(kThreads) void bucket_reduce_kernel(GroupArgs a, Up
     reduce_runs<DT, G>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
     return;
   }
+  if (b.low_bits == 0) {  // the bucket holds one row: a single run, already in position order
+    if (threadIdx.x == 0) {
+      s.heads[0] = 0;
+      s.heads[1] = b.n;
+    }
+    __syncthreads();
+    const uint32_t nlong = collect_long_runs(s, 1);
+    reduce_runs<DT, G>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
+                       part);
+    return;
+  }
+  if (b.low_bits <= kSegMaxBits) return;  // sorted and reduced by the segment kernels
+  // many unsorted bits: this workgroup sorts the bucket alone, through global memory
   const int src = sort_bucket_global(a, b, s);
   __syncthreads();
-  // walk the sorted bucket in windows of kBktCap positions; a run belongs to the window that
-  // holds its head and may extend past it (entries are read from global memory)
   const uint32_t* keys = a.keys[src] + b.start;
   const uint32_t* bags = a.vals[src] + b.start;
-  for (uint32_t w0 = 0; w0 < b.n; w0 += kBktCap) {
-    const int cnt = (int)(b.n - w0 < (uint32_t)kBktCap ? b.n - w0 : (uint32_t)kBktCap);
-    const int tid = threadIdx.x;
-    uint32_t flags = 0, c = 0;
-#pragma unroll
-    for (int j = 0; j < kBktItems; ++j) {
-      const int li = tid * kBktItems + j;
-      if (li < cnt && (w0 + li == 0 || keys[w0 + li] != keys[w0 + li - 1])) {
-        flags |= 1u << j;
-        ++c;
-      }
-    }
-    uint32_t total;
-    uint32_t pos = block_exclusive_scan<kThreads>(c, s.smem, &total);
-#pragma unroll
-    for (int j = 0; j < kBktItems; ++j) {
-      if (flags & (1u << j)) s.heads[pos++] = w0 + (uint32_t)(tid * kBktItems + j);
-    }
-    __syncthreads();
-    // end of the window's last run: first position >= w0 + cnt whose key differs (uniform walk
-    // in steps of the workgroup), or the end of the bucket
-    if (total > 0) {
-      const uint32_t last_key = keys[s.heads[total - 1]];
-      uint32_t e = w0 + (uint32_t)cnt;
-      while (e < b.n) {
-        const uint32_t q = e + tid;
-        const int same = (q < b.n && keys[q] == last_key) ? 1 : 0;
-        const int ns = __syncthreads_count(same);  // keys are sorted: the first ns probes match
-        e += (uint32_t)ns;
-        if (ns < kThreads) break;
-      }
-      if (tid == 0) s.heads[total] = e;
-      __syncthreads();
-      const uint32_t nlong = collect_long_runs(s, total);
-      reduce_runs<DT, G>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
-    }
-    __syncthreads();
+  for (uint32_t w0 = 0; w0 < b.n; w0 += kBktCap) reduce_window<DT, G>(a, u, b, W, keys, bags, w0, src, s, part);
+}
+
+// --- 4c. oversized buckets ("segments") sorted by one workgroup per tile ------------------------
+__device__ inline bool find_segment_tile(const GroupArgs& a, SegInfo* sg, uint32_t* t) {
+  const uint32_t nseg = a.seg_meta[0], ntiles = a.seg_meta[1];
+  if (blockIdx.x >= ntiles) return false;
+  uint32_t lo = 0, hi = nseg;  // segs[lo].tile0 <= tile < segs[hi].tile0
+  while (hi - lo > 1) {
+    const uint32_t mid = (lo + hi) >> 1;
+    if (a.segs[mid].tile0 <= blockIdx.x) lo = mid; else hi = mid;
   }
+  *sg = a.segs[lo];
+  *t = blockIdx.x - sg->tile0;
+  return true;
+}
+
+// Every workgroup counts, per row of the segment, the pairs in the tiles before its own and in
+// the whole segment (the segment's keys stream through L2), sorts its own tile in LDS, and
+// writes each pair to  segment start + rows before + same row in earlier tiles + rank in tile:
+// the segment ends up fully sorted by (row, position) in pair buffer 0.
+__global__ __launch_bounds__(kThreads) void segment_sort_kernel(GroupArgs a) {
+  __shared__ SortLds s;
+  __shared__ uint32_t before[kSegKeys];
+  __shared__ uint32_t base[kSegKeys];
+  SegInfo sg;
+  uint32_t t;
+  if (!find_segment_tile(a, &sg, &t)) return;
+  const int tid = threadIdx.x;
+  const uint32_t nkeys = 1u << sg.low_bits, mask = nkeys - 1u;
+  const uint32_t tstart = t * kBktCap;
+  const uint32_t cnt = sg.n - tstart < (uint32_t)kBktCap ? sg.n - tstart : (uint32_t)kBktCap;
+  for (uint32_t i = tid; i < nkeys; i += kThreads) {
+    before[i] = 0;
+    base[i] = 0;
+  }
+  __syncthreads();
+  const uint32_t* kin = a.keys[1] + sg.start;
+  for (uint32_t i0 = 0; i0 < sg.n; i0 += kThreads * 8) {  // 8 loads in flight per thread
+    uint32_t kk[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t i = i0 + q * kThreads + tid;
+      kk[q] = kin[i < sg.n ? i : sg.n - 1];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      // a wavefront covers 64 consecutive positions, all on one side of tstart (a multiple of 64).
+      // Segments are dominated by a few rows: the lanes that agree with the first valid lane
+      // are counted with ONE LDS atomic instead of a 64-way conflict on the same counter.
+      const uint32_t i = i0 + q * kThreads + tid;
+      const bool valid = i < sg.n;
+      uint32_t* ctr = i < tstart ? before : base;
+      const uint32_t r = kk[q] & mask;
+      const unsigned long long vm = __ballot(valid);
+      if (vm == 0ull) continue;  // wave-uniform
+      const int first = __ffsll((long long)vm) - 1;
+      const uint32_t r0 = __shfl(r, first, DLRM_WAVE);
+      const unsigned long long same = __ballot(valid && r == r0);
+      if (lane_id() == first) atomicAdd(&ctr[r0], (uint32_t)__popcll(same));
+      if (valid && r != r0) atomicAdd(&ctr[r], 1u);
+    }
+  }
+  __syncthreads();
+  {  // base[r] <- number of pairs of the segment with a smaller row (exclusive scan of the totals)
+    const uint32_t per = (nkeys + kThreads - 1) / kThreads;
+    uint32_t sum = 0;
+    for (uint32_t j = 0; j < per; ++j) {
+      const uint32_t r = tid * per + j;
+      if (r < nkeys) sum += before[r] + base[r];
+    }
+    uint32_t all;
+    uint32_t run = block_exclusive_scan<kThreads>(sum, s.smem, &all);
+    for (uint32_t j = 0; j < per; ++j) {
+      const uint32_t r = tid * per + j;
+      if (r < nkeys) {
+        const uint32_t c = before[r] + base[r];
+        base[r] = run;
+        run += c;
+      }
+    }
+  }
+  __syncthreads();
+  Bucket tb;
+  tb.k = (int)sg.k;
+  tb.start = sg.start + tstart;
+  tb.n = cnt;
+  tb.low_bits = (int)sg.low_bits;
+  sort_bucket_lds(a, tb, s);
+  uint32_t* kout = a.keys[0] + sg.start;
+  uint32_t* vout = a.vals[0] + sg.start;
+  for (uint32_t p = tid; p < cnt; p += kThreads) {
+    const uint32_t key = s.skey[p];
+    uint32_t lo = 0, hi = p;  // first position of this key in the sorted tile
+    while (lo < hi) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (s.skey[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    const uint32_t r = key & mask;
+    const uint32_t dst = base[r] + before[r] + (p - lo);
+    kout[dst] = key;
+    vout[dst] = s.sval[p];
+  }
+}
+
+template <int DT, int G>
+__global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, UpdArgs u) {
+  __shared__ SortLds s;
+  __shared__ float part[kThreads * 4];
+  SegInfo sg;
+  uint32_t t;
+  if (!find_segment_tile(a, &sg, &t)) return;
+  Bucket b;
+  b.k = (int)sg.k;
+  b.start = sg.start;
+  b.n = sg.n;
+  b.low_bits = 0;
+  char* W = static_cast<char*>(u.tables[b.k]);
+  reduce_window<DT, G>(a, u, b, W, a.keys[0] + sg.start, a.vals[0] + sg.start, t * kBktCap, 0, s, part);
 }
 
 // --- 5. runs too long for one workgroup ---------------------------------------------------------
@@ -933,8 +1200,10 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
 // --- export (debug / parity): bucket sort written back, then canonical run lists --------------
 __global__ __launch_bounds__(kThreads) void bucket_sort_only_kernel(GroupArgs a) {
   __shared__ SortLds s;
-  const Bucket b = bucket_of_block(a);
+  if (blockIdx.x == 0) prepare_segments(a, s.smem);
+  const Bucket b = bucket_of_block(a, blockIdx.x);
   if (b.n == 0) return;
+  if (b.n > (uint32_t)kBktCap && b.low_bits >= 1 && b.low_bits <= kSegMaxBits) return;  // a segment
   uint32_t* kout = a.keys[0] + b.start;
   uint32_t* vout = a.vals[0] + b.start;
   if (b.n <= (uint32_t)kBktCap) {
@@ -1067,9 +1336,10 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.K = s->K;
   g.B = s->B;
   g.nt_max = (int32_t)L.nt_max;
-  // partition digit: one workgroup per bucket, so aim at >= ~4096 buckets when the batch is
-  // large enough, with 128..1024 pairs per bucket; never more digits than the row ids have
-  double target = (double)s->nnz_total / 4096.0;
+  // partition digit: one workgroup per bucket, so aim at >= ~1536 buckets when the batch is
+  // large enough, with 128..1024 pairs per bucket (measured on the 8 x 1M x 64 multi-hot batch:
+  // 800 pairs per bucket beat 200 by 8%); never more digits than the row ids have
+  double target = (double)s->nnz_total / 1536.0;
   if (target < 128.0) target = 128.0;
   if (target > 1024.0) target = 1024.0;
   const double per_table = (double)s->nnz_total / (double)s->K;
@@ -1090,6 +1360,15 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
   g.huge_ctr = reinterpret_cast<unsigned long long*>(base + L.huge_ctr);
+  g.over_cnt = reinterpret_cast<uint32_t*>(base + L.huge_ctr + 8);
+  g.over_list = reinterpret_cast<uint32_t*>(base + L.over_list);
+  g.segs = reinterpret_cast<SegInfo*>(base + L.segs);
+  g.seg_meta = reinterpret_cast<uint32_t*>(base + L.seg_meta);
+  {
+    const int64_t nbk = (int64_t)s->K << tb, cap = s->nnz_total / kBktCap + 1;
+    g.max_over = (int32_t)(nbk < cap ? nbk : cap);
+    g.seg_tiles_max = (int32_t)(s->nnz_total / kBktCap + g.max_over);
+  }
   g.huge_runs = reinterpret_cast<HugeRun*>(base + L.huge_runs);
   g.huge_part = reinterpret_cast<float*>(base + L.huge_part);
 }
@@ -1113,11 +1392,16 @@ static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 template <int DT, int G>
 static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
-  const unsigned blocks = (unsigned)K << g.top_bits;
+  const unsigned blocks = ((unsigned)K << g.top_bits) + (unsigned)g.max_over;
   if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return DLRM_ERR_HIP;
   hipLaunchKernelGGL((bucket_reduce_kernel<DT, G>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
+  const unsigned seg_tiles = (unsigned)(g.seg_tiles_max);
+  hipLaunchKernelGGL(segment_sort_kernel, dim3(seg_tiles), dim3(kThreads), 0, st, g);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL((segment_reduce_kernel<DT, G>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
+  DLRM_CHECK_LAUNCH();
   hipLaunchKernelGGL((huge_runs_kernel<DT, G>), dim3(1024), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
@@ -1256,6 +1540,8 @@ extern "C" int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* s, vo
   st = enqueue_partition(s, g, hs);
   if (st != DLRM_OK) return st;
   hipLaunchKernelGGL(bucket_sort_only_kernel, dim3((unsigned)s->K << g.top_bits), dim3(kThreads), 0, hs, g);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL(segment_sort_kernel, dim3((unsigned)g.seg_tiles_max), dim3(kThreads), 0, hs, g);
   DLRM_CHECK_LAUNCH();
   hipLaunchKernelGGL(heads_count_kernel, dim3(g.nt_max), dim3(kThreads), 0, hs, g);
   DLRM_CHECK_LAUNCH();
