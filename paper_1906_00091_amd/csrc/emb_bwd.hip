@@ -39,7 +39,9 @@ constexpr int kBktItems = 8;                    // positions per thread in a buc
 constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size are sorted in LDS
 constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
-constexpr int kHugeChunk = 1024;
+constexpr int kHotTileFloats = 16384;            // 64 KB of LDS: gradient rows of one bag tile
+constexpr int kHotTilesPerGroup = 8;            // bag tiles streamed by one workgroup
+constexpr int kHotRunsPerWave = 4;              // hot runs a wavefront accumulates at once
 constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatter below this
 constexpr int kSegMaxBits = 13;                 // oversized buckets with at most this many low bits are
                                                 // sorted by many workgroups (per-row counters in LDS)
@@ -55,12 +57,13 @@ struct WsLayout {
   size_t seg_start;          // uint32[nnz + 1]      (export only)
   size_t seg_tbl;            // uint32[nnz]          (export only)
   size_t n_seg;              // uint32[4]            (export only)
-  size_t huge_ctr;           // uint64[2]: packed (runs << 32 | chunks) counter; [1] = oversized-bucket count
+  size_t huge_ctr;           // uint32[4]: [2] = oversized-bucket count
+  size_t hot_cnt;            // uint32[K]: queued hot runs per table
   size_t over_list;          // uint32[nnz / kBktCap + 1]: buckets too large for the LDS sort
   size_t segs;               // SegInfo[nnz / kBktCap + 2]: those of them sorted by many workgroups
   size_t seg_meta;           // uint32[8]: nseg, ntiles, scatter tickets
-  size_t huge_runs;          // HugeRun[nnz / kHugeRun + 1]
-  size_t huge_part;          // float[(nnz / kHugeChunk + max_runs) * d]
+  size_t huge_runs;          // HugeRun[nnz / kHugeRun + K]: table k's list starts at sum_{j<k}(nnz_j/kHugeRun + 1)
+  size_t huge_part;          // float[max_runs * bag groups * d]
   size_t total;
   int64_t nt_max;            // upper bound on the number of tiles
   int64_t max_huge;          // upper bound on the number of queued runs
@@ -73,17 +76,23 @@ struct SegInfo {
 
 struct HugeRun {
   uint32_t k, row, start, len;   // start: global position of the run's first sorted entry
-  uint32_t chunk_base, nchunks, done, src;
+  uint32_t done, src, pad0, pad1; // done: bag groups finished; src: pair buffer holding the run
 };
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-static WsLayout ws_layout(int32_t K, int32_t d, int64_t nnz) {
+static inline int hot_tile_bags(int d) { return kHotTileFloats / d; }
+static inline int hot_groups(int B, int d) {
+  const int gb = hot_tile_bags(d) * kHotTilesPerGroup;
+  return (B + gb - 1) / gb;
+}
+
+static WsLayout ws_layout(int32_t K, int32_t B, int32_t d, int64_t nnz) {
   WsLayout L;
   size_t o = 0;
   const size_t n = (size_t)(nnz > 0 ? nnz : 1);
   L.nt_max = nnz / kTile + K;
-  L.max_huge = nnz / kHugeRun + 1;
+  L.max_huge = nnz / kHugeRun + K;
   for (int i = 0; i < 2; ++i) { L.keys[i] = o; o = align256(o + n * 4); }
   for (int i = 0; i < 2; ++i) { L.vals[i] = o; o = align256(o + n * 4); }
   L.hist = o;         o = align256(o + (size_t)kMaxBuckets * (size_t)L.nt_max * 4);
@@ -93,11 +102,12 @@ static WsLayout ws_layout(int32_t K, int32_t d, int64_t nnz) {
   L.seg_tbl = o;      o = align256(o + n * 4);
   L.n_seg = o;        o = align256(o + 16);
   L.huge_ctr = o;     o = align256(o + 16);
+  L.hot_cnt = o;      o = align256(o + (size_t)K * 4);
   L.over_list = o;    o = align256(o + ((size_t)(nnz / kBktCap) + 1) * 4);
   L.segs = o;         o = align256(o + ((size_t)(nnz / kBktCap) + 2) * sizeof(SegInfo));
   L.seg_meta = o;     o = align256(o + 32);
   L.huge_runs = o;    o = align256(o + (size_t)L.max_huge * sizeof(HugeRun));
-  L.huge_part = o;    o = align256(o + ((size_t)(nnz / kHugeChunk) + (size_t)L.max_huge) * (size_t)d * 4);
+  L.huge_part = o;    o = align256(o + (size_t)L.max_huge * (size_t)hot_groups(B, d) * (size_t)d * 4);
   L.total = o;
   return L;
 }
@@ -120,7 +130,7 @@ struct GroupArgs {            // everything the grouping kernels need
   uint32_t* seg_start;
   uint32_t* seg_tbl;
   uint32_t* n_seg;
-  unsigned long long* huge_ctr;
+  uint32_t* hot_cnt;
   uint32_t* over_cnt;
   uint32_t* over_list;
   int32_t max_over;           // workgroups reserved at the front of the bucket grid for oversized buckets
@@ -130,6 +140,13 @@ struct GroupArgs {            // everything the grouping kernels need
   HugeRun* huge_runs;
   float* huge_part;
 };
+
+// start of table k's hot-run list: every table may queue at most nnz_k / kHugeRun runs
+__device__ inline uint32_t hot_list_base(const GroupArgs& a, int k) {
+  uint32_t base = 0;
+  for (int j = 0; j < k; ++j) base += (uint32_t)((a.tbl_off[j + 1] - a.tbl_off[j]) / kHugeRun) + 1u;
+  return base;
+}
 
 // bits needed to index m rows; the partition digit of table k is row >> top_shift(k)
 __device__ inline int key_bits(int64_t m) { return m <= 1 ? 0 : 64 - __clzll((unsigned long long)(m - 1)); }
@@ -200,8 +217,8 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
   __syncthreads();
   for (int i = threadIdx.x; i < nb; i += kThreads) a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
   if (blockIdx.x == 0 && threadIdx.x == 0) {  // consumed by later launches of the same call
-    a.huge_ctr[0] = 0ull;
     *a.over_cnt = 0u;
+    for (int k = 0; k < a.K; ++k) a.hot_cnt[k] = 0u;
     a.seg_meta[0] = 0u;
     a.seg_meta[1] = 0u;
     a.seg_meta[2] = 0u;
@@ -838,18 +855,15 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     const uint32_t len = i1 - i0;
     if (len > (uint32_t)kHugeRun) {  // queue for the multi-workgroup pass
       if (threadIdx.x == 0) {
-        const uint32_t nch = (len + kHugeChunk - 1) / kHugeChunk;
-        const unsigned long long t = atomicAdd(a.huge_ctr, (1ull << 32) | nch);
         HugeRun hr;
         hr.k = (uint32_t)b.k;
         hr.row = keys[i0];
         hr.start = b.start + h0 + i0;
         hr.len = len;
-        hr.chunk_base = (uint32_t)(t & 0xFFFFFFFFull);
-        hr.nchunks = nch;
         hr.done = 0;
         hr.src = (uint32_t)src;
-        a.huge_runs[(uint32_t)(t >> 32)] = hr;
+        hr.pad0 = hr.pad1 = 0;
+        a.huge_runs[hot_list_base(a, b.k) + atomicAdd(&a.hot_cnt[b.k], 1u)] = hr;
       }
       continue;
     }
@@ -1110,54 +1124,111 @@ __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, U
   reduce_window<DT, G>(a, u, b, W, a.keys[0] + sg.start, a.vals[0] + sg.start, t * kBktCap, 0, s, part);
 }
 
-// --- 5. runs too long for one workgroup ---------------------------------------------------------
+// --- 5. hot rows: runs too long for one workgroup -------------------------------------------------
+// A hot row is looked up by a large share of the bags, so summing its run entry by entry would
+// fetch nearly the whole gradient slice dS[:, k, :] once per hot row.  Instead workgroup (g, k)
+// streams the gradient rows of bag group g of table k through LDS ONCE, tile by tile, and every
+// wavefront adds, for each of its hot runs, the rows of the run's entries whose bag lies in the
+// tile (a run's bags are sorted, so a cursor per run only moves forward).  Partial sums per
+// (run, bag group) go to global memory; the group that finishes a run last adds them in group
+// order and updates the row (fence + counter, nobody waits).
 template <int DT, int G>
-__global__ __launch_bounds__(kThreads) void huge_runs_kernel(GroupArgs a, UpdArgs u) {
-  __shared__ float part[kThreads * 4];
-  __shared__ uint32_t ticket;
-  constexpr int NG = kThreads / G;
-  const unsigned long long ctr = a.huge_ctr[0];
-  const uint32_t nruns = (uint32_t)(ctr >> 32), nchunks = (uint32_t)(ctr & 0xFFFFFFFFull);
-  const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
+__global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int tile_bags,
+                                                            int group_bags, int ngroups) {
+  __shared__ float tile[kHotTileFloats];
+  constexpr int S = DLRM_WAVE / G;
+  constexpr int MR = kHotRunsPerWave;
+  const int k = blockIdx.y, g = blockIdx.x;
+  const uint32_t nruns = a.hot_cnt[k];
+  if (nruns == 0) return;  // uniform
+  const uint32_t base = hot_list_base(a, k);
+  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
+  const int slot = lane / G, chunk = lane % G;
   const bool col_ok = chunk * 4 < u.d;
-  for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {  // uniform
-    // the run owning chunk c: runs were queued with increasing chunk_base
-    uint32_t lo = 0, hi = nruns;
-    while (hi - lo > 1) {
-      const uint32_t mid = (lo + hi) >> 1;
-      if (a.huge_runs[mid].chunk_base <= c) lo = mid; else hi = mid;
-    }
-    const HugeRun hr = a.huge_runs[lo];
-    const uint32_t ci = c - hr.chunk_base;
-    const uint32_t i0 = hr.start + ci * kHugeChunk;
-    const uint32_t i1 = (ci + 1) * kHugeChunk < hr.len ? i0 + kHugeChunk : hr.start + hr.len;
-    const float* g = u.dS + (int64_t)hr.k * u.stride_k + (col_ok ? chunk : 0) * 4;
-    const f32x4 acc = sum_entries<4>(g, u.stride_b, a.vals[hr.src], i0, i1, (uint32_t)grp, (uint32_t)NG);
-    __syncthreads();
-    if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
-    __syncthreads();
-    float* slot = a.huge_part + (size_t)c * u.d;
-    if (grp == 0 && col_ok) {
-      f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
+  const int d4 = u.d >> 2;
+  const int bag_lo = g * group_bags;
+  const int bag_hi = bag_lo + group_bags < a.B ? bag_lo + group_bags : a.B;
+  const float* gk = u.dS + (int64_t)k * u.stride_k;
+  for (uint32_t r0 = 0; r0 < nruns; r0 += kNW * MR) {  // uniform
+    uint32_t cur[MR], end[MR];
+    const uint32_t* bags[MR];
+    f32x4 acc[MR];
 #pragma unroll
-      for (int s = 0; s < NG; ++s) tot += loadf4(part + s * (G * 4) + chunk * 4);
-      storef4(slot + chunk * 4, tot);
-    }
-    // the chunk that finishes last adds the run's partials in chunk order and updates the row
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) ticket = atomicAdd(&a.huge_runs[lo].done, 1u);
-    __syncthreads();
-    if (ticket == hr.nchunks - 1) {
-      __threadfence();
-      if (grp == 0 && col_ok) {
-        f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
-        const float* p = a.huge_part + (size_t)hr.chunk_base * u.d + chunk * 4;
-        for (uint32_t j = 0; j < hr.nchunks; ++j) tot += loadf4(p + (size_t)j * u.d);
-        sgd_row_update<DT>(static_cast<char*>(u.tables[hr.k]), u, hr.row, chunk, tot);
+    for (int i = 0; i < MR; ++i) {
+      const uint32_t r = r0 + w + kNW * i;
+      acc[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      cur[i] = end[i] = 0;
+      bags[i] = a.vals[0];
+      if (r < nruns) {  // wave-uniform
+        const HugeRun hr = a.huge_runs[base + r];
+        bags[i] = hr.src ? a.vals[1] : a.vals[0];
+        end[i] = hr.start + hr.len;
+        // first entry whose bag is >= bag_lo: 64-ary search over the sorted bags of the run
+        uint32_t lo = hr.start, hi = end[i];
+        while (lo < hi) {
+          const uint32_t step = (hi - lo + DLRM_WAVE - 1) / DLRM_WAVE;
+          const uint32_t q = lo + lane * step;
+          const bool less = q < hi && bags[i][q] < (uint32_t)bag_lo;
+          const uint32_t cnt = (uint32_t)__popcll(__ballot(less));  // sorted: the first cnt probes
+          if (cnt == 0) break;
+          const uint32_t nhi = lo + cnt * step < hi ? lo + cnt * step : hi;
+          lo = lo + (cnt - 1) * step + 1;
+          hi = nhi;
+        }
+        cur[i] = lo;
       }
     }
-    __syncthreads();
+    for (int tb0 = bag_lo; tb0 < bag_hi; tb0 += tile_bags) {  // uniform
+      const int tb1 = tb0 + tile_bags < bag_hi ? tb0 + tile_bags : bag_hi;
+      __syncthreads();  // the previous tile has been consumed
+      for (int idx = tid; idx < (tb1 - tb0) * d4; idx += kThreads) {
+        const int bb = idx / d4, c4 = idx - bb * d4;
+        storef4(tile + bb * u.d + c4 * 4, loadf4(gk + (int64_t)(tb0 + bb) * u.stride_b + c4 * 4));
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < MR; ++i) {
+        while (cur[i] < end[i]) {  // wave-uniform
+          const uint32_t nav = end[i] - cur[i] < (uint32_t)DLRM_WAVE ? end[i] - cur[i] : (uint32_t)DLRM_WAVE;
+          const uint32_t bag = (uint32_t)lane < nav ? bags[i][cur[i] + lane] : 0xFFFFFFFFu;
+          const uint32_t cnt = (uint32_t)__popcll(__ballot(bag < (uint32_t)tb1));
+          for (uint32_t e = 0; e < cnt; e += S) {
+            const uint32_t idx = e + slot;
+            const uint32_t bb = __shfl(bag, (int)(idx & (DLRM_WAVE - 1)), DLRM_WAVE);
+            if (idx < cnt && col_ok) acc[i] += loadf4(tile + (bb - (uint32_t)tb0) * u.d + chunk * 4);
+          }
+          cur[i] += cnt;
+          if (cnt < (uint32_t)DLRM_WAVE) break;
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < MR; ++i) {
+      const uint32_t r = r0 + w + kNW * i;
+      if (r >= nruns) continue;  // wave-uniform
+      f32x4 tot = acc[i];
+#pragma unroll
+      for (int o = G; o < DLRM_WAVE; o <<= 1) {
+        tot.x += __shfl_xor(tot.x, o, DLRM_WAVE);
+        tot.y += __shfl_xor(tot.y, o, DLRM_WAVE);
+        tot.z += __shfl_xor(tot.z, o, DLRM_WAVE);
+        tot.w += __shfl_xor(tot.w, o, DLRM_WAVE);
+      }
+      float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d;
+      if (slot == 0 && col_ok) storef4(part + (size_t)g * u.d + chunk * 4, tot);
+      __threadfence();
+      uint32_t ticket = 0;
+      if (lane == 0) ticket = atomicAdd(&a.huge_runs[base + r].done, 1u);
+      ticket = __shfl(ticket, 0, DLRM_WAVE);
+      if (ticket == (uint32_t)ngroups - 1u) {  // every bag group of this run is in: finish it
+        __threadfence();
+        if (slot == 0 && col_ok) {
+          f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+          for (int gg = 0; gg < ngroups; ++gg) sum += loadf4(part + (size_t)gg * u.d + chunk * 4);
+          sgd_row_update<DT>(static_cast<char*>(u.tables[k]), u, a.huge_runs[base + r].row, chunk, sum);
+        }
+      }
+    }
   }
 }
 
@@ -1359,7 +1430,7 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.seg_start = reinterpret_cast<uint32_t*>(base + L.seg_start);
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
-  g.huge_ctr = reinterpret_cast<unsigned long long*>(base + L.huge_ctr);
+  g.hot_cnt = reinterpret_cast<uint32_t*>(base + L.hot_cnt);
   g.over_cnt = reinterpret_cast<uint32_t*>(base + L.huge_ctr + 8);
   g.over_list = reinterpret_cast<uint32_t*>(base + L.over_list);
   g.segs = reinterpret_cast<SegInfo*>(base + L.segs);
@@ -1402,7 +1473,8 @@ static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_
   DLRM_CHECK_LAUNCH();
   hipLaunchKernelGGL((segment_reduce_kernel<DT, G>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
-  hipLaunchKernelGGL((huge_runs_kernel<DT, G>), dim3(1024), dim3(kThreads), 0, st, g, u);
+  const int tb = hot_tile_bags(u.d), gb = tb * kHotTilesPerGroup, ng = hot_groups(g.B, u.d);
+  hipLaunchKernelGGL((hot_rows_kernel<DT, G>), dim3(ng, K), dim3(kThreads), 0, st, g, u, tb, gb, ng);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
@@ -1431,7 +1503,7 @@ static int launch_atomic(const AtomArgs& a, hipStream_t st) {
 }
 
 static int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout* L) {
-  *L = ws_layout(s->K, s->d, s->nnz_total);
+  *L = ws_layout(s->K, s->B, s->d, s->nnz_total);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || bytes < L->total) return DLRM_ERR_WORKSPACE;
   if (L->nt_max > 0x7FFFFFFF || ((int64_t)s->K << kMaxTopBits) > 0x7FFFFFFF) return DLRM_ERR_BAD_SHAPE;
   return DLRM_OK;
@@ -1453,7 +1525,7 @@ extern "C" size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t
   if (K < 1 || B < 1 || d < 1 || nnz_total < 0 || nnz_total > DLRM_MAX_NNZ || max_rows < 1 ||
       max_rows > DLRM_MAX_ROWS || !dtype_ok(table_dtype))
     return 0;
-  return ws_layout(K, d, nnz_total).total;
+  return ws_layout(K, B, d, nnz_total).total;
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
