@@ -41,7 +41,7 @@ constexpr int kLongRun = 32;                    // longer runs are summed by the
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
 constexpr int kHotTileFloats = 16384;            // 64 KB of LDS: gradient rows of one bag tile
 constexpr int kHotTilesPerGroup = 8;            // bag tiles streamed by one workgroup
-constexpr int kHotRunsPerWave = 4;              // hot runs a wavefront accumulates at once
+constexpr int kHotRunsPerWave = 8;              // hot runs a wavefront accumulates at once
 constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatter below this
 constexpr int kSegMaxBits = 13;                 // oversized buckets with at most this many low bits are
                                                 // sorted by many workgroups (per-row counters in LDS)
@@ -1136,6 +1136,7 @@ template <int DT, int G>
 __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int tile_bags,
                                                             int group_bags, int ngroups) {
   __shared__ float tile[kHotTileFloats];
+  __shared__ uint32_t wbag[kNW][256];
   constexpr int S = DLRM_WAVE / G;
   constexpr int MR = kHotRunsPerWave;
   const int k = blockIdx.y, g = blockIdx.x;
@@ -1189,16 +1190,27 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
 #pragma unroll
       for (int i = 0; i < MR; ++i) {
         while (cur[i] < end[i]) {  // wave-uniform
-          const uint32_t nav = end[i] - cur[i] < (uint32_t)DLRM_WAVE ? end[i] - cur[i] : (uint32_t)DLRM_WAVE;
-          const uint32_t bag = (uint32_t)lane < nav ? bags[i][cur[i] + lane] : 0xFFFFFFFFu;
-          const uint32_t cnt = (uint32_t)__popcll(__ballot(bag < (uint32_t)tb1));
-          for (uint32_t e = 0; e < cnt; e += S) {
-            const uint32_t idx = e + slot;
-            const uint32_t bb = __shfl(bag, (int)(idx & (DLRM_WAVE - 1)), DLRM_WAVE);
-            if (idx < cnt && col_ok) acc[i] += loadf4(tile + (bb - (uint32_t)tb0) * u.d + chunk * 4);
+          // window of up to 256 entries of the run: 4 coalesced loads, parked in this wave's LDS
+          const uint32_t left = end[i] - cur[i];
+          uint32_t cnt = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t p = (uint32_t)(j * DLRM_WAVE + lane);
+            const uint32_t bag = p < left ? bags[i][cur[i] + p] : 0xFFFFFFFFu;
+            wbag[w][p] = bag;
+            cnt += (uint32_t)__popcll(__ballot(bag < (uint32_t)tb1));  // sorted: a prefix of the window
+          }
+          for (uint32_t e = 0; e < cnt; e += 2 * S) {
+            const uint32_t i0 = e + slot, i1 = e + S + slot;
+            const uint32_t b0 = wbag[w][i0 & 255u], b1 = wbag[w][i1 & 255u];
+            f32x4 v0 = {0.0f, 0.0f, 0.0f, 0.0f}, v1 = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (i0 < cnt && col_ok) v0 = loadf4(tile + (b0 - (uint32_t)tb0) * u.d + chunk * 4);
+            if (i1 < cnt && col_ok) v1 = loadf4(tile + (b1 - (uint32_t)tb0) * u.d + chunk * 4);
+            acc[i] += v0;
+            acc[i] += v1;
           }
           cur[i] += cnt;
-          if (cnt < (uint32_t)DLRM_WAVE) break;
+          if (cnt < 256u) break;
         }
       }
     }
@@ -1216,12 +1228,21 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
       }
       float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d;
       if (slot == 0 && col_ok) storef4(part + (size_t)g * u.d + chunk * 4, tot);
-      __threadfence();
+    }
+    // one release fence per workgroup (it writes back the whole L2 slice: keep them rare), then
+    // a ticket per run; the bag group that arrives last adds the run's partials in group order
+    __threadfence();
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MR; ++i) {
+      const uint32_t r = r0 + w + kNW * i;
+      if (r >= nruns) continue;  // wave-uniform
       uint32_t ticket = 0;
       if (lane == 0) ticket = atomicAdd(&a.huge_runs[base + r].done, 1u);
       ticket = __shfl(ticket, 0, DLRM_WAVE);
-      if (ticket == (uint32_t)ngroups - 1u) {  // every bag group of this run is in: finish it
+      if (ticket == (uint32_t)ngroups - 1u) {
         __threadfence();
+        const float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d;
         if (slot == 0 && col_ok) {
           f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
           for (int gg = 0; gg < ngroups; ++gg) sum += loadf4(part + (size_t)gg * u.d + chunk * 4);
