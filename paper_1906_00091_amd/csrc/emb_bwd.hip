@@ -40,12 +40,17 @@ constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size
 constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
 constexpr int kHotTileFloats = 16384;            // 64 KB of LDS: gradient rows of one bag tile
+constexpr int kHotZeroRow = 256;                // floats of the widest gradient row
+constexpr int kHotStagePasses = 16;             // float4 registers per thread holding the next tile
 constexpr int kHotTilesPerGroup = 8;            // bag tiles streamed by one workgroup
 constexpr int kHotRunsPerWave = 8;              // hot runs a wavefront accumulates at once
 constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatter below this
 constexpr int kSegMaxBits = 13;                 // oversized buckets with at most this many low bits are
                                                 // sorted by many workgroups (per-row counters in LDS)
 constexpr int kSegKeys = 1 << kSegMaxBits;
+constexpr int kCandMin = 128;                   // a row with this many of an oversized bucket's first
+                                                // kBktCap pairs is split off before any sorting
+constexpr int kCand = kBktCap / kCandMin;       // at most this many such rows
 
 // ---------------------------------------------------------------------------
 // Workspace layout (all offsets 256-byte aligned)
@@ -61,7 +66,7 @@ struct WsLayout {
   size_t hot_cnt;            // uint32[K]: queued hot runs per table
   size_t over_list;          // uint32[nnz / kBktCap + 1]: buckets too large for the LDS sort
   size_t segs;               // SegInfo[nnz / kBktCap + 2]: those of them sorted by many workgroups
-  size_t seg_meta;           // uint32[8]: nseg, ntiles, scatter tickets
+  size_t seg_meta;           // uint32[8]: segment tiles, segments
   size_t huge_runs;          // HugeRun[nnz / kHugeRun + K]: table k's list starts at sum_{j<k}(nnz_j/kHugeRun + 1)
   size_t huge_part;          // float[max_runs * bag groups * d]
   size_t total;
@@ -71,19 +76,22 @@ struct WsLayout {
 
 struct SegInfo {
   uint32_t start, n, k, low_bits;   // an oversized bucket: global position, pairs, table, unsorted bits
-  uint32_t tile0, pad0, pad1, pad2;  // index of its first kBktCap-position tile among all segments
+  uint32_t tile0, src, pad1, pad2;   // index of its first kBktCap-position tile among all segments;
+                                     // pair buffer holding the unsorted pairs
 };
 
 struct HugeRun {
   uint32_t k, row, start, len;   // start: global position of the run's first sorted entry
-  uint32_t done, src, pad0, pad1; // done: bag groups finished; src: pair buffer holding the run
+  uint32_t pad0, src, pad1, pad2; // src: pair buffer holding the run
 };
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-static inline int hot_tile_bags(int d) { return kHotTileFloats / d; }
+// bags whose gradient rows one hot-row workgroup streams: kHotTilesPerGroup tiles of
+// kHotStagePasses passes of kThreads / G rows (G lanes per row)
+static inline int hot_group_bags(int d) { return kThreads / pow2_ceil(d / 4) * kHotStagePasses * kHotTilesPerGroup; }
 static inline int hot_groups(int B, int d) {
-  const int gb = hot_tile_bags(d) * kHotTilesPerGroup;
+  const int gb = hot_group_bags(d);
   return (B + gb - 1) / gb;
 }
 
@@ -136,7 +144,7 @@ struct GroupArgs {            // everything the grouping kernels need
   int32_t max_over;           // workgroups reserved at the front of the bucket grid for oversized buckets
   SegInfo* segs;
   int32_t seg_tiles_max;      // upper bound on the number of segment tiles
-  uint32_t* seg_meta;         // [0] nseg, [1] ntiles, [2] scatter-done tickets
+  uint32_t* seg_meta;         // [0] segment tiles, [1] segments (one 64-bit counter)
   HugeRun* huge_runs;
   float* huge_part;
 };
@@ -360,15 +368,16 @@ __device__ inline void prepare_segments(const GroupArgs& a, uint32_t* smem) {
     const uint32_t tpos = block_exclusive_scan<kThreads>(nt, smem, &tot_t);
     if (ok) {
       sg.tile0 = ntiles + tpos;
-      sg.pad0 = sg.pad1 = sg.pad2 = 0;
+      sg.src = 1;
+      sg.pad1 = sg.pad2 = 0;
       a.segs[nseg + slot] = sg;
     }
     nseg += tot_s;
     ntiles += tot_t;
   }
   if (threadIdx.x == 0) {
-    a.seg_meta[0] = nseg;
-    a.seg_meta[1] = ntiles;
+    a.seg_meta[0] = ntiles;
+    a.seg_meta[1] = nseg;
   }
 }
 
@@ -587,12 +596,12 @@ struct SortLds {
 
 __device__ inline int pass_bits(int left, int passes_left) { return (left + passes_left - 1) / passes_left; }
 
-// Buckets of at most kBktCap pairs: stable LSD passes entirely in LDS.  The pairs end up in
-// s.skey / s.sval in (row, position) order.
-__device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, SortLds& s) {
+// Buckets of at most kBktCap pairs (read from pair buffer src): stable LSD passes entirely in
+// LDS.  The pairs end up in s.skey / s.sval in (row, position) order.
+__device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, SortLds& s, int src = 1) {
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
-  const uint32_t* kin = a.keys[1] + b.start;
-  const uint32_t* vin = a.vals[1] + b.start;
+  const uint32_t* kin = a.keys[src] + b.start;
+  const uint32_t* vin = a.vals[src] + b.start;
   const int n = (int)b.n;
   uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
   bool ok[kBktItems];
@@ -655,11 +664,12 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
 }
 
 // Larger buckets: the same stable passes, one workgroup streaming its bucket through global
-// memory (ping-pong between the two pair buffers).  Returns the buffer holding the result.
-__device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, SortLds& s) {
+// memory (ping-pong between the two pair buffers, starting in buffer src).  Returns the buffer
+// holding the result.
+__device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, SortLds& s, int src = 1) {
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
   const int passes = (b.low_bits + kSortBits - 1) / kSortBits;
-  int src = 1, shift = 0;
+  int shift = 0;
   for (int p = 0; p < passes; ++p) {
     const int bits = pass_bits(b.low_bits - shift, passes - p);
     const int nb = 1 << bits;
@@ -860,9 +870,8 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
         hr.row = keys[i0];
         hr.start = b.start + h0 + i0;
         hr.len = len;
-        hr.done = 0;
         hr.src = (uint32_t)src;
-        hr.pad0 = hr.pad1 = 0;
+        hr.pad0 = hr.pad1 = hr.pad2 = 0;
         a.huge_runs[hot_list_base(a, b.k) + atomicAdd(&a.hot_cnt[b.k], 1u)] = hr;
       }
       continue;
@@ -967,12 +976,199 @@ __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const
   __syncthreads();
 }
 
+// --- 4a. oversized buckets: dominant rows split off first ------------------------------------------
+// A bucket outgrows the LDS sort almost always because a few hot rows own most of its pairs.
+// Rows holding at least kCandMin of the bucket's first kBktCap pairs become candidates (at most
+// kCand = kBktCap / kCandMin of them).  One count pass and one stable partition pass over the
+// bucket then give every candidate its own list (position order is kept, so its bags ascend) and
+// collect the rest behind them; no pair of a candidate is ever sorted.  The rest usually fits
+// the LDS sort; if not, it alone goes to the segment kernels or the streaming sort.
+struct SplitLds {
+  uint32_t cand[kCand];       // candidate row ids, in row order; unused slots 0xFFFFFFFF
+  uint32_t cnt[kCand + 1];    // pairs per class; class kCand = every other row
+  uint32_t cbase[kCand + 2];  // exclusive prefix of cnt
+  uint32_t nc;
+};
+
+__device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd) {
+  uint32_t cls = (uint32_t)kCand;
+#pragma unroll
+  for (int c = 0; c < kCand; ++c) cls = key == cd[c] ? (uint32_t)c : cls;
+  return cls;
+}
+
+// Pairs [bk.start, bk.start + bk.n) of pair buffer src, more than kBktCap of them, that no
+// shortcut applies to: queued as a segment when per-row counters fit LDS, else sorted here.
 template <int DT, int G>
-__global__ __launch_bounds__(kThreads) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
+__device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, const Bucket& bk, char* W,
+                                         int src, SortLds& s, float* part) {
+  if (bk.low_bits <= kSegMaxBits) {
+    if (threadIdx.x == 0) {
+      const uint32_t nt = (bk.n + kBktCap - 1) / kBktCap;
+      // one 64-bit counter hands out the slot and the first tile together, so that the list is
+      // ordered by first tile
+      const unsigned long long old =
+          atomicAdd(reinterpret_cast<unsigned long long*>(a.seg_meta), (1ull << 32) | (unsigned long long)nt);
+      SegInfo sg;
+      sg.start = bk.start;
+      sg.n = bk.n;
+      sg.k = (uint32_t)bk.k;
+      sg.low_bits = (uint32_t)bk.low_bits;
+      sg.tile0 = (uint32_t)old;
+      sg.src = (uint32_t)src;
+      sg.pad1 = sg.pad2 = 0;
+      a.segs[(uint32_t)(old >> 32)] = sg;
+    }
+    return;
+  }
+  const int res = sort_bucket_global(a, bk, s, src);
+  __syncthreads();
+  const uint32_t* keys = a.keys[res] + bk.start;
+  const uint32_t* bags = a.vals[res] + bk.start;
+  for (uint32_t w0 = 0; w0 < bk.n; w0 += kBktCap) reduce_window<DT, G>(a, u, bk, W, keys, bags, w0, res, s, part);
+}
+
+template <int DT, int G>
+__device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
+                                        SortLds& s, SplitLds& sp, float* part) {
+  const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
+  // ---- candidates: long runs among the first kBktCap pairs
+  if (tid < kCand) sp.cand[tid] = 0xFFFFFFFFu;
+  if (tid < kCand + 1) sp.cnt[tid] = 0;
+  {
+    Bucket head = b;
+    head.n = (uint32_t)kBktCap;
+    sort_bucket_lds(a, head, s, 1);
+    const uint32_t nruns = compact_heads_lds(s, kBktCap);
+    uint32_t flags = 0, c = 0;
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {  // thread t owns runs [t*kBktItems, (t+1)*kBktItems): row order
+      const uint32_t r = (uint32_t)(tid * kBktItems + j);
+      if (r < nruns && s.heads[r + 1] - s.heads[r] >= (uint32_t)kCandMin) {
+        flags |= 1u << j;
+        ++c;
+      }
+    }
+    uint32_t total;
+    uint32_t pos = block_exclusive_scan<kThreads>(c, s.smem, &total);
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j)
+      if (flags & (1u << j)) sp.cand[pos++] = s.skey[s.heads[tid * kBktItems + j]];
+    if (tid == 0) sp.nc = total;
+  }
+  __syncthreads();
+  const uint32_t nc = sp.nc;
+  if (nc == 0) {  // uniform
+    sort_reduce_large<DT, G>(a, u, b, W, 1, s, part);
+    return;
+  }
+  uint32_t cd[kCand];
+#pragma unroll
+  for (int c = 0; c < kCand; ++c) cd[c] = sp.cand[c];
+  const uint32_t* kin = a.keys[1] + b.start;
+  const uint32_t* vin = a.vals[1] + b.start;
+  // ---- pass 1: pairs per class.  A wavefront's lanes mostly agree (the dominant row): those
+  // that agree with the first valid lane are counted with one LDS atomic
+  for (uint32_t i0 = 0; i0 < b.n; i0 += kThreads * 8) {
+    uint32_t kk[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t i = i0 + q * kThreads + tid;
+      kk[q] = kin[i < b.n ? i : b.n - 1];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t i = i0 + q * kThreads + tid;
+      const bool valid = i < b.n;
+      const uint32_t cls = class_of(kk[q], cd);
+      const unsigned long long vm = __ballot(valid);
+      if (vm == 0ull) continue;  // wave-uniform
+      const int first = __ffsll((long long)vm) - 1;
+      const uint32_t c0 = __shfl(cls, first, DLRM_WAVE);
+      const unsigned long long same = __ballot(valid && cls == c0);
+      if (lane == first) atomicAdd(&sp.cnt[c0], (uint32_t)__popcll(same));
+      if (valid && cls != c0) atomicAdd(&sp.cnt[cls], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t run = 0;
+    for (int c = 0; c <= kCand; ++c) {
+      sp.cbase[c] = run;
+      run += sp.cnt[c];
+    }
+    sp.cbase[kCand + 1] = run;
+  }
+  __syncthreads();
+  // ---- pass 2: stable partition by class into pair buffer 0, tiles in order.  Candidate lists
+  // keep only the bags (plus the row id at their first position); the rest keeps (row, bag).
+  uint32_t* kout = a.keys[0] + b.start;
+  uint32_t* vout = a.vals[0] + b.start;
+  constexpr int kClsBits = 5;
+  static_assert(kCand + 1 <= (1 << kClsBits), "class ids must fit the ranking digit");
+  if (tid < (1 << kClsBits)) s.base[tid] = tid <= kCand ? sp.cbase[tid] : 0u;
+  __syncthreads();
+  for (uint32_t t0 = 0; t0 < b.n; t0 += kBktCap) {
+    const int cnt = (int)(b.n - t0 < (uint32_t)kBktCap ? b.n - t0 : (uint32_t)kBktCap);
+    uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
+    bool ok[kBktItems];
+    for (int i = tid; i < kNW * kSortBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+      ok[j] = li < cnt;
+      key[j] = ok[j] ? kin[t0 + li] : 0xFFFFFFFFu;
+      val[j] = ok[j] ? vin[t0 + li] : 0u;
+      dg[j] = class_of(key[j], cd);
+    }
+    __syncthreads();
+    rank_items<kBktItems, kSortBuckets>(dg, ok, kClsBits, s.wcnt, rnk);
+    __syncthreads();
+    uint32_t lofs, tot;
+    digit_offsets<kSortBuckets>(1 << kClsBits, s.wcnt, s.smem, &lofs, &tot);
+    if (tid < (1 << kClsBits)) s.heads[tid] = lofs;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kBktItems; ++j) {
+      if (ok[j]) {
+        const uint32_t dst = s.base[dg[j]] + (s.wcnt[w][dg[j]] - s.heads[dg[j]]) + rnk[j];
+        vout[dst] = val[j];
+        if (dg[j] == (uint32_t)kCand) kout[dst] = key[j];
+      }
+    }
+    __syncthreads();
+    if (tid < (1 << kClsBits)) s.base[tid] += tot;
+    __syncthreads();
+  }
+  if ((uint32_t)tid < nc) kout[sp.cbase[tid]] = sp.cand[tid];
+  if ((uint32_t)tid <= nc) s.heads[tid] = sp.cbase[tid];
+  __syncthreads();
+  // ---- candidate lists are runs: short ones summed here, those above kHugeRun queued as hot rows
+  {
+    const uint32_t nlong = collect_long_runs(s, nc);
+    reduce_runs<DT, G>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
+  }
+  // ---- the rest
+  Bucket rest = b;
+  rest.start = b.start + sp.cbase[kCand];
+  rest.n = sp.cnt[kCand];
+  __syncthreads();
+  if (rest.n == 0) return;  // uniform
+  if (rest.n > (uint32_t)kBktCap) {
+    sort_reduce_large<DT, G>(a, u, rest, W, 0, s, part);
+    return;
+  }
+  sort_bucket_lds(a, rest, s, 0);
+  const uint32_t nruns = compact_heads_lds(s, (int)rest.n);
+  const uint32_t nlong = collect_long_runs(s, nruns);
+  reduce_runs<DT, G>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
+}
+
+template <int DT, int G>
+__global__ __launch_bounds__(kThreads, 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
+  __shared__ SplitLds sp;
   __shared__ float part[kThreads * 4];
-  // workgroup 0 (always a front workgroup) also builds the segment list for the next launch
-  if (blockIdx.x == 0) prepare_segments(a, s.smem);
   uint32_t bid;
   bool oversized;
   if (!bucket_id_of_block(a, &bid, &oversized)) return;
@@ -997,18 +1193,12 @@ __global__ __launch_bounds__(kThreads) void bucket_reduce_kernel(GroupArgs a, Up
                        part);
     return;
   }
-  if (b.low_bits <= kSegMaxBits) return;  // sorted and reduced by the segment kernels
-  // many unsorted bits: this workgroup sorts the bucket alone, through global memory
-  const int src = sort_bucket_global(a, b, s);
-  __syncthreads();
-  const uint32_t* keys = a.keys[src] + b.start;
-  const uint32_t* bags = a.vals[src] + b.start;
-  for (uint32_t w0 = 0; w0 < b.n; w0 += kBktCap) reduce_window<DT, G>(a, u, b, W, keys, bags, w0, src, s, part);
+  reduce_oversized<DT, G>(a, u, b, W, s, sp, part);
 }
 
 // --- 4c. oversized buckets ("segments") sorted by one workgroup per tile ------------------------
 __device__ inline bool find_segment_tile(const GroupArgs& a, SegInfo* sg, uint32_t* t) {
-  const uint32_t nseg = a.seg_meta[0], ntiles = a.seg_meta[1];
+  const uint32_t ntiles = a.seg_meta[0], nseg = a.seg_meta[1];
   if (blockIdx.x >= ntiles) return false;
   uint32_t lo = 0, hi = nseg;  // segs[lo].tile0 <= tile < segs[hi].tile0
   while (hi - lo > 1) {
@@ -1023,7 +1213,7 @@ __device__ inline bool find_segment_tile(const GroupArgs& a, SegInfo* sg, uint32
 // Every workgroup counts, per row of the segment, the pairs in the tiles before its own and in
 // the whole segment (the segment's keys stream through L2), sorts its own tile in LDS, and
 // writes each pair to  segment start + rows before + same row in earlier tiles + rank in tile:
-// the segment ends up fully sorted by (row, position) in pair buffer 0.
+// the segment ends up fully sorted by (row, position) in the other pair buffer.
 __global__ __launch_bounds__(kThreads) void segment_sort_kernel(GroupArgs a) {
   __shared__ SortLds s;
   __shared__ uint32_t before[kSegKeys];
@@ -1040,7 +1230,7 @@ __global__ __launch_bounds__(kThreads) void segment_sort_kernel(GroupArgs a) {
     base[i] = 0;
   }
   __syncthreads();
-  const uint32_t* kin = a.keys[1] + sg.start;
+  const uint32_t* kin = a.keys[sg.src] + sg.start;
   for (uint32_t i0 = 0; i0 < sg.n; i0 += kThreads * 8) {  // 8 loads in flight per thread
     uint32_t kk[8];
 #pragma unroll
@@ -1091,9 +1281,9 @@ __global__ __launch_bounds__(kThreads) void segment_sort_kernel(GroupArgs a) {
   tb.start = sg.start + tstart;
   tb.n = cnt;
   tb.low_bits = (int)sg.low_bits;
-  sort_bucket_lds(a, tb, s);
-  uint32_t* kout = a.keys[0] + sg.start;
-  uint32_t* vout = a.vals[0] + sg.start;
+  sort_bucket_lds(a, tb, s, (int)sg.src);
+  uint32_t* kout = a.keys[sg.src ^ 1u] + sg.start;
+  uint32_t* vout = a.vals[sg.src ^ 1u] + sg.start;
   for (uint32_t p = tid; p < cnt; p += kThreads) {
     const uint32_t key = s.skey[p];
     uint32_t lo = 0, hi = p;  // first position of this key in the sorted tile
@@ -1121,96 +1311,171 @@ __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, U
   b.n = sg.n;
   b.low_bits = 0;
   char* W = static_cast<char*>(u.tables[b.k]);
-  reduce_window<DT, G>(a, u, b, W, a.keys[0] + sg.start, a.vals[0] + sg.start, t * kBktCap, 0, s, part);
+  const int dst = (int)(sg.src ^ 1u);
+  reduce_window<DT, G>(a, u, b, W, a.keys[dst] + sg.start, a.vals[dst] + sg.start, t * kBktCap, dst, s, part);
 }
 
 // --- 5. hot rows: runs too long for one workgroup -------------------------------------------------
 // A hot row is looked up by a large share of the bags, so summing its run entry by entry would
 // fetch nearly the whole gradient slice dS[:, k, :] once per hot row.  Instead workgroup (g, k)
-// streams the gradient rows of bag group g of table k through LDS ONCE, tile by tile, and every
-// wavefront adds, for each of its hot runs, the rows of the run's entries whose bag lies in the
-// tile (a run's bags are sorted, so a cursor per run only moves forward).  Partial sums per
-// (run, bag group) go to global memory; the group that finishes a run last adds them in group
-// order and updates the row (fence + counter, nobody waits).
+// streams the gradient rows of bag group g of table k through LDS ONCE, tile by tile (the next
+// tile travels in registers while the current one is consumed), and every wavefront adds, for
+// each of its hot runs, the rows of the run's entries whose bag lies in the tile.  A run's bags
+// ascend, so binary searches give its entry range per tile, and equal neighbours (a bag that
+// looks the row up several times) are folded into one LDS read times a multiplicity.  Partial
+// sums per (run, bag group) go to global memory; hot_finish_kernel adds them in group order.
+
+// Entry e + slot of the 64 values the lanes hold in `v` (e: uniform).  Few slots: scalar lane
+// reads and selects, no LDS round trip; many slots: a lane permute.
+template <int S>
+__device__ inline uint32_t lane_entry(uint32_t v, uint32_t e, int slot) {
+  if constexpr (S <= 4) {
+    uint32_t r = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)(e & 63u));
+#pragma unroll
+    for (int sl = 1; sl < S; ++sl) {
+      const uint32_t o = (uint32_t)__builtin_amdgcn_readlane((int)v, (int)((e + sl) & 63u));
+      r = slot == sl ? o : r;
+    }
+    return r;
+  } else {
+    return (uint32_t)__shfl((int)v, (int)((e + (uint32_t)slot) & 63u), DLRM_WAVE);
+  }
+}
+
 template <int DT, int G>
-__global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int tile_bags,
-                                                            int group_bags, int ngroups) {
-  __shared__ float tile[kHotTileFloats];
-  __shared__ uint32_t wbag[kNW][256];
+__global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int ngroups) {
   constexpr int S = DLRM_WAVE / G;
   constexpr int MR = kHotRunsPerWave;
+  constexpr int NT = kHotTilesPerGroup;
+  constexpr int HU = S <= 8 ? 8 : DLRM_WAVE / S;  // HU * S entries per round, never past the 64 held
+  constexpr int NG = kThreads / G;                // gradient rows staged per pass of the workgroup
+  constexpr int NP = kHotStagePasses;
+  constexpr int TB = NG * NP;                     // bags per tile: TB * d <= kHotTileFloats
+  constexpr int GB = TB * NT;                     // bags per workgroup
+  __shared__ float tile[kHotTileFloats + kHotZeroRow];  // gradient rows of a bag tile, then a row of zeros
+  __shared__ uint32_t cursor[kNW * MR][NT + 1];  // first entry of a run at or after every tile boundary
+  __shared__ uint32_t rsrc[kNW * MR];            // pair buffer holding the run
+  __shared__ uint32_t wsc[kNW][DLRM_WAVE];       // per wavefront: compacted (offset, multiplicity) words
   const int k = blockIdx.y, g = blockIdx.x;
   const uint32_t nruns = a.hot_cnt[k];
   if (nruns == 0) return;  // uniform
   const uint32_t base = hot_list_base(a, k);
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
   const int slot = lane / G, chunk = lane % G;
+  const int grp = tid / G;
   const bool col_ok = chunk * 4 < u.d;
-  const int d4 = u.d >> 2;
-  const int bag_lo = g * group_bags;
-  const int bag_hi = bag_lo + group_bags < a.B ? bag_lo + group_bags : a.B;
-  const float* gk = u.dS + (int64_t)k * u.stride_k;
+  const int cchunk = col_ok ? chunk : 0;  // lanes past the last column shadow column group 0, never store
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  const int bag_lo = g * GB;
+  const int bag_hi = bag_lo + GB < a.B ? bag_lo + GB : a.B;
+  const float* gk = u.dS + (int64_t)k * u.stride_k + cchunk * 4;
+  for (int i = tid; i < kHotZeroRow; i += kThreads) tile[kHotTileFloats + i] = 0.0f;
   for (uint32_t r0 = 0; r0 < nruns; r0 += kNW * MR) {  // uniform
-    uint32_t cur[MR], end[MR];
+    __syncthreads();
+    for (int task = tid; task < kNW * MR * (NT + 1); task += kThreads) {
+      const int rl = task / (NT + 1), tb = task - rl * (NT + 1);
+      const uint32_t r = r0 + (uint32_t)rl;
+      uint32_t c = 0;
+      if (r < nruns) {
+        const HugeRun hr = a.huge_runs[base + r];
+        const uint32_t* bags = (hr.src ? a.vals[1] : a.vals[0]) + hr.start;
+        const int bnd = bag_lo + tb * TB;
+        const uint32_t bound = (uint32_t)(bnd < bag_hi ? bnd : bag_hi);
+        uint32_t lo = 0, hi = hr.len;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (bags[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+        c = hr.start + lo;
+        if (tb == 0) rsrc[rl] = hr.src;
+      }
+      cursor[rl][tb] = c;
+    }
+    __syncthreads();
     const uint32_t* bags[MR];
     f32x4 acc[MR];
 #pragma unroll
     for (int i = 0; i < MR; ++i) {
-      const uint32_t r = r0 + w + kNW * i;
+      const int rl = w + kNW * i;
       acc[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-      cur[i] = end[i] = 0;
-      bags[i] = a.vals[0];
-      if (r < nruns) {  // wave-uniform
-        const HugeRun hr = a.huge_runs[base + r];
-        bags[i] = hr.src ? a.vals[1] : a.vals[0];
-        end[i] = hr.start + hr.len;
-        // first entry whose bag is >= bag_lo: 64-ary search over the sorted bags of the run
-        uint32_t lo = hr.start, hi = end[i];
-        while (lo < hi) {
-          const uint32_t step = (hi - lo + DLRM_WAVE - 1) / DLRM_WAVE;
-          const uint32_t q = lo + lane * step;
-          const bool less = q < hi && bags[i][q] < (uint32_t)bag_lo;
-          const uint32_t cnt = (uint32_t)__popcll(__ballot(less));  // sorted: the first cnt probes
-          if (cnt == 0) break;
-          const uint32_t nhi = lo + cnt * step < hi ? lo + cnt * step : hi;
-          lo = lo + (cnt - 1) * step + 1;
-          hi = nhi;
-        }
-        cur[i] = lo;
+      bags[i] = (r0 + (uint32_t)rl < nruns && rsrc[rl]) ? a.vals[1] : a.vals[0];
+    }
+    // staging registers: row p*NG + grp of a tile, this lane's 4 columns (rows past the tile's
+    // end repeat its last row and are never stored)
+    f32x4 stage[NP];
+    {
+      const int nb = bag_hi - bag_lo < TB ? bag_hi - bag_lo : TB;
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const int bb = p * NG + grp < nb ? p * NG + grp : nb - 1;
+        stage[p] = loadf4(gk + (int64_t)(bag_lo + bb) * u.stride_b);
       }
     }
-    for (int tb0 = bag_lo; tb0 < bag_hi; tb0 += tile_bags) {  // uniform
-      const int tb1 = tb0 + tile_bags < bag_hi ? tb0 + tile_bags : bag_hi;
-      __syncthreads();  // the previous tile has been consumed
-      for (int idx = tid; idx < (tb1 - tb0) * d4; idx += kThreads) {
-        const int bb = idx / d4, c4 = idx - bb * d4;
-        storef4(tile + bb * u.d + c4 * 4, loadf4(gk + (int64_t)(tb0 + bb) * u.stride_b + c4 * 4));
-      }
-      __syncthreads();
+    int t = 0;
+    for (int tb0 = bag_lo; tb0 < bag_hi; tb0 += TB, ++t) {  // uniform
+      const int nb = bag_hi - tb0 < TB ? bag_hi - tb0 : TB;
+      // the first 64 bags of every run of this wave are requested before the tile is stored
+      uint32_t first[MR];
 #pragma unroll
       for (int i = 0; i < MR; ++i) {
-        while (cur[i] < end[i]) {  // wave-uniform
-          // window of up to 256 entries of the run: 4 coalesced loads, parked in this wave's LDS
-          const uint32_t left = end[i] - cur[i];
-          uint32_t cnt = 0;
+        const uint32_t c0 = cursor[w + kNW * i][t], c1 = cursor[w + kNW * i][t + 1];
+        first[i] = 0;
+        if (c0 + (uint32_t)lane < c1) first[i] = bags[i][c0 + lane];
+      }
+      __syncthreads();  // the previous tile has been consumed
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint32_t p = (uint32_t)(j * DLRM_WAVE + lane);
-            const uint32_t bag = p < left ? bags[i][cur[i] + p] : 0xFFFFFFFFu;
-            wbag[w][p] = bag;
-            cnt += (uint32_t)__popcll(__ballot(bag < (uint32_t)tb1));  // sorted: a prefix of the window
+      for (int p = 0; p < NP; ++p) {
+        const int bb = p * NG + grp;
+        if (bb < nb && col_ok) storef4(tile + bb * u.d + chunk * 4, stage[p]);
+      }
+      __syncthreads();
+      if (tb0 + TB < bag_hi) {  // uniform: the next tile travels while this one is summed
+        const int nn = bag_hi - (tb0 + TB) < TB ? bag_hi - (tb0 + TB) : TB;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const int bb = p * NG + grp < nn ? p * NG + grp : nn - 1;
+          stage[p] = loadf4(gk + (int64_t)(tb0 + TB + bb) * u.stride_b);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < MR; ++i) {
+        // the cursors are the same in every lane: scalar loop control
+        const uint32_t c0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cursor[w + kNW * i][t]);
+        const uint32_t c1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)cursor[w + kNW * i][t + 1]);
+        uint32_t cur = first[i];
+        for (uint32_t e0 = c0; e0 < c1; e0 += DLRM_WAVE) {
+          uint32_t nxt = 0;  // the next 64 bags travel while these are summed
+          if (e0 + DLRM_WAVE + (uint32_t)lane < c1) nxt = bags[i][e0 + DLRM_WAVE + lane];
+          const uint32_t cnt = c1 - e0 < (uint32_t)DLRM_WAVE ? c1 - e0 : (uint32_t)DLRM_WAVE;
+          // fold equal neighbours: the first entry of each distinct bag carries how many follow
+          const uint32_t prev = (uint32_t)__shfl_up((int)cur, 1, DLRM_WAVE);
+          const bool head = (uint32_t)lane < cnt && (lane == 0 || cur != prev);
+          const unsigned long long hm = __ballot(head);
+          const uint32_t nh = (uint32_t)__popcll(hm);
+          const unsigned long long rest = (hm >> lane) >> 1;
+          const uint32_t nextp = rest ? (uint32_t)lane + (uint32_t)__ffsll((long long)rest) : cnt;
+          // LDS offset of the bag's gradient row (< 2^16) | multiplicity << 16
+          if (head) wsc[w][__popcll(hm & lt)] = ((nextp - (uint32_t)lane) << 16) | ((cur - (uint32_t)tb0) * (uint32_t)u.d);
+          uint32_t mine = wsc[w][lane];
+          mine = (uint32_t)lane < nh ? mine : (uint32_t)kHotTileFloats;  // the row of zeros, zero times
+          for (uint32_t e = 0; e < nh; e += HU * S) {
+            f32x4 v[HU];
+            float m[HU];
+#pragma unroll
+            for (int q = 0; q < HU; ++q) {  // HU independent LDS reads in flight
+              const uint32_t pk = lane_entry<S>(mine, e + (uint32_t)(q * S), slot);
+              v[q] = loadf4(tile + (pk & 0xFFFFu) + cchunk * 4);
+              m[q] = (float)(pk >> 16);
+            }
+#pragma unroll
+            for (int q = 0; q < HU; ++q) {
+              acc[i].x = fmaf(m[q], v[q].x, acc[i].x);
+              acc[i].y = fmaf(m[q], v[q].y, acc[i].y);
+              acc[i].z = fmaf(m[q], v[q].z, acc[i].z);
+              acc[i].w = fmaf(m[q], v[q].w, acc[i].w);
+            }
           }
-          for (uint32_t e = 0; e < cnt; e += 2 * S) {
-            const uint32_t i0 = e + slot, i1 = e + S + slot;
-            const uint32_t b0 = wbag[w][i0 & 255u], b1 = wbag[w][i1 & 255u];
-            f32x4 v0 = {0.0f, 0.0f, 0.0f, 0.0f}, v1 = {0.0f, 0.0f, 0.0f, 0.0f};
-            if (i0 < cnt && col_ok) v0 = loadf4(tile + (b0 - (uint32_t)tb0) * u.d + chunk * 4);
-            if (i1 < cnt && col_ok) v1 = loadf4(tile + (b1 - (uint32_t)tb0) * u.d + chunk * 4);
-            acc[i] += v0;
-            acc[i] += v1;
-          }
-          cur[i] += cnt;
-          if (cnt < 256u) break;
+          cur = nxt;
         }
       }
     }
@@ -1229,27 +1494,34 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
       float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d;
       if (slot == 0 && col_ok) storef4(part + (size_t)g * u.d + chunk * 4, tot);
     }
-    // one release fence per workgroup (it writes back the whole L2 slice: keep them rare), then
-    // a ticket per run; the bag group that arrives last adds the run's partials in group order
-    __threadfence();
-    __syncthreads();
+  }
+}
+
+// A lane group per hot run adds the run's partial sums in bag-group order and updates the row.
+// A launch of its own: the kernel boundary orders it after every partial, at no fence.
+template <int DT, int G>
+__global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdArgs u, int ngroups) {
+  constexpr int S = DLRM_WAVE / G;
+  const int k = blockIdx.y;
+  const uint32_t nruns = a.hot_cnt[k];
+  if (nruns == 0) return;
+  const uint32_t base = hot_list_base(a, k);
+  const int lane = lane_id();
+  const int chunk = lane % G;
+  if (chunk * 4 >= u.d) return;
+  char* W = static_cast<char*>(u.tables[k]);
+  for (uint32_t r = (blockIdx.x * kNW + wave_id()) * S + lane / G; r < nruns; r += gridDim.x * kNW * S) {
+    const float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d + chunk * 4;
+    f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g0 = 0; g0 < ngroups; g0 += 8) {
+      f32x4 v[8];
 #pragma unroll
-    for (int i = 0; i < MR; ++i) {
-      const uint32_t r = r0 + w + kNW * i;
-      if (r >= nruns) continue;  // wave-uniform
-      uint32_t ticket = 0;
-      if (lane == 0) ticket = atomicAdd(&a.huge_runs[base + r].done, 1u);
-      ticket = __shfl(ticket, 0, DLRM_WAVE);
-      if (ticket == (uint32_t)ngroups - 1u) {
-        __threadfence();
-        const float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d;
-        if (slot == 0 && col_ok) {
-          f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-          for (int gg = 0; gg < ngroups; ++gg) sum += loadf4(part + (size_t)gg * u.d + chunk * 4);
-          sgd_row_update<DT>(static_cast<char*>(u.tables[k]), u, a.huge_runs[base + r].row, chunk, sum);
-        }
-      }
+      for (int q = 0; q < 8; ++q) v[q] = loadf4(part + (size_t)(g0 + q < ngroups ? g0 + q : g0) * u.d);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (g0 + q < ngroups) sum += v[q];
     }
+    sgd_row_update<DT>(W, u, a.huge_runs[base + r].row, chunk, sum);
   }
 }
 
@@ -1494,8 +1766,10 @@ static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_
   DLRM_CHECK_LAUNCH();
   hipLaunchKernelGGL((segment_reduce_kernel<DT, G>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
-  const int tb = hot_tile_bags(u.d), gb = tb * kHotTilesPerGroup, ng = hot_groups(g.B, u.d);
-  hipLaunchKernelGGL((hot_rows_kernel<DT, G>), dim3(ng, K), dim3(kThreads), 0, st, g, u, tb, gb, ng);
+  const int ng = hot_groups(g.B, u.d);
+  hipLaunchKernelGGL((hot_rows_kernel<DT, G>), dim3(ng, K), dim3(kThreads), 0, st, g, u, ng);
+  DLRM_CHECK_LAUNCH();
+  hipLaunchKernelGGL((hot_finish_kernel<DT, G>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
