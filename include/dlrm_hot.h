@@ -47,6 +47,7 @@ extern "C" {
 #define DLRM_BWD_AUTO 0   /* library's measured choice for the shape */
 #define DLRM_BWD_SORT 1   /* group (row, bag) pairs by row, reduce, one update per row; deterministic */
 #define DLRM_BWD_ATOMIC 2 /* fp32 tables only: one hardware fp32 atomic add per looked-up element */
+#define DLRM_BWD_SORT_PREPARED 3 /* DLRM_BWD_SORT whose grouping dlrm_emb_bag_bwd_prepare already did */
 
 /* supported ranges */
 #define DLRM_MAX_ROW_BYTES 1024         /* d * sizeof(element) <= 1024, multiple of 16 */
@@ -169,6 +170,22 @@ size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t
 int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
                              int64_t stride_k, float lr, void* workspace, size_t workspace_bytes,
                              int32_t algo, void* stream);
+
+/*
+ * The index-only half of DLRM_BWD_SORT (Sec. 4.1: the indices of a batch are known
+ * before its forward pass): partitions the batch's (row, bag) pairs by row inside
+ * `workspace`.  It reads indices, offsets, tbl_off and rows only -- no table, no
+ * gradient -- so a caller may enqueue it on a second stream while the forward pass
+ * and the interaction run, then call dlrm_emb_bag_bwd_sgd with
+ * algo = DLRM_BWD_SORT_PREPARED, the same batch and the same workspace once both
+ * streams have met (the caller orders the two calls, e.g. with an event; nothing
+ * else may touch the workspace in between).  Prepare + prepared update perform the
+ * same launches as one DLRM_BWD_SORT call and give the same bits.
+ * An update with DLRM_BWD_SORT_PREPARED on a workspace that was not prepared for
+ * this batch is undefined (it is not detected).
+ */
+int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* batch, void* workspace,
+                                 size_t workspace_bytes, void* stream);
 
 /*
  * Runs only the grouping stage of DLRM_BWD_SORT and exports it in canonical

@@ -13,7 +13,7 @@ import torch
 from . import build as _build
 
 F32, F16, BF16 = 0, 1, 2
-BWD_AUTO, BWD_SORT, BWD_ATOMIC = 0, 1, 2
+BWD_AUTO, BWD_SORT, BWD_ATOMIC, BWD_SORT_PREPARED = 0, 1, 2, 3
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 _ELEM = {F32: 4, F16: 2, BF16: 2}
 
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i32]
         L.dlrm_emb_bag_bwd_sgd.restype = i32
         L.dlrm_emb_bag_bwd_sgd.argtypes = [sb, vp, i64, i64, f32, vp, sz, i32, vp]
+        L.dlrm_emb_bag_bwd_prepare.restype = i32
+        L.dlrm_emb_bag_bwd_prepare.argtypes = [sb, vp, sz, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
         L.dlrm_emb_bag_bwd_export_groups.argtypes = [sb, vp, sz, vp, vp, vp, vp, vp]
         L.dlrm_profile_reduce_kernel.restype = i32
@@ -177,6 +179,13 @@ def dlrm_emb_bag_bwd_sgd(batch: SparseBatch, dS: torch.Tensor, stride_b: int, st
     _check("dlrm_emb_bag_bwd_sgd",
            lib().dlrm_emb_bag_bwd_sgd(batch.ref(), _ptr(dS) + 4 * dS_offset, stride_b, stride_k,
                                       C.c_float(lr), _ptr(workspace), ws_bytes, algo, _stream()))
+
+
+def dlrm_emb_bag_bwd_prepare(batch: SparseBatch, workspace: torch.Tensor):
+    """Enqueued on torch's current stream, like every other call."""
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check("dlrm_emb_bag_bwd_prepare",
+           lib().dlrm_emb_bag_bwd_prepare(batch.ref(), _ptr(workspace), ws_bytes, _stream()))
 
 
 def dlrm_emb_bag_bwd_export_groups(batch: SparseBatch, workspace: torch.Tensor,

@@ -1832,7 +1832,8 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   if ((s->d & 3) || stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0)
     return DLRM_ERR_BAD_SHAPE;
   if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
-  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_ATOMIC) return DLRM_ERR_BAD_ALGO;
+  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_ATOMIC && algo != DLRM_BWD_SORT_PREPARED)
+    return DLRM_ERR_BAD_ALGO;
   if (algo == DLRM_BWD_ATOMIC && s->table_dtype != DLRM_F32) return DLRM_ERR_BAD_DTYPE;
   if (algo == DLRM_BWD_AUTO) algo = DLRM_BWD_SORT;
   hipStream_t hs = static_cast<hipStream_t>(stream);
@@ -1871,8 +1872,10 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   if (s->nnz_total == 0) return DLRM_OK;
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
-  st = enqueue_partition(s, g, hs);
-  if (st != DLRM_OK) return st;
+  if (algo != DLRM_BWD_SORT_PREPARED) {
+    st = enqueue_partition(s, g, hs);
+    if (st != DLRM_OK) return st;
+  }
   UpdArgs u;
   u.tables = s->tables;
   u.dS = dS;
@@ -1886,6 +1889,20 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
     case DLRM_BF16: return dispatch_reduce<DLRM_BF16>(g, u, G, s->K, hs);
   }
   return DLRM_ERR_BAD_DTYPE;
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* workspace,
+                                            size_t workspace_bytes, void* stream) {
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  if ((s->d & 3) || pow2_ceil(s->d / 4) > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
+  WsLayout L;
+  st = check_ws(s, workspace, workspace_bytes, &L);
+  if (st != DLRM_OK) return st;
+  if (s->nnz_total == 0) return DLRM_OK;
+  GroupArgs g;
+  fill_group_args(g, s, L, workspace);
+  return enqueue_partition(s, g, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* s, void* workspace,

@@ -63,6 +63,11 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert call(_batch(), C.c_void_p(0x1000), need - 1, hot.BWD_SORT) == -4
     assert call(_batch(), C.c_void_p(0x1010), need, hot.BWD_SORT) == -4      # misaligned
     assert call(_batch(), C.c_void_p(0x1000), need, 9) == -5
+    assert call(_batch(), None, 0, hot.BWD_SORT_PREPARED) == -4
+    prep = lambda b, ws, n: L.dlrm_emb_bag_bwd_prepare(C.byref(b), ws, n, None)
+    assert prep(_batch(), None, 0) == -4
+    assert prep(_batch(), C.c_void_p(0x1000), need - 1) == -4
+    assert prep(_batch(K=0), C.c_void_p(0x1000), need) != 0
     assert call(_batch(table_dtype=1), C.c_void_p(0x1000), need, hot.BWD_ATOMIC) == -3
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(0, 4, 16, 8, 100, 0) == 0
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 8, 100, 5) == 0

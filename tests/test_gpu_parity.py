@@ -277,6 +277,42 @@ def test_emb_bag_bwd_sgd_matches_oracle(case, algo):
             assert torch.equal(tables2[k].view(torch.uint8), tables[k].view(torch.uint8))
 
 
+@pytest.mark.parametrize("case", [c for c in BWD_CASES if c[0] in ("multi-tile-ragged", "hot-rows",
+                                                                   "f16-d128-fixed32")], ids=lambda c: c[0])
+def test_prepare_on_a_second_stream_then_update_gives_the_same_bits(case):
+    """dlrm_emb_bag_bwd_prepare on a side stream (while other work runs on the main one), then
+    the update with DLRM_BWD_SORT_PREPARED, against the single-call sort path."""
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("emb_bag_bwd prepare/update %s" % name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=6)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    one = upload_tables(host, dtype)
+    two = upload_tables(host, dtype)
+    F = K + 1
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(b.dS()).to(DEV)
+    lr = float(np.float32(w.lr))
+    sb1 = make_sparse_batch(b, one)
+    ws1 = hot.alloc_workspace(sb1)
+    hot.dlrm_emb_bag_bwd_sgd(sb1, dT, F * d, d, lr, ws1, algo=hot.BWD_SORT, dS_offset=d)
+    sb2 = make_sparse_batch(b, two)
+    ws2 = hot.alloc_workspace(sb2)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    with torch.cuda.stream(side):
+        hot.dlrm_emb_bag_bwd_prepare(sb2, ws2)
+        done.record(side)
+    pooled = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(sb2, pooled, F * d, d, out_offset=d)   # the main stream is busy meanwhile
+    torch.cuda.current_stream().wait_event(done)
+    hot.dlrm_emb_bag_bwd_sgd(sb2, dT, F * d, d, lr, ws2, algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert torch.equal(one[k].view(torch.uint8), two[k].view(torch.uint8))
+
+
 def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
     lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
     b = gen.batch_from_lists([8, 8, 8], lists, d=8)
