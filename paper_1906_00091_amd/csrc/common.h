@@ -66,9 +66,10 @@ __device__ inline void bf162_to_float2(uint32_t bits, float& a, float& b) {
   b = u2f(bits & 0xFFFF0000u);
 }
 __device__ inline uint32_t float_to_bf16_rne(float f) {
-  uint32_t u = f2u(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  const uint32_t u = f2u(f);
+  const uint32_t nan = (u >> 16) | 0x40u;  // NaN stays NaN (quiet)
+  const uint32_t rne = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  return (u & 0x7FFFFFFFu) > 0x7F800000u ? nan : rne;
 }
 __device__ inline uint32_t float2_to_bf162(float a, float b) {
   return float_to_bf16_rne(a) | (float_to_bf16_rne(b) << 16);

@@ -986,6 +986,8 @@ __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const
 struct SplitLds {
   uint32_t cand[kCand];       // candidate row ids, in row order; unused slots 0xFFFFFFFF
   uint32_t cnt[kCand + 1];    // pairs per class; class kCand = every other row
+  uint32_t wcnt[kNW][kCand + 1];   // the same per wavefront (each streams a quarter of the bucket)
+  uint32_t wbase[kNW][kCand + 1];  // running destination of every (wavefront, class)
   uint32_t cbase[kCand + 2];  // exclusive prefix of cnt
   uint32_t nc;
 };
@@ -1034,7 +1036,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
   // ---- candidates: long runs among the first kBktCap pairs
   if (tid < kCand) sp.cand[tid] = 0xFFFFFFFFu;
-  if (tid < kCand + 1) sp.cnt[tid] = 0;
+  if (tid < kNW * (kCand + 1)) (&sp.wcnt[0][0])[tid] = 0;
   {
     Bucket head = b;
     head.n = (uint32_t)kBktCap;
@@ -1067,28 +1069,51 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   for (int c = 0; c < kCand; ++c) cd[c] = sp.cand[c];
   const uint32_t* kin = a.keys[1] + b.start;
   const uint32_t* vin = a.vals[1] + b.start;
-  // ---- pass 1: pairs per class.  A wavefront's lanes mostly agree (the dominant row): those
-  // that agree with the first valid lane are counted with one LDS atomic
-  for (uint32_t i0 = 0; i0 < b.n; i0 += kThreads * 8) {
-    uint32_t kk[8];
+  // Both passes: wavefront w streams its own quarter [q0, q1) of the bucket, no barriers inside.
+  const uint32_t span = (b.n + kNW * DLRM_WAVE - 1) / (kNW * DLRM_WAVE) * DLRM_WAVE;
+  const uint32_t q0 = (uint32_t)w * span < b.n ? (uint32_t)w * span : b.n;
+  const uint32_t q1 = q0 + span < b.n ? q0 + span : b.n;
+  // ---- pass 1: pairs per (wavefront, class).  A wavefront's lanes mostly agree (the dominant
+  // row): those that agree with the first valid lane are counted with one LDS atomic
+  // (the next 8 steps of 64 pairs are in flight while the current 8 are processed)
+  uint32_t kk[8];
+  if (q0 < q1) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const uint32_t i = i0 + q * kThreads + tid;
-      kk[q] = kin[i < b.n ? i : b.n - 1];
+      const uint32_t i = q0 + q * DLRM_WAVE + lane;
+      kk[q] = kin[i < q1 ? i : q1 - 1];
+    }
+  }
+  for (uint32_t i0 = q0; i0 < q1; i0 += DLRM_WAVE * 8) {
+    uint32_t nk[8];
+    if (i0 + DLRM_WAVE * 8 < q1) {  // uniform
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t i = i0 + DLRM_WAVE * 8 + q * DLRM_WAVE + lane;
+        nk[q] = kin[i < q1 ? i : q1 - 1];
+      }
     }
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
-      const uint32_t i = i0 + q * kThreads + tid;
-      const bool valid = i < b.n;
+      const uint32_t i = i0 + q * DLRM_WAVE + lane;
+      const bool valid = i < q1;
       const uint32_t cls = class_of(kk[q], cd);
       const unsigned long long vm = __ballot(valid);
       if (vm == 0ull) continue;  // wave-uniform
       const int first = __ffsll((long long)vm) - 1;
-      const uint32_t c0 = __shfl(cls, first, DLRM_WAVE);
+      const uint32_t c0 = (uint32_t)__builtin_amdgcn_readlane((int)cls, first);
       const unsigned long long same = __ballot(valid && cls == c0);
-      if (lane == first) atomicAdd(&sp.cnt[c0], (uint32_t)__popcll(same));
-      if (valid && cls != c0) atomicAdd(&sp.cnt[cls], 1u);
+      if (lane == first) atomicAdd(&sp.wcnt[w][c0], (uint32_t)__popcll(same));
+      if (valid && cls != c0) atomicAdd(&sp.wcnt[w][cls], 1u);
     }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) kk[q] = nk[q];
+  }
+  __syncthreads();
+  if (tid <= kCand) {
+    uint32_t tot = 0;
+    for (int i = 0; i < kNW; ++i) tot += sp.wcnt[i][tid];
+    sp.cnt[tid] = tot;
   }
   __syncthreads();
   if (tid == 0) {
@@ -1100,46 +1125,68 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
     sp.cbase[kCand + 1] = run;
   }
   __syncthreads();
-  // ---- pass 2: stable partition by class into pair buffer 0, tiles in order.  Candidate lists
-  // keep only the bags (plus the row id at their first position); the rest keeps (row, bag).
+  if (tid <= kCand) {  // where wavefront i's first pair of the class goes
+    uint32_t run = sp.cbase[tid];
+    for (int i = 0; i < kNW; ++i) {
+      sp.wbase[i][tid] = run;
+      run += sp.wcnt[i][tid];
+    }
+  }
+  __syncthreads();
+  // ---- pass 2: stable partition by class into pair buffer 0.  Candidate lists keep only the
+  // bags (plus the row id at their first position); the rest keeps (row, bag).  Within a step
+  // of 64 pairs the lanes of one class rank themselves by ballot; the wavefront's running
+  // destination per class lives in its own LDS row.
   uint32_t* kout = a.keys[0] + b.start;
   uint32_t* vout = a.vals[0] + b.start;
-  constexpr int kClsBits = 5;
-  static_assert(kCand + 1 <= (1 << kClsBits), "class ids must fit the ranking digit");
-  if (tid < (1 << kClsBits)) s.base[tid] = tid <= kCand ? sp.cbase[tid] : 0u;
-  __syncthreads();
-  for (uint32_t t0 = 0; t0 < b.n; t0 += kBktCap) {
-    const int cnt = (int)(b.n - t0 < (uint32_t)kBktCap ? b.n - t0 : (uint32_t)kBktCap);
-    uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
-    bool ok[kBktItems];
-    for (int i = tid; i < kNW * kSortBuckets; i += kThreads) (&s.wcnt[0][0])[i] = 0;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  uint32_t key[8], val[8];
+  if (q0 < q1) {
 #pragma unroll
-    for (int j = 0; j < kBktItems; ++j) {
-      const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
-      ok[j] = li < cnt;
-      key[j] = ok[j] ? kin[t0 + li] : 0xFFFFFFFFu;
-      val[j] = ok[j] ? vin[t0 + li] : 0u;
-      dg[j] = class_of(key[j], cd);
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t i = q0 + q * DLRM_WAVE + lane;
+      key[q] = kin[i < q1 ? i : q1 - 1];
+      val[q] = vin[i < q1 ? i : q1 - 1];
     }
-    __syncthreads();
-    rank_items<kBktItems, kSortBuckets>(dg, ok, kClsBits, s.wcnt, rnk);
-    __syncthreads();
-    uint32_t lofs, tot;
-    digit_offsets<kSortBuckets>(1 << kClsBits, s.wcnt, s.smem, &lofs, &tot);
-    if (tid < (1 << kClsBits)) s.heads[tid] = lofs;
-    __syncthreads();
+  }
+  for (uint32_t i0 = q0; i0 < q1; i0 += DLRM_WAVE * 8) {
+    uint32_t nk[8], nv[8];
+    if (i0 + DLRM_WAVE * 8 < q1) {  // uniform
 #pragma unroll
-    for (int j = 0; j < kBktItems; ++j) {
-      if (ok[j]) {
-        const uint32_t dst = s.base[dg[j]] + (s.wcnt[w][dg[j]] - s.heads[dg[j]]) + rnk[j];
-        vout[dst] = val[j];
-        if (dg[j] == (uint32_t)kCand) kout[dst] = key[j];
+      for (int q = 0; q < 8; ++q) {
+        const uint32_t i = i0 + DLRM_WAVE * 8 + q * DLRM_WAVE + lane;
+        nk[q] = kin[i < q1 ? i : q1 - 1];
+        nv[q] = vin[i < q1 ? i : q1 - 1];
       }
     }
-    __syncthreads();
-    if (tid < (1 << kClsBits)) s.base[tid] += tot;
-    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const uint32_t i = i0 + q * DLRM_WAVE + lane;
+      const bool valid = i < q1;
+      const uint32_t cls = class_of(key[q], cd);
+      unsigned long long rem = __ballot(valid);
+      uint32_t dst = 0;
+      while (rem != 0ull) {  // wave-uniform: one round per class present in the step
+        const int f = __ffsll((long long)rem) - 1;
+        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cls, f);
+        const unsigned long long m = __ballot(valid && cls == c);
+        const uint32_t bs = sp.wbase[w][c];
+        if (valid && cls == c) dst = bs + (uint32_t)__popcll(m & lt);
+        if (lane == f) sp.wbase[w][c] = bs + (uint32_t)__popcll(m);
+        rem &= ~m;
+      }
+      if (valid) {
+        vout[dst] = val[q];
+        if (cls == (uint32_t)kCand) kout[dst] = key[q];
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      key[q] = nk[q];
+      val[q] = nv[q];
+    }
   }
+  __syncthreads();
   if ((uint32_t)tid < nc) kout[sp.cbase[tid]] = sp.cand[tid];
   if ((uint32_t)tid <= nc) s.heads[tid] = sp.cbase[tid];
   __syncthreads();
