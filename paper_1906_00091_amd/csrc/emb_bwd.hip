@@ -15,12 +15,16 @@
 //                       then a lane group per run sums its dS rows in ascending position
 //                       order (fp32) and read-modify-writes the table row once.  Runs longer
 //                       than 32 are summed by the whole workgroup; runs longer than 2048 are
-//                       queued for step 5.
-//   5. huge_runs      : 1024-entry chunks of the queued runs are summed by separate
-//                       workgroups; the last chunk to finish adds the partials in chunk order
-//                       and updates the row (no waiting on other workgroups).
+//                       queued per table as hot rows.  Buckets too large for LDS first split
+//                       off their dominant rows unsorted (4a); what still does not fit goes to
+//   4b. segment_sort / segment_reduce : a large list sorted by one workgroup per 2048 pairs
+//                       with per-row counters in LDS, then reduced window by window.
+//   5. hot_rows       : workgroup (bag group, table) streams the gradient rows of its bags
+//                       through LDS once and adds them into every hot row that names them;
+//      hot_finish     : adds a hot row's partial sums in bag-group order and updates the row.
+// Steps 1-3 read indices and offsets only; dlrm_emb_bag_bwd_prepare enqueues just them.
 // ATOMIC path (fp32 tables): a lane group per bag adds -lr*dS[b,k,:] to every row of the bag
-// with hardware fp32 atomics; no workspace, one launch.  Measured 3.8x slower than SORT on the
+// with hardware fp32 atomics; no workspace, one launch.  Measured 6x slower than SORT on the
 // 8 x 1M x 64 multi-hot workload, so AUTO always takes SORT.
 #include "common.h"
 
