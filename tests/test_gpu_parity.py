@@ -178,6 +178,15 @@ BWD_CASES = [
     ("f16-d128-fixed32", 4, 300, 128, gen.F16, 20000, ("fixed", 32), ("zipf", 1.2)),
     ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
     ("one-row-table", 2, 5000, 16, gen.F32, 1, ("fixed", 1), ("uniform",)),
+    # rarely taken routes of the sort path
+    # 40 rows x ~4096 lookups each: more hot rows per table than one pass of the hot-row kernel holds
+    ("many-hot-rows", 2, 4096, 32, gen.F32, 40, ("fixed", 40), ("uniform",)),
+    # every bucket too large for the LDS sort, nothing dominant, few unsorted bits: segment kernels
+    ("segments-no-dominant-row", 1, 32768, 8, gen.F32, 1 << 22, ("fixed", 96), ("uniform",)),
+    # dominant rows split off AND a remainder that is still too large
+    ("dominant-rows-large-rest", 1, 32768, 16, gen.F32, 1 << 22, ("fixed", 96), ("zipf", 1.1)),
+    # too many unsorted bits for per-row counters: a workgroup streams its bucket through global memory
+    ("large-buckets-many-bits", 1, 65536, 4, gen.F32, 1 << 25, ("fixed", 64), ("uniform",)),
 ]
 
 
