@@ -14,13 +14,17 @@
  *   - backward of the two, by the chain rule (the paper prints no backward)
  *   - sparse SGD              W <- W - lr * dW on touched rows (Sec. 5.1: SGD,
  *                             no regularisation)
+ *   - sparse Adagrad          the other optimizer Sec. 5.1 names, element-wise:
+ *                             h <- h + dW^2, W <- W - lr * dW / (sqrt(h) + eps)
+ *                             on touched rows
  * Table storage is fp32 (Sec. 5: fp32 parameters) or fp16/bf16 (widened exactly,
  * narrowed once with round-to-nearest-even).
  *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py
  * (the printed CSR example, one-hot == row gather, dense A^T W by a library
  * matmul, tril(T T^T), closed forms for F = 2, finite differences, count x g,
- * numpy.unique, exhaustive fp16 widening / RNE narrowing against numpy).
+ * numpy.unique, exhaustive fp16 widening / RNE narrowing against numpy; Adagrad:
+ * closed forms, the coalescing of duplicates, torch.optim.Adagrad on the CPU).
  *
  * Optional OpenMP `parallel for` over the outermost independent loop is the only
  * concession to speed; oracle_set_threads(1) gives the single-thread run.
@@ -386,6 +390,64 @@ int oracle_emb_bag_bwd_sgd(int32_t K, int32_t B, int32_t d, int32_t dtype, void*
       if (uniq_rows_out)
         for (int64_t u = 0; u < U; ++u) uniq_rows_out[base + u] = uniq[base + u];
       if (n_uniq_out) n_uniq_out[k] = U;
+    }
+  }
+  free(sorted_pos);
+  free(sorted_bag);
+  free(uniq);
+  free(seg);
+  free(nu);
+  return status;
+}
+
+/* Sparse Adagrad in place of the SGD step (Sec. 5.1 names both optimizers; the paper prints no
+ * formula, this is the standard element-wise one).  For every distinct row r of table k, with
+ * g the row's batch gradient as in oracle_emb_bag_bwd_sgd (duplicates summed first):
+ *   h_k[r,:] <- h_k[r,:] + g*g            (fp32 state, one rounding)
+ *   W_k[r,:] <- W_k[r,:] - lr * g / (sqrt(h_k[r,:]) + eps)   with the updated h, one rounding
+ * Rows nobody looks up keep W and h. */
+int oracle_emb_bag_bwd_adagrad(int32_t K, int32_t B, int32_t d, int32_t dtype, void* const* tables,
+                               float* const* state, const int64_t* rows, const int64_t* indices,
+                               const int64_t* offsets, const int64_t* tbl_off, const float* dS,
+                               int64_t stride_b, int64_t stride_k, double lr, double eps) {
+  if (!tables || !state || !rows || !offsets || !tbl_off || !dS || K <= 0 || B <= 0 || d <= 0)
+    return ORC_ERR_ARG;
+  int64_t nnz_total = tbl_off[K];
+  size_t n = (size_t)(nnz_total > 0 ? nnz_total : 1);
+  int64_t* sorted_pos = (int64_t*)malloc(sizeof(int64_t) * n);
+  int32_t* sorted_bag = (int32_t*)malloc(sizeof(int32_t) * n);
+  int64_t* uniq = (int64_t*)malloc(sizeof(int64_t) * n);
+  int64_t* seg = (int64_t*)malloc(sizeof(int64_t) * n);
+  int64_t* nu = (int64_t*)malloc(sizeof(int64_t) * (size_t)K);
+  int status = ORC_ERR_MEM;
+  if (sorted_pos && sorted_bag && uniq && seg && nu)
+    status = oracle_group_rows(K, B, indices, offsets, tbl_off, sorted_pos, sorted_bag, uniq, seg, nu);
+  if (status == ORC_OK) {
+    for (int32_t k = 0; k < K; ++k) {
+      int64_t base = tbl_off[k], nnz = tbl_off[k + 1] - tbl_off[k];
+      int64_t U = nu[k];
+      int bad = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 64) num_threads(ORC_NT)
+#endif
+      for (int64_t u = 0; u < U; ++u) {
+        int64_t r = uniq[base + u];
+        if (r < 0 || r >= rows[k]) {
+          bad = 1;
+          continue;
+        }
+        int64_t t0 = seg[base + u], t1 = (u + 1 < U) ? seg[base + u + 1] : nnz;
+        for (int32_t c = 0; c < d; ++c) {
+          double g = 0.0;
+          for (int64_t t = t0; t < t1; ++t)
+            g += (double)dS[(int64_t)sorted_bag[base + t] * stride_b + (int64_t)k * stride_k + c];
+          double h = (double)state[k][r * d + c] + g * g;
+          state[k][r * d + c] = (float)h;
+          double w = widen(tables[k], dtype, r * d + c);
+          narrow_store(tables[k], dtype, r * d + c, w - lr * g / (sqrt(h) + eps));
+        }
+      }
+      if (bad) status = ORC_ERR_INDEX;
     }
   }
   free(sorted_pos);

@@ -219,3 +219,25 @@ def emb_bag_bwd_sgd(tables: Sequence[np.ndarray], dtype: int, indices, offsets, 
         if want_grad:
             grad_l.append(grad[a:a + u].copy())
     return uniq_l, (grad_l if want_grad else None)
+
+
+def emb_bag_bwd_adagrad(tables: Sequence[np.ndarray], state: Sequence[np.ndarray], dtype: int, indices,
+                        offsets, tbl_off, dS: np.ndarray, lr: float, eps: float):
+    """Updates ``tables`` and the float32 accumulators ``state`` in place.  dS float32 [B,K,d]."""
+    indices, offsets, tbl_off = _i64(indices), _i64(offsets), _i64(tbl_off)
+    dS = np.ascontiguousarray(dS, dtype=np.float32)
+    K, B1 = offsets.shape
+    B = B1 - 1
+    d = tables[0].shape[1]
+    assert dS.shape == (B, K, d)
+    for t, h in zip(tables, state):
+        assert h.dtype == np.float32 and h.shape == t.shape and h.flags["C_CONTIGUOUS"]
+    rows = _i64([t.shape[0] for t in tables])
+    ptrs, keep = _table_ptrs(tables, dtype)
+    sptrs = (C.c_void_p * K)(*[h.ctypes.data for h in state])
+    st = lib().oracle_emb_bag_bwd_adagrad(
+        C.c_int32(K), C.c_int32(B), C.c_int32(d), C.c_int32(dtype), ptrs, sptrs, _p(rows), _p(indices),
+        _p(offsets), _p(tbl_off), _p(dS), C.c_int64(K * d), C.c_int64(d), C.c_double(float(lr)),
+        C.c_double(float(eps)))
+    if st != 0:
+        raise ValueError("oracle_emb_bag_bwd_adagrad status %d" % st)

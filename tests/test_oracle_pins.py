@@ -409,3 +409,102 @@ def test_fp16_tables_update_rounds_once():
     for ui, r in enumerate(uniq[0]):
         want = (W[r].astype(np.float64) - lr * grad[0][ui]).astype(np.float16)
         assert np.array_equal(W2[r].view(np.uint16), want.view(np.uint16))
+
+
+# ------------------------------------------------------------------ sparse Adagrad (Sec. 5.1)
+def _one_table_batch(rows, lists, d):
+    return gen.batch_from_lists([rows], [lists], d=d)
+
+
+def test_adagrad_closed_forms_single_row():
+    # one row, one lookup, g = 2, h0 = 0, eps = 0: h = 4, W = 1 - 0.1 * 2 / 2 = 0.9 (to fp32)
+    b = _one_table_batch(3, [[1]], d=2)
+    dS = np.array([[[2.0, -4.0]]], dtype=np.float32)
+    W = [np.ones((3, 2), dtype=np.float32)]
+    h = [np.zeros((3, 2), dtype=np.float32)]
+    oracle.emb_bag_bwd_adagrad(W, h, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 0.1, 0.0)
+    assert np.array_equal(h[0][1], np.array([4.0, 16.0], dtype=np.float32))
+    assert np.array_equal(W[0][1], np.array([np.float32(1.0 - 0.1), np.float32(1.0 + 0.1)]))
+    # from h = 0 with eps = 0 the first step is lr * sign(g) whatever |g| is
+    assert np.array_equal(W[0][[0, 2]], np.ones((2, 2), dtype=np.float32))
+    assert np.array_equal(h[0][[0, 2]], np.zeros((2, 2), dtype=np.float32))
+    # n steps with the same gradient: h = n g^2, W = 1 - lr * sum_{i<=n} 1/sqrt(i)
+    W = [np.ones((3, 2), dtype=np.float64).astype(np.float32)]
+    h = [np.zeros((3, 2), dtype=np.float32)]
+    dS = np.array([[[0.5, 0.5]]], dtype=np.float32)
+    for _ in range(9):
+        oracle.emb_bag_bwd_adagrad(W, h, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 0.01, 0.0)
+    assert np.array_equal(h[0][1], np.full(2, 9 * 0.25, dtype=np.float32))
+    want = 1.0 - 0.01 * sum(1.0 / np.sqrt(i) for i in range(1, 10))
+    assert np.allclose(W[0][1], want, rtol=0, atol=5e-7)
+    # eps enters outside the square root: g = 3, h0 = 16 -> h = 25, W = 1 - 1 * 3 / (5 + 1)
+    W = [np.ones((3, 2), dtype=np.float32)]
+    h = [np.full((3, 2), 16.0, dtype=np.float32)]
+    dS = np.array([[[3.0, -3.0]]], dtype=np.float32)
+    oracle.emb_bag_bwd_adagrad(W, h, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 1.0, 1.0)
+    assert np.array_equal(W[0][1], np.array([0.5, 1.5], dtype=np.float32))
+
+
+def test_adagrad_sums_duplicates_before_squaring():
+    # row 2 is looked up by three bags with gradients 1, 2, -0.5: h = (2.5)^2, not 1 + 4 + 0.25
+    b = _one_table_batch(4, [[2], [2, 0], [2]], d=1)
+    dS = np.array([[[1.0]], [[2.0]], [[-0.5]]], dtype=np.float32)
+    W = [np.zeros((4, 1), dtype=np.float32)]
+    h = [np.zeros((4, 1), dtype=np.float32)]
+    oracle.emb_bag_bwd_adagrad(W, h, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 1.0, 0.0)
+    assert h[0][2, 0] == np.float32(6.25) and W[0][2, 0] == np.float32(-1.0)
+    assert h[0][0, 0] == np.float32(4.0) and W[0][0, 0] == np.float32(-1.0)
+    assert np.all(h[0][[1, 3]] == 0) and np.all(W[0][[1, 3]] == 0)
+
+
+def test_adagrad_matches_the_library_optimizer_on_dense_gradients():
+    torch = pytest.importorskip("torch")
+    w = gen.custom_workload("ada", K=2, B=40, d=8, rows=30, bag=("uniform", 0, 5))
+    b = gen.make_batch(w)
+    rng = np.random.default_rng(3)
+    tables = _rand_tables(rng, b.rows, w.d)
+    state = [np.zeros_like(t) for t in tables]
+    params = [torch.nn.Parameter(torch.from_numpy(t.copy())) for t in tables]
+    opt = torch.optim.Adagrad(params, lr=0.05, eps=1e-10, initial_accumulator_value=0.0)
+    for step in range(3):
+        dS = rng.standard_normal((w.B, w.K, w.d)).astype(np.float32)
+        # the dense gradient of every table by the library's scatter-add; untouched rows get 0,
+        # for which the dense optimizer changes nothing either
+        for k in range(w.K):
+            dense = torch.zeros(int(b.rows[k]), w.d, dtype=torch.float64)
+            off = b.offsets[k]
+            bag_of = np.repeat(np.arange(w.B), np.diff(off))
+            dense.index_add_(0, torch.from_numpy(b.indices_of(k)),
+                             torch.from_numpy(dS[bag_of, k, :].astype(np.float64)))
+            params[k].grad = dense.to(torch.float32)
+        opt.step()
+        oracle.emb_bag_bwd_adagrad(tables, state, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 0.05, 1e-10)
+        for k in range(w.K):
+            touched = np.unique(b.indices_of(k))
+            lib_w = params[k].detach().numpy()
+            lib_h = opt.state[params[k]]["sum"].numpy()
+            # the library works in fp32 throughout, the oracle in fp64 with one rounding
+            assert np.allclose(tables[k], lib_w, rtol=2e-6, atol=1e-7), (step, k)
+            assert np.allclose(state[k], lib_h, rtol=2e-6, atol=1e-9), (step, k)
+            mask = np.ones(int(b.rows[k]), dtype=bool)
+            mask[touched] = False
+            assert np.all(state[k][mask] == 0)
+
+
+def test_adagrad_fp16_tables_round_once_and_keep_untouched_rows():
+    b = _one_table_batch(5, [[4], [1, 4]], d=2)
+    dS = np.array([[[1.0, 1.0]], [[1.0, 3.0]]], dtype=np.float32)
+    W16 = np.full((5, 2), 0.1, dtype=np.float16)
+    W = [W16.copy()]
+    h = [np.full((5, 2), 5.0, dtype=np.float32)]
+    oracle.emb_bag_bwd_adagrad(W, h, gen.F16, b.indices, b.offsets, b.tbl_off, dS, 0.01, 1e-10)
+    w0 = float(np.float16(0.1))
+    # row 4: g = (2, 4) -> h = (9, 21); row 1: g = (1, 3) -> h = (6, 14)
+    assert np.array_equal(h[0][4], np.array([9.0, 21.0], dtype=np.float32))
+    assert np.array_equal(h[0][1], np.array([6.0, 14.0], dtype=np.float32))
+    want4 = np.array([w0 - 0.01 * 2 / 3.0, w0 - 0.01 * 4 / np.sqrt(21.0)]).astype(np.float16)
+    want1 = np.array([w0 - 0.01 * 1 / np.sqrt(6.0), w0 - 0.01 * 3 / np.sqrt(14.0)]).astype(np.float16)
+    assert np.array_equal(W[0][4].view(np.uint16), want4.view(np.uint16))
+    assert np.array_equal(W[0][1].view(np.uint16), want1.view(np.uint16))
+    assert np.array_equal(W[0][[0, 2, 3]].view(np.uint16), W16[[0, 2, 3]].view(np.uint16))
+    assert np.all(h[0][[0, 2, 3]] == 5.0)
