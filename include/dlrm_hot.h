@@ -172,6 +172,25 @@ int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, in
                              int32_t algo, void* stream);
 
 /*
+ * The same backward with sparse Adagrad in place of the SGD step (Sec. 5.1 trains with "SGD
+ * and Adagrad"; the paper prints no formula: this is the standard element-wise rule applied
+ * to the rows a batch touches, duplicates summed first as for SGD).  For every distinct row r
+ * of table k, with g as in dlrm_emb_bag_bwd_sgd:
+ *   h_k[r,:] <- h_k[r,:] + g*g
+ *   W_k[r,:] <- W_k[r,:] - lr * g / (sqrt(h_k[r,:]) + eps)        (the updated h)
+ * state: device array of K device pointers; state[k] is the fp32 accumulator h_k, row-major
+ * [rows[k], d], 16-byte aligned, owned and initialised by the caller (zeros for a fresh
+ * optimizer), updated in place.  Rows that are not looked up keep W and h bit for bit.
+ * Arithmetic is fp32; fp16/bf16 tables are widened, updated and rounded once.
+ * eps must be > 0 (else DLRM_ERR_BAD_SHAPE).  algo: DLRM_BWD_AUTO, DLRM_BWD_SORT or
+ * DLRM_BWD_SORT_PREPARED (else DLRM_ERR_BAD_ALGO); bitwise reproducible.  Everything else
+ * as for dlrm_emb_bag_bwd_sgd.
+ */
+int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* batch, void* const* state, const float* dS,
+                                 int64_t stride_b, int64_t stride_k, float lr, float eps,
+                                 void* workspace, size_t workspace_bytes, int32_t algo, void* stream);
+
+/*
  * The index-only half of DLRM_BWD_SORT (Sec. 4.1: the indices of a batch are known
  * before its forward pass): partitions the batch's (row, bag) pairs by row inside
  * `workspace`.  It reads indices, offsets, tbl_off and rows only -- no table, no

@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i32]
         L.dlrm_emb_bag_bwd_sgd.restype = i32
         L.dlrm_emb_bag_bwd_sgd.argtypes = [sb, vp, i64, i64, f32, vp, sz, i32, vp]
+        L.dlrm_emb_bag_bwd_adagrad.restype = i32
+        L.dlrm_emb_bag_bwd_adagrad.argtypes = [sb, vp, vp, i64, i64, f32, f32, vp, sz, i32, vp]
         L.dlrm_emb_bag_bwd_prepare.restype = i32
         L.dlrm_emb_bag_bwd_prepare.argtypes = [sb, vp, sz, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
@@ -179,6 +181,24 @@ def dlrm_emb_bag_bwd_sgd(batch: SparseBatch, dS: torch.Tensor, stride_b: int, st
     _check("dlrm_emb_bag_bwd_sgd",
            lib().dlrm_emb_bag_bwd_sgd(batch.ref(), _ptr(dS) + 4 * dS_offset, stride_b, stride_k,
                                       C.c_float(lr), _ptr(workspace), ws_bytes, algo, _stream()))
+
+
+def dlrm_emb_bag_bwd_adagrad(batch: SparseBatch, state_ptrs: torch.Tensor, dS: torch.Tensor, stride_b: int,
+                             stride_k: int, lr: float, eps: float, workspace: Optional[torch.Tensor],
+                             algo: int = BWD_AUTO, dS_offset: int = 0):
+    """state_ptrs: int64 device tensor [K] of the accumulators' addresses (see state_pointers)."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check("dlrm_emb_bag_bwd_adagrad",
+           lib().dlrm_emb_bag_bwd_adagrad(batch.ref(), _ptr(state_ptrs), _ptr(dS) + 4 * dS_offset, stride_b,
+                                          stride_k, C.c_float(lr), C.c_float(eps), _ptr(workspace), ws_bytes,
+                                          algo, _stream()))
+
+
+def state_pointers(state: Sequence[torch.Tensor]) -> torch.Tensor:
+    """Device array of the K accumulators' base addresses; the caller keeps `state` alive."""
+    for h in state:
+        assert h.dtype == torch.float32 and h.is_contiguous()
+    return torch.tensor([h.data_ptr() for h in state], dtype=torch.int64, device=state[0].device)
 
 
 def dlrm_emb_bag_bwd_prepare(batch: SparseBatch, workspace: torch.Tensor):

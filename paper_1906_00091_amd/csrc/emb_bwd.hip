@@ -738,11 +738,17 @@ __device__ inline int sort_bucket_global(const GroupArgs& a, const Bucket& b, So
 // --- 4b. runs -> row updates ------------------------------------------------------------------
 struct UpdArgs {
   void* const* tables;
+  void* const* state;   // Adagrad: K fp32 accumulators shaped like the tables; else unused
   const float* dS;
   int64_t stride_b, stride_k;
-  float lr;
+  float lr, eps;
   int32_t d;
 };
+
+// What is done to a row once its gradient g is summed (Sec. 5.1 names both optimizers):
+//   kSgd     : W <- W - lr * g
+//   kAdagrad : h <- h + g*g (fp32 state), W <- W - lr * g / (sqrt(h) + eps), element-wise
+constexpr int kSgd = 0, kAdagrad = 1;
 
 // The 4 columns [chunk*4, chunk*4+4) of a table row: raw load, and update + store
 // (fp32: W - lr*g; fp16/bf16: widen, update in fp32, one round-to-nearest-even).
@@ -795,10 +801,59 @@ __device__ inline void row_chunk_update_store(char* p, u32x4 raw, f32x4 g, float
     *reinterpret_cast<u32x2*>(p) = b;
   }
 }
-template <int DT>
-__device__ inline void sgd_row_update(char* W, const UpdArgs& u, uint32_t row, int chunk, f32x4 g) {
-  char* p = row_chunk_ptr<DT>(W, u.d, row, chunk);
-  row_chunk_update_store<DT>(p, row_chunk_load<DT>(p), g, u.lr);
+// The same 4 columns of a row together with their optimizer state (none for SGD).
+struct RowRef {
+  char* w;
+  float* h;
+};
+struct RowVal {
+  u32x4 w;
+  f32x4 h;
+};
+template <int DT, int OPT>
+__device__ inline RowRef row_ref(char* W, float* H, int d, uint32_t row, int chunk) {
+  const int64_t e = (int64_t)row * d + chunk * 4;
+  RowRef r;
+  r.w = W + e * Tab<DT>::EB;
+  r.h = OPT == kAdagrad ? H + e : nullptr;
+  return r;
+}
+template <int DT, int OPT>
+__device__ inline RowVal row_load(const RowRef& r) {
+  RowVal v;
+  v.w = row_chunk_load<DT>(r.w);
+  v.h = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  if constexpr (OPT == kAdagrad) v.h = loadf4(r.h);
+  return v;
+}
+template <int DT, int OPT>
+__device__ inline void row_update_store(const RowRef& r, const RowVal& v, f32x4 g, const UpdArgs& u) {
+  if constexpr (OPT == kAdagrad) {
+    f32x4 h, step;
+    h.x = fmaf(g.x, g.x, v.h.x);
+    h.y = fmaf(g.y, g.y, v.h.y);
+    h.z = fmaf(g.z, g.z, v.h.z);
+    h.w = fmaf(g.w, g.w, v.h.w);
+    storef4(r.h, h);
+    step.x = u.lr * g.x / (sqrtf(h.x) + u.eps);
+    step.y = u.lr * g.y / (sqrtf(h.y) + u.eps);
+    step.z = u.lr * g.z / (sqrtf(h.z) + u.eps);
+    step.w = u.lr * g.w / (sqrtf(h.w) + u.eps);
+    row_chunk_update_store<DT>(r.w, v.w, step, 1.0f);  // W - 1 * step, one rounding
+  } else {
+    row_chunk_update_store<DT>(r.w, v.w, g, u.lr);
+  }
+}
+template <int DT, int OPT>
+__device__ inline void row_update(char* W, float* H, const UpdArgs& u, uint32_t row, int chunk, f32x4 g) {
+  const RowRef r = row_ref<DT, OPT>(W, H, u.d, row, chunk);
+  row_update_store<DT, OPT>(r, row_load<DT, OPT>(r), g, u);
+}
+// base of table k's optimizer state (read once per workgroup, like the table base)
+template <int OPT>
+__device__ inline float* state_base(const UpdArgs& u, int k) {
+  if constexpr (OPT == kAdagrad) return static_cast<float*>(u.state[k]);
+  return nullptr;
 }
 
 // Sum dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from i0 + first;
@@ -823,7 +878,7 @@ __device__ inline f32x4 sum_entries(const float* g, int64_t stride_b, const uint
 
 // keys/bags: the bucket's sorted pairs (n of them; LDS or global), heads: LDS list of run starts
 // with heads[nruns] = n.  gpos0: global position of the bucket's first pair.
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                    const uint32_t* keys, const uint32_t* bags, const uint32_t* heads,
                                    uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
@@ -835,30 +890,31 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
   const float* g = u.dS + (int64_t)b.k * u.stride_k + (col_ok ? chunk : 0) * 4;
   // short runs: a lane group takes RU runs per round; the table rows and the first gradient
   // row of all RU runs are requested before any of them is consumed
-  constexpr int RU = 4;
+  constexpr int RU = OPT == kAdagrad ? 2 : 4;  // Adagrad also holds the state rows
   const int cchunk = col_ok ? chunk : 0;
+  float* H = state_base<OPT>(u, b.k);
   for (uint32_t r0 = (uint32_t)grp * RU; r0 < nruns; r0 += NG * RU) {
     uint32_t i0[RU], i1[RU];
-    char* wp[RU];
-    u32x4 wv[RU];
+    RowRef wp[RU];
+    RowVal wv[RU];
     f32x4 acc[RU];
 #pragma unroll
     for (int t = 0; t < RU; ++t) {
       const uint32_t rr = r0 + t < nruns ? r0 + t : nruns - 1;  // the tail repeats the last run
       i0[t] = heads[rr] - h0;
       i1[t] = heads[rr + 1] - h0;
-      wp[t] = row_chunk_ptr<DT>(W, u.d, keys[i0[t]], cchunk);
+      wp[t] = row_ref<DT, OPT>(W, H, u.d, keys[i0[t]], cchunk);
     }
 #pragma unroll
     for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)bags[i0[t]] * u.stride_b);
 #pragma unroll
-    for (int t = 0; t < RU; ++t) wv[t] = row_chunk_load<DT>(wp[t]);
+    for (int t = 0; t < RU; ++t) wv[t] = row_load<DT, OPT>(wp[t]);
 #pragma unroll
     for (int t = 0; t < RU; ++t) {
       const uint32_t len = i1[t] - i0[t];
       if (r0 + t >= nruns || len > (uint32_t)kLongRun) continue;
       if (len > 1) acc[t] += sum_entries<4>(g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
-      if (col_ok) row_chunk_update_store<DT>(wp[t], wv[t], acc[t], u.lr);
+      if (col_ok) row_update_store<DT, OPT>(wp[t], wv[t], acc[t], u);
     }
   }
   // long runs: the whole workgroup per run, lane group s taking entries s, s+NG, ...; the NG
@@ -888,7 +944,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
       f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int s = 0; s < NG; ++s) tot += loadf4(part + s * (G * 4) + chunk * 4);
-      sgd_row_update<DT>(W, u, keys[i0], chunk, tot);
+      row_update<DT, OPT>(W, H, u, keys[i0], chunk, tot);
     }
   }
 }
@@ -948,7 +1004,7 @@ __device__ inline uint32_t run_end_search(const uint32_t* keys, uint32_t lo, uin
 
 // One window of kBktCap positions of a sorted pair list (global memory): the runs whose head
 // lies in the window are reduced and applied; a run may extend past the window.
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                      const uint32_t* keys, const uint32_t* bags, uint32_t w0, int src,
                                      SortLds& s, float* part) {
@@ -975,7 +1031,7 @@ __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const
     if (tid == 0) s.heads[total] = e;
     __syncthreads();
     const uint32_t nlong = collect_long_runs(s, total);
-    reduce_runs<DT, G>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
+    reduce_runs<DT, G, OPT>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
   }
   __syncthreads();
 }
@@ -1005,7 +1061,7 @@ __device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd) {
 
 // Pairs [bk.start, bk.start + bk.n) of pair buffer src, more than kBktCap of them, that no
 // shortcut applies to: queued as a segment when per-row counters fit LDS, else sorted here.
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, const Bucket& bk, char* W,
                                          int src, SortLds& s, float* part) {
   if (bk.low_bits <= kSegMaxBits) {
@@ -1031,10 +1087,10 @@ __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, c
   __syncthreads();
   const uint32_t* keys = a.keys[res] + bk.start;
   const uint32_t* bags = a.vals[res] + bk.start;
-  for (uint32_t w0 = 0; w0 < bk.n; w0 += kBktCap) reduce_window<DT, G>(a, u, bk, W, keys, bags, w0, res, s, part);
+  for (uint32_t w0 = 0; w0 < bk.n; w0 += kBktCap) reduce_window<DT, G, OPT>(a, u, bk, W, keys, bags, w0, res, s, part);
 }
 
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                         SortLds& s, SplitLds& sp, float* part) {
   const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -1065,7 +1121,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   __syncthreads();
   const uint32_t nc = sp.nc;
   if (nc == 0) {  // uniform
-    sort_reduce_large<DT, G>(a, u, b, W, 1, s, part);
+    sort_reduce_large<DT, G, OPT>(a, u, b, W, 1, s, part);
     return;
   }
   uint32_t cd[kCand];
@@ -1197,7 +1253,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   // ---- candidate lists are runs: short ones summed here, those above kHugeRun queued as hot rows
   {
     const uint32_t nlong = collect_long_runs(s, nc);
-    reduce_runs<DT, G>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
+    reduce_runs<DT, G, OPT>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
   }
   // ---- the rest
   Bucket rest = b;
@@ -1206,17 +1262,17 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   __syncthreads();
   if (rest.n == 0) return;  // uniform
   if (rest.n > (uint32_t)kBktCap) {
-    sort_reduce_large<DT, G>(a, u, rest, W, 0, s, part);
+    sort_reduce_large<DT, G, OPT>(a, u, rest, W, 0, s, part);
     return;
   }
   sort_bucket_lds(a, rest, s, 0);
   const uint32_t nruns = compact_heads_lds(s, (int)rest.n);
   const uint32_t nlong = collect_long_runs(s, nruns);
-  reduce_runs<DT, G>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
+  reduce_runs<DT, G, OPT>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
 }
 
-template <int DT, int G>
-__global__ __launch_bounds__(kThreads, 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
+template <int DT, int G, int OPT>
+__global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ SplitLds sp;
   __shared__ float part[kThreads * 4];
@@ -1230,7 +1286,7 @@ __global__ __launch_bounds__(kThreads, 4) void bucket_reduce_kernel(GroupArgs a,
     sort_bucket_lds(a, b, s);
     const uint32_t nruns = compact_heads_lds(s, (int)b.n);
     const uint32_t nlong = collect_long_runs(s, nruns);
-    reduce_runs<DT, G>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
+    reduce_runs<DT, G, OPT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
     return;
   }
   if (b.low_bits == 0) {  // the bucket holds one row: a single run, already in position order
@@ -1240,11 +1296,11 @@ __global__ __launch_bounds__(kThreads, 4) void bucket_reduce_kernel(GroupArgs a,
     }
     __syncthreads();
     const uint32_t nlong = collect_long_runs(s, 1);
-    reduce_runs<DT, G>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
+    reduce_runs<DT, G, OPT>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
                        part);
     return;
   }
-  reduce_oversized<DT, G>(a, u, b, W, s, sp, part);
+  reduce_oversized<DT, G, OPT>(a, u, b, W, s, sp, part);
 }
 
 // --- 4c. oversized buckets ("segments") sorted by one workgroup per tile ------------------------
@@ -1349,7 +1405,7 @@ __global__ __launch_bounds__(kThreads) void segment_sort_kernel(GroupArgs a) {
   }
 }
 
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ float part[kThreads * 4];
@@ -1363,7 +1419,7 @@ __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, U
   b.low_bits = 0;
   char* W = static_cast<char*>(u.tables[b.k]);
   const int dst = (int)(sg.src ^ 1u);
-  reduce_window<DT, G>(a, u, b, W, a.keys[dst] + sg.start, a.vals[dst] + sg.start, t * kBktCap, dst, s, part);
+  reduce_window<DT, G, OPT>(a, u, b, W, a.keys[dst] + sg.start, a.vals[dst] + sg.start, t * kBktCap, dst, s, part);
 }
 
 // --- 5. hot rows: runs too long for one workgroup -------------------------------------------------
@@ -1550,7 +1606,7 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
 
 // A lane group per hot run adds the run's partial sums in bag-group order and updates the row.
 // A launch of its own: the kernel boundary orders it after every partial, at no fence.
-template <int DT, int G>
+template <int DT, int G, int OPT>
 __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdArgs u, int ngroups) {
   constexpr int S = DLRM_WAVE / G;
   const int k = blockIdx.y;
@@ -1561,6 +1617,7 @@ __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdAr
   const int chunk = lane % G;
   if (chunk * 4 >= u.d) return;
   char* W = static_cast<char*>(u.tables[k]);
+  float* H = state_base<OPT>(u, k);
   for (uint32_t r = (blockIdx.x * kNW + wave_id()) * S + lane / G; r < nruns; r += gridDim.x * kNW * S) {
     const float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d + chunk * 4;
     f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -1572,7 +1629,7 @@ __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdAr
       for (int q = 0; q < 8; ++q)
         if (g0 + q < ngroups) sum += v[q];
     }
-    sgd_row_update<DT>(W, u, a.huge_runs[base + r].row, chunk, sum);
+    row_update<DT, OPT>(W, H, u, a.huge_runs[base + r].row, chunk, sum);
   }
 }
 
@@ -1805,38 +1862,65 @@ static int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hip
 // optional pair of caller-owned HIP events recorded around the bucket_reduce launch
 static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
-template <int DT, int G>
+template <int DT, int G, int OPT>
 static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
   const unsigned blocks = ((unsigned)K << g.top_bits) + (unsigned)g.max_over;
   if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return DLRM_ERR_HIP;
-  hipLaunchKernelGGL((bucket_reduce_kernel<DT, G>), dim3(blocks), dim3(kThreads), 0, st, g, u);
+  hipLaunchKernelGGL((bucket_reduce_kernel<DT, G, OPT>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
   const unsigned seg_tiles = (unsigned)(g.seg_tiles_max);
   hipLaunchKernelGGL(segment_sort_kernel, dim3(seg_tiles), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
-  hipLaunchKernelGGL((segment_reduce_kernel<DT, G>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
+  hipLaunchKernelGGL((segment_reduce_kernel<DT, G, OPT>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   const int ng = hot_groups(g.B, u.d);
   hipLaunchKernelGGL((hot_rows_kernel<DT, G>), dim3(ng, K), dim3(kThreads), 0, st, g, u, ng);
   DLRM_CHECK_LAUNCH();
-  hipLaunchKernelGGL((hot_finish_kernel<DT, G>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
+  hipLaunchKernelGGL((hot_finish_kernel<DT, G, OPT>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
 
-template <int DT>
+template <int DT, int OPT>
 static int dispatch_reduce(const GroupArgs& g, const UpdArgs& u, int G, int K, hipStream_t st) {
   switch (G) {
-    case 1: return launch_reduce<DT, 1>(g, u, K, st);
-    case 2: return launch_reduce<DT, 2>(g, u, K, st);
-    case 4: return launch_reduce<DT, 4>(g, u, K, st);
-    case 8: return launch_reduce<DT, 8>(g, u, K, st);
-    case 16: return launch_reduce<DT, 16>(g, u, K, st);
-    case 32: return launch_reduce<DT, 32>(g, u, K, st);
-    case 64: return launch_reduce<DT, 64>(g, u, K, st);
+    case 1: return launch_reduce<DT, 1, OPT>(g, u, K, st);
+    case 2: return launch_reduce<DT, 2, OPT>(g, u, K, st);
+    case 4: return launch_reduce<DT, 4, OPT>(g, u, K, st);
+    case 8: return launch_reduce<DT, 8, OPT>(g, u, K, st);
+    case 16: return launch_reduce<DT, 16, OPT>(g, u, K, st);
+    case 32: return launch_reduce<DT, 32, OPT>(g, u, K, st);
+    case 64: return launch_reduce<DT, 64, OPT>(g, u, K, st);
   }
   return DLRM_ERR_BAD_SHAPE;
+}
+
+static int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout* L);
+
+// The sort path behind both optimizers' entry points: grouping (unless prepared), then the
+// reduce launches with the row update OPT.
+template <int OPT>
+static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* workspace, size_t workspace_bytes,
+                         bool prepared, hipStream_t hs) {
+  const int G = pow2_ceil(s->d / 4);  // lanes per fp32 gradient row
+  if (G > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
+  WsLayout L;
+  int st = check_ws(s, workspace, workspace_bytes, &L);
+  if (st != DLRM_OK) return st;
+  if (s->nnz_total == 0) return DLRM_OK;
+  GroupArgs g;
+  fill_group_args(g, s, L, workspace);
+  if (!prepared) {
+    st = enqueue_partition(s, g, hs);
+    if (st != DLRM_OK) return st;
+  }
+  switch (s->table_dtype) {
+    case DLRM_F32: return dispatch_reduce<DLRM_F32, OPT>(g, u, G, s->K, hs);
+    case DLRM_F16: return dispatch_reduce<DLRM_F16, OPT>(g, u, G, s->K, hs);
+    case DLRM_BF16: return dispatch_reduce<DLRM_BF16, OPT>(g, u, G, s->K, hs);
+  }
+  return DLRM_ERR_BAD_DTYPE;
 }
 
 template <int G>
@@ -1917,29 +2001,41 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
     return DLRM_ERR_BAD_SHAPE;
   }
 
-  WsLayout L;
-  st = check_ws(s, workspace, workspace_bytes, &L);
-  if (st != DLRM_OK) return st;
-  if (s->nnz_total == 0) return DLRM_OK;
-  GroupArgs g;
-  fill_group_args(g, s, L, workspace);
-  if (algo != DLRM_BWD_SORT_PREPARED) {
-    st = enqueue_partition(s, g, hs);
-    if (st != DLRM_OK) return st;
-  }
   UpdArgs u;
   u.tables = s->tables;
+  u.state = nullptr;
   u.dS = dS;
   u.stride_b = stride_b;
   u.stride_k = stride_k;
   u.lr = lr;
+  u.eps = 0.0f;
   u.d = s->d;
-  switch (s->table_dtype) {
-    case DLRM_F32: return dispatch_reduce<DLRM_F32>(g, u, G, s->K, hs);
-    case DLRM_F16: return dispatch_reduce<DLRM_F16>(g, u, G, s->K, hs);
-    case DLRM_BF16: return dispatch_reduce<DLRM_BF16>(g, u, G, s->K, hs);
-  }
-  return DLRM_ERR_BAD_DTYPE;
+  return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo == DLRM_BWD_SORT_PREPARED, hs);
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* const* state, const float* dS,
+                                            int64_t stride_b, int64_t stride_k, float lr, float eps,
+                                            void* workspace, size_t workspace_bytes, int32_t algo,
+                                            void* stream) {
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  if (!dS || !state) return DLRM_ERR_NULL;
+  if ((s->d & 3) || stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0)
+    return DLRM_ERR_BAD_SHAPE;
+  if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
+  if (!(eps > 0.0f)) return DLRM_ERR_BAD_SHAPE;  // h = 0 and g = 0 would divide 0 by 0
+  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_SORT_PREPARED) return DLRM_ERR_BAD_ALGO;
+  UpdArgs u;
+  u.tables = s->tables;
+  u.state = state;
+  u.dS = dS;
+  u.stride_b = stride_b;
+  u.stride_k = stride_k;
+  u.lr = lr;
+  u.eps = eps;
+  u.d = s->d;
+  return run_sort_path<kAdagrad>(s, u, workspace, workspace_bytes, algo == DLRM_BWD_SORT_PREPARED,
+                                 static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* workspace,

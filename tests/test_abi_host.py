@@ -68,6 +68,11 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert prep(_batch(), None, 0) == -4
     assert prep(_batch(), C.c_void_p(0x1000), need - 1) == -4
     assert prep(_batch(K=0), C.c_void_p(0x1000), need) != 0
+    ada = lambda b, st, eps, algo: L.dlrm_emb_bag_bwd_adagrad(C.byref(b), st, ds, 64, 16, C.c_float(0.01),
+                                                              C.c_float(eps), C.c_void_p(0x1000), need, algo, None)
+    assert ada(_batch(), None, 1e-8, hot.BWD_SORT) == -1            # no state
+    assert ada(_batch(), C.c_void_p(0x1000), 0.0, hot.BWD_SORT) == -2   # eps must be positive
+    assert ada(_batch(), C.c_void_p(0x1000), 1e-8, hot.BWD_ATOMIC) == -5
     assert call(_batch(table_dtype=1), C.c_void_p(0x1000), need, hot.BWD_ATOMIC) == -3
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(0, 4, 16, 8, 100, 0) == 0
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 8, 100, 5) == 0

@@ -322,6 +322,88 @@ def test_prepare_on_a_second_stream_then_update_gives_the_same_bits(case):
         assert torch.equal(one[k].view(torch.uint8), two[k].view(torch.uint8))
 
 
+ADAGRAD_CASES = [c for c in BWD_CASES if c[0] in (
+    "tiny-shape", "multi-tile-ragged", "hot-rows", "d48-nonpow2", "f16-d128-fixed32", "bf16-d64",
+    "many-hot-rows", "dominant-rows-large-rest")]
+
+
+@pytest.mark.parametrize("fresh", [False, True], ids=["warm-state", "fresh-state"])
+@pytest.mark.parametrize("case", ADAGRAD_CASES, ids=lambda c: c[0])
+def test_emb_bag_bwd_adagrad_matches_oracle(case, fresh):
+    """h <- h + g^2, W <- W - lr g / (sqrt(h) + eps) on the touched rows (Sec. 5.1's second optimizer).
+    Error model: the fp32 sum g carries |dg| <= n 2^-24 S_g (S_g = sum of |terms|); h + g^2 has only
+    positive terms, so h is compared relative to h0 + S_g^2; d(step)/dg is at most lr / (sqrt(h0) + eps),
+    so W is compared relative to |W| + lr S_g / (sqrt(h0) + eps).  With a fresh state (h0 = 0) that bound is
+    vacuous where g cancels to ~0 (the step is lr*sign(g) there): those elements are left out."""
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("emb_bag_bwd_adagrad %s fresh=%s" % (name, fresh))
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=8)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    rng = np.random.default_rng(12)
+    h0 = [np.zeros((int(r), d), dtype=np.float32) if fresh
+          else rng.uniform(0.01, 1.0, size=(int(r), d)).astype(np.float32) for r in b.rows]
+    tables = upload_tables(host, dtype)
+    state = [torch.from_numpy(h.copy()).to(DEV) for h in h0]
+    sptr = hot.state_pointers(state)
+    sb = make_sparse_batch(b, tables)
+    F = K + 1
+    dS = b.dS()
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+    ws = hot.alloc_workspace(sb)
+    lr, eps = float(np.float32(0.05)), float(np.float32(1e-8))
+    hot.dlrm_emb_bag_bwd_adagrad(sb, sptr, dT, F * d, d, lr, eps, ws, dS_offset=d)
+    torch.cuda.synchronize()
+    ref_w = [t.copy() for t in host]
+    ref_h = [h.copy() for h in h0]
+    oracle.emb_bag_bwd_adagrad(ref_w, ref_h, dtype, b.indices, b.offsets, b.tbl_off, dS, lr, eps)
+    # S_g per touched row: the oracle's SGD on zero tables with |dS| and lr = -1
+    sg = [np.zeros((int(r), d), dtype=np.float32) for r in b.rows]
+    uniq, _ = oracle.emb_bag_bwd_sgd(sg, gen.F32, b.indices, b.offsets, b.tbl_off, np.abs(dS), -1.0)
+    for k in range(K):
+        got_w = table_to_numpy(tables[k], dtype)
+        got_h = state[k].cpu().numpy()
+        mask = np.ones(int(b.rows[k]), dtype=bool)
+        mask[uniq[k]] = False
+        assert np.array_equal(got_w[mask].view(np.uint8), host[k][mask].view(np.uint8))
+        assert np.array_equal(got_h[mask].view(np.uint32), h0[k][mask].view(np.uint32))
+        if len(uniq[k]) == 0:
+            continue
+        u = uniq[k]
+        S = sg[k][u].astype(np.float64)
+        assert rel_err(got_h[u], ref_h[k][u], h0[k][u] + S * S) <= 1e-5
+        gw, rw = widen_host(got_w[u], dtype), widen_host(ref_w[k][u], dtype)
+        w0 = np.abs(widen_host(host[k][u], dtype)).astype(np.float64)
+        if fresh:
+            g_ref = np.sqrt(ref_h[k][u].astype(np.float64))      # |g| (h0 = 0)
+            ok = g_ref >= 1e-3 * S
+            assert ok.mean() > 0.9
+            scale = w0 + lr
+            err = np.abs(gw.astype(np.float64) - rw.astype(np.float64)) / np.maximum(scale, SCALE_FLOOR[dtype])
+            assert err[ok].max() <= TOL[dtype]
+        else:
+            scale = w0 + lr * S / (np.sqrt(h0[k][u].astype(np.float64)) + eps)
+            assert rel_err(gw, rw, scale, SCALE_FLOOR[dtype]) <= TOL[dtype]
+    # bitwise reproducible, and the same bits when the grouping was prepared on another stream
+    tables2 = upload_tables(host, dtype)
+    state2 = [torch.from_numpy(h.copy()).to(DEV) for h in h0]
+    sb2 = make_sparse_batch(b, tables2)
+    side = torch.cuda.Stream()
+    done = torch.cuda.Event()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        hot.dlrm_emb_bag_bwd_prepare(sb2, ws)
+        done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    hot.dlrm_emb_bag_bwd_adagrad(sb2, hot.state_pointers(state2), dT, F * d, d, lr, eps, ws,
+                                 algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+    torch.cuda.synchronize()
+    for k in range(K):
+        assert torch.equal(tables2[k].view(torch.uint8), tables[k].view(torch.uint8))
+        assert torch.equal(state2[k], state[k])
+
+
 def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
     lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
     b = gen.batch_from_lists([8, 8, 8], lists, d=8)
