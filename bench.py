@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = multi-hot bandwidth)")
     ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
+    ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adagrad"],
+                    help="row update of the fused backward (the metric is quoted on sgd)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="group the (row, bag) pairs inside the backward call instead of on a second "
                          "stream beside the forward pass")
@@ -112,6 +114,18 @@ def main():
     R = torch.empty((B, d + P), dtype=torch.float32, device=dev)
     dT = torch.empty((B, F, d), dtype=torch.float32, device=dev)
     lr = float(np.float32(w.lr))
+    adagrad = args.optimizer == "adagrad"
+    if adagrad:
+        assert args.algo != "atomic", "adagrad runs on the sort path only"
+        state = [torch.zeros_like(t, dtype=torch.float32) for t in tables]
+        state_ptrs = hot.state_pointers(state)
+        eps = 1e-8
+
+    def backward(sb, algo_code):
+        if adagrad:
+            hot.dlrm_emb_bag_bwd_adagrad(sb, state_ptrs, dT, F * d, d, lr, eps, ws, algo=algo_code, dS_offset=d)
+        else:
+            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo_code, dS_offset=d)
 
     stages = ["place_dense", "emb_bag_fwd", "interact_dot_fwd", "interact_dot_bwd", "emb_bag_bwd_sgd"]
     # The grouping of the batch's (row, bag) pairs needs the indices only: it is enqueued on a
@@ -168,10 +182,10 @@ def main():
             hot.dlrm_profile_reduce_kernel(red[0], red[1])
         if overlap:
             torch.cuda.current_stream().wait_event(prep_done)
-            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+            backward(sb, hot.BWD_SORT_PREPARED)
             upd_done.record()
         else:
-            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo, dS_offset=d)
+            backward(sb, algo)
         if ev is not None:
             ev[5].record()
 
@@ -210,7 +224,8 @@ def main():
     nnz_mean = mean("nnz")
     lookups_per_s = nnz_mean / (ms_per_step * 1e-3)
     emb_ms = stage_ms["emb_bag_fwd"] + stage_ms["emb_bag_bwd_sgd"]
-    emb_bytes = mean("fwd") + mean("bwd")
+    bwd_bytes = mean("bwd") + (2 * mean("U") * d * 4 if adagrad else 0.0)
+    emb_bytes = mean("fwd") + bwd_bytes
 
     # ---- roofline of the dominant kernel.  Both embedding kernels are HBM-bound gathers /
     # scatters; the forward call is one kernel (its call events time it), the backward's
@@ -224,7 +239,9 @@ def main():
         red_ms /= args.steps
     # algorithmic bytes of one bucket_reduce launch: the sorted (row, bag) pairs (8 B per lookup),
     # every pooled-vector gradient once, every touched row read and written once
-    red_bytes = float(np.mean([abytes[i]["nnz"] * 8 + K * B * d * 4 + 2 * abytes[i]["U"] * d * eb for i in ids]))
+    # (Adagrad: plus every touched row of the fp32 state read and written once)
+    row_rw = d * eb + (d * 4 if adagrad else 0)
+    red_bytes = float(np.mean([abytes[i]["nnz"] * 8 + K * B * d * 4 + 2 * abytes[i]["U"] * row_rw for i in ids]))
     kernels = {
         "emb_fwd_kernel": (mean("fwd"), stage_ms["emb_bag_fwd"]),
         "bucket_reduce_kernel": (red_bytes, red_ms),
@@ -234,7 +251,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.config, dom)),
+                "traffic": MEASURED_TRAFFIC.get((args.config, dom)) if not adagrad else None,
                 "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_ms": round(dom_ms, 5),
                 "other_kernels": {n: {"algorithmic_bytes_per_launch": int(v[0]), "avg_launch_ms": round(v[1], 5),
                                       "achieved": round(v[0] / (v[1] * 1e-3) / 1e9, 1) if v[1] > 0 else None}
@@ -249,7 +266,7 @@ def main():
         "config": {"workload": "%d:%s" % (args.config, w.name), "tables": K, "batch": B, "dim": d,
                    "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
                    "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
-                   "bwd_algo": args.algo, "lr": w.lr,
+                   "bwd_algo": args.algo, "optimizer": args.optimizer, "lr": w.lr,
                    "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
         "emb_fwd_bwd": {"ms": round(emb_ms, 5), "lookups_per_s": round(nnz_mean / (emb_ms * 1e-3), 1),
@@ -259,7 +276,7 @@ def main():
         "stage_ms_source": "separate single-stream pass of %d steps after the timed region" % nbk,
         "stage_algorithmic_GBps": {
             "emb_bag_fwd": round(mean("fwd") / (stage_ms["emb_bag_fwd"] * 1e-3) / 1e9, 1),
-            "emb_bag_bwd_sgd": round(mean("bwd") / (stage_ms["emb_bag_bwd_sgd"] * 1e-3) / 1e9, 1),
+            "emb_bag_bwd_sgd": round(bwd_bytes / (stage_ms["emb_bag_bwd_sgd"] * 1e-3) / 1e9, 1),
             "interact_dot_fwd": round(mean("int_fwd") / (stage_ms["interact_dot_fwd"] * 1e-3) / 1e9, 1),
             "interact_dot_bwd": round(mean("int_bwd") / (stage_ms["interact_dot_bwd"] * 1e-3) / 1e9, 1)},
         "roofline": roofline,
@@ -288,6 +305,7 @@ def main():
                                    else a.numpy())
                 idx[b.tbl_off[k]:b.tbl_off[k + 1]] = np.searchsorted(u, b.indices_of(k))
             sample = "whole steps of workload %d on the touched rows only (compacted tables)" % args.config
+        host_state = [np.zeros(t.shape, dtype=np.float32) for t in host_tables] if adagrad else None
         nsteps, t_cpu = 0, 0.0
         while t_cpu < args.cpu_seconds and nsteps < 1000:
             c0 = time.perf_counter()
@@ -295,8 +313,11 @@ def main():
             Th = np.concatenate([b.x[:, None, :], S.astype(np.float32)], axis=1)
             oracle.interact_dot_fwd(Th)
             dTh = oracle.interact_dot_bwd(Th, b.dR)
-            oracle.emb_bag_bwd_sgd(host_tables, w.dtype, idx, b.offsets, b.tbl_off,
-                                   np.ascontiguousarray(dTh[:, 1:, :], dtype=np.float32), lr)
+            dSh = np.ascontiguousarray(dTh[:, 1:, :], dtype=np.float32)
+            if adagrad:
+                oracle.emb_bag_bwd_adagrad(host_tables, host_state, w.dtype, idx, b.offsets, b.tbl_off, dSh, lr, eps)
+            else:
+                oracle.emb_bag_bwd_sgd(host_tables, w.dtype, idx, b.offsets, b.tbl_off, dSh, lr)
             t_cpu += time.perf_counter() - c0
             nsteps += 1
         out["cpu_baseline"] = {"value": round(b.nnz * nsteps / t_cpu, 1), "unit": "lookups/s",

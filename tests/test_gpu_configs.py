@@ -148,3 +148,72 @@ def test_config4_large_onehot():
 
 def test_config5_hotrow_stress():
     _check_config(5)
+
+
+def _check_adagrad_config(cfg_id, h_init=0.1, steps=2):
+    """The Adagrad backward at a workload's full size, in the launch configuration the benchmark
+    uses (grouping prepared on a second stream for >= 200K lookups): two steps with the same
+    gradient, W and h of every touched row against the oracle, untouched rows sampled."""
+    w = gen.WORKLOADS[cfg_id]
+    b = gen.make_batch(w)
+    _say("adagrad %s: nnz=%d" % (w.name, b.nnz))
+    tables = device_hash_tables(b)
+    state = [torch.full(t.shape, h_init, dtype=torch.float32, device=DEV) for t in tables]
+    sptr = hot.state_pointers(state)
+    sb = make_sparse_batch(b, tables)
+    F, B, d, K = w.F, w.B, w.d, w.K
+    dS_h = b.dS()
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS_h).to(DEV)
+    ws = hot.alloc_workspace(sb)
+    lr, eps = float(np.float32(w.lr)), float(np.float32(1e-8))
+    side, done = torch.cuda.Stream(), torch.cuda.Event()
+    torch.cuda.synchronize()
+    for _ in range(steps):
+        if b.nnz >= 200_000:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                hot.dlrm_emb_bag_bwd_prepare(sb, ws)
+                done.record(side)
+            torch.cuda.current_stream().wait_event(done)
+            hot.dlrm_emb_bag_bwd_adagrad(sb, sptr, dT, F * d, d, lr, eps, ws, algo=hot.BWD_SORT_PREPARED,
+                                         dS_offset=d)
+        else:
+            hot.dlrm_emb_bag_bwd_adagrad(sb, sptr, dT, F * d, d, lr, eps, ws, dS_offset=d)
+    torch.cuda.synchronize()
+    comp = Compact(b)
+    ref_w = [t.copy() for t in comp.tables]
+    ref_h = [np.full(t.shape, h_init, dtype=np.float32) for t in comp.tables]
+    for _ in range(steps):
+        oracle.emb_bag_bwd_adagrad(ref_w, ref_h, w.dtype, comp.indices, b.offsets, b.tbl_off, dS_h, lr, eps)
+    sg = [np.zeros(t.shape, dtype=np.float32) for t in comp.tables]
+    oracle.emb_bag_bwd_sgd(sg, gen.F32, comp.indices, b.offsets, b.tbl_off, np.abs(dS_h), -1.0)
+    got_w = comp.gather_device(tables, w.dtype)
+    got_h = comp.gather_device(state, gen.F32)
+    worst_w = worst_h = 0.0
+    for k in range(K):
+        S = sg[k].astype(np.float64)
+        worst_h = max(worst_h, rel_err(got_h[k], ref_h[k], h_init + steps * S * S))
+        scale = np.abs(widen_host(comp.tables[k], w.dtype)) + steps * lr * S / (np.sqrt(h_init) + eps)
+        worst_w = max(worst_w, rel_err(widen_host(got_w[k], w.dtype), widen_host(ref_w[k], w.dtype), scale,
+                                       SCALE_FLOOR[w.dtype]))
+    _say("adagrad: W rel err %.2e, h rel err %.2e" % (worst_w, worst_h))
+    assert worst_h <= 1e-5 and worst_w <= TOL[w.dtype]
+    rng = np.random.default_rng(98)
+    for k in range(K):
+        m = int(b.rows[k])
+        cand = np.setdiff1d(np.unique(rng.integers(0, m, size=min(20000, m))), comp.uniq[k])
+        if len(cand) == 0:
+            continue
+        sel = torch.from_numpy(cand).to(DEV)
+        got = table_to_numpy(tables[k].index_select(0, sel), w.dtype)
+        assert np.array_equal(got.view(np.uint8), gen.init_rows(b.seed, k, m, w.d, w.dtype, cand).view(np.uint8))
+        assert bool(torch.all(state[k].index_select(0, sel) == h_init))
+
+
+def test_config3_multihot_bandwidth_adagrad():
+    _check_adagrad_config(3)
+
+
+def test_config2_clicklog_onehot_adagrad():
+    _check_adagrad_config(2)
