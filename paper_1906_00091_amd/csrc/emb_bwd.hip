@@ -52,6 +52,9 @@ constexpr int kFusedScanMaxTiles = 512;         // fold the scan into the scatte
 constexpr int kSegMaxBits = 13;                 // oversized buckets with at most this many low bits are
                                                 // sorted by many workgroups (per-row counters in LDS)
 constexpr int kSegKeys = 1 << kSegMaxBits;
+constexpr int kSmallBatch = 65536;              // up to this many lookups the four launches that only
+                                                // serve oversized buckets and hot rows cost more (~16 us)
+                                                // than one workgroup doing that work in place ever could
 constexpr int kCandMin = 128;                   // a row with this many of an oversized bucket's first
                                                 // kBktCap pairs is split off before any sorting
 constexpr int kCand = kBktCap / kCandMin;       // at most this many such rows
@@ -134,6 +137,8 @@ struct GroupArgs {            // everything the grouping kernels need
   int32_t nt_max;
   int32_t top_bits;           // bits of the partition digit (0..kMaxTopBits)
   int32_t fused_scan;         // 1: the scatter derives its offsets from the raw tile counts
+  int32_t no_tail;            // 1: small batch, the segment and hot-row launches are left out and
+                              //    bucket_reduce handles whatever they would have taken
   uint32_t* keys[2];
   uint32_t* vals[2];
   uint32_t* hist;
@@ -923,7 +928,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     const uint32_t r = longs[q];
     const uint32_t i0 = heads[r] - h0, i1 = heads[r + 1] - h0;
     const uint32_t len = i1 - i0;
-    if (len > (uint32_t)kHugeRun) {  // queue for the multi-workgroup pass
+    if (len > (uint32_t)kHugeRun && !a.no_tail) {  // queue for the multi-workgroup pass
       if (threadIdx.x == 0) {
         HugeRun hr;
         hr.k = (uint32_t)b.k;
@@ -1064,7 +1069,7 @@ __device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd) {
 template <int DT, int G, int OPT>
 __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, const Bucket& bk, char* W,
                                          int src, SortLds& s, float* part) {
-  if (bk.low_bits <= kSegMaxBits) {
+  if (bk.low_bits <= kSegMaxBits && !a.no_tail) {
     if (threadIdx.x == 0) {
       const uint32_t nt = (bk.n + kBktCap - 1) / kBktCap;
       // one 64-bit counter hands out the slot and the first tile together, so that the list is
@@ -1821,6 +1826,7 @@ static void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   if (tb > kb) tb = kb;
   g.top_bits = tb;
   g.fused_scan = L.nt_max <= kFusedScanMaxTiles ? 1 : 0;
+  g.no_tail = s->nnz_total <= kSmallBatch ? 1 : 0;
   for (int i = 0; i < 2; ++i) {
     g.keys[i] = reinterpret_cast<uint32_t*>(base + L.keys[i]);
     g.vals[i] = reinterpret_cast<uint32_t*>(base + L.vals[i]);
@@ -1869,6 +1875,7 @@ static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_
   hipLaunchKernelGGL((bucket_reduce_kernel<DT, G, OPT>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
+  if (g.no_tail) return DLRM_OK;
   const unsigned seg_tiles = (unsigned)(g.seg_tiles_max);
   hipLaunchKernelGGL(segment_sort_kernel, dim3(seg_tiles), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
