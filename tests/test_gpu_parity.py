@@ -133,7 +133,11 @@ def test_emb_bag_fwd_single_index_bags_copy_rows_bitwise_even_in_the_long_bag_ke
 
 # ------------------------------------------------------------------ interaction
 INT_CASES = [(1, 2, 4), (37, 2, 16), (128, 9, 16), (300, 9, 64), (77, 27, 16), (41, 27, 128),
-             (19, 65, 128), (5, 3, 256), (1030, 5, 8)]
+             (19, 65, 128), (5, 3, 256), (1030, 5, 8),
+             # every count of 16-row blocks (1..8), F = 1, block boundaries (17, 18, 33, 34), the largest
+             # F and d, and d that is no multiple of 16 / 64
+             (3, 1, 8), (9, 17, 12), (9, 18, 20), (7, 33, 16), (6, 34, 36), (4, 50, 72), (3, 66, 64),
+             (3, 90, 24), (2, 100, 40), (2, 113, 4), (2, 128, 256)]
 
 
 @pytest.mark.parametrize("B,F,d", INT_CASES)
