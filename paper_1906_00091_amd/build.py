@@ -11,7 +11,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libdlrm_hot.so")
-SOURCES = ["util.hip", "emb_fwd.hip", "emb_bwd.hip", "interact.hip"]
+SOURCES = ["bwd_reduce_sgd.hip", "bwd_reduce_adagrad.hip", "bwd_tail.hip", "bwd_partition.hip", "bwd_export.hip",
+           "emb_bwd.hip", "emb_fwd.hip", "interact.hip", "util.hip"]
 
 # -packed-fp32-ops: keep hipcc from forming packed fp32 VALU instructions.
 HIPCC_FLAGS = [
@@ -55,7 +56,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         # the host pass warns that it does not know -packed-fp32-ops: harmless, not shown
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)

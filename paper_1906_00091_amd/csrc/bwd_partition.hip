@@ -1,0 +1,253 @@
+// Backward grouping, steps 1-3: most-significant-digit partition of the (row, bag) pairs.
+#include "bwd_common.h"
+
+namespace dlrm {
+
+// --- 1. per-tile histogram of the partition digit ----------------------------------
+__global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
+  __shared__ uint32_t h[kMaxBuckets];
+  __shared__ uint32_t smem[kNW + 1];
+  TileInfo ti;
+  if (!find_tile(a, blockIdx.x, ti, smem)) return;
+  const int nb = 1 << a.top_bits;
+  for (int i = threadIdx.x; i < nb; i += kThreads) h[i] = 0;
+  __syncthreads();
+  const int64_t* idx = a.indices + ti.start;
+  const int shift = top_shift(a, ti.k);
+  const uint32_t mask = (uint32_t)nb - 1;
+  for (int i = threadIdx.x; i < ti.count; i += kThreads)
+    atomicAdd(&h[((uint32_t)idx[i] >> shift) & mask], 1u);
+  __syncthreads();
+  for (int i = threadIdx.x; i < nb; i += kThreads) a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
+  if (blockIdx.x == 0 && threadIdx.x == 0) {  // consumed by later launches of the same call
+    *a.over_cnt = 0u;
+    for (int k = 0; k < a.K; ++k) a.hot_cnt[k] = 0u;
+    a.seg_meta[0] = 0u;
+    a.seg_meta[1] = 0u;
+    a.seg_meta[2] = 0u;
+  }
+}
+
+// --- 2. per-table scan (large batches only): counts -> destination offsets ------------
+// One workgroup per table walks (digit, tile) in digit-major order with a running carry
+// that starts at the table's slice, so every table is scattered inside its own slice.
+__global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
+  __shared__ uint32_t smem[1024 / DLRM_WAVE + 1];
+  const int k = blockIdx.x;
+  // first tile of table k = tiles of all earlier tables
+  uint32_t t0 = 0;
+  for (int j = 0; j < k; ++j) t0 += (uint32_t)((a.tbl_off[j + 1] - a.tbl_off[j] + kTile - 1) / kTile);
+  const int nt = (int)((a.tbl_off[k + 1] - a.tbl_off[k] + kTile - 1) / kTile);
+  const int nb = 1 << a.top_bits;
+  uint32_t carry = (uint32_t)a.tbl_off[k];
+  if (nt <= 0) {
+    for (int i = threadIdx.x; i < nb; i += 1024) a.bucket_start[(size_t)k * nb + i] = carry;
+    return;
+  }
+  const int64_t n = (int64_t)nt * nb;
+  for (int64_t e0 = 0; e0 < n; e0 += 1024) {
+    const int64_t e = e0 + threadIdx.x;
+    uint32_t v = 0;
+    size_t addr = 0;
+    int digit = 0, t = 0;
+    if (e < n) {
+      digit = (int)(e / nt);
+      t = (int)(e - (int64_t)digit * nt);
+      addr = (size_t)digit * a.nt_max + t0 + t;
+      v = a.hist[addr];
+    }
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan<1024>(v, smem, &total);
+    if (e < n) {
+      a.hist[addr] = carry + ex;
+      if (t == 0) a.bucket_start[(size_t)k * nb + digit] = carry + ex;
+    }
+    carry += total;
+  }
+  __syncthreads();  // this workgroup's bucket_start writes are visible to it
+  for (int dg = threadIdx.x; dg < nb; dg += 1024) {
+    const uint32_t st = a.bucket_start[(size_t)k * nb + dg];
+    const uint32_t en = dg + 1 < nb ? a.bucket_start[(size_t)k * nb + dg + 1] : (uint32_t)a.tbl_off[k + 1];
+    if (en - st > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(k * nb + dg);
+  }
+}
+
+
+// --- 3. stable scatter into buckets ---------------------------------------------------
+__global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
+  __shared__ uint32_t wcnt[kNW][kMaxBuckets];
+  __shared__ uint32_t gofs[kMaxBuckets];
+  __shared__ uint32_t skey[kTile];
+  __shared__ uint32_t sval[kTile];
+  __shared__ uint32_t smem[kNW + 1];
+  __shared__ int sflag[1];
+  TileInfo ti;
+  if (!find_tile(a, blockIdx.x, ti, smem)) return;
+  const int nb = 1 << a.top_bits;
+  const uint32_t mask = (uint32_t)nb - 1;
+  const int lane = lane_id(), w = wave_id();
+  const int tid = threadIdx.x;
+
+  // ---- requested first so that their latency hides behind the bag search: the tile's row ids
+  // (wave-striped) and, for small batches, this digit's counts in all tiles of the table
+  const int64_t* kin = a.indices + ti.start;
+  const int shift = top_shift(a, ti.k);
+  uint32_t key[kItems], val[kItems], dg[kItems], rnk[kItems];
+  bool ok[kItems];
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
+    ok[j] = li < ti.count;
+    key[j] = ok[j] ? (uint32_t)kin[li] : 0xFFFFFFFFu;
+    dg[j] = (key[j] >> shift) & mask;
+  }
+  // thread t owns the partition digits t*kDPT .. t*kDPT + kDPT-1
+  uint32_t goff[kDPT], before[kDPT], total[kDPT];
+#pragma unroll
+  for (int q = 0; q < kDPT; ++q) {
+    const int dgt = tid * kDPT + q;
+    goff[q] = before[q] = total[q] = 0;
+    if (dgt >= nb) continue;
+    if (a.fused_scan) {
+      const uint32_t* hrow = a.hist + (size_t)dgt * a.nt_max + ti.t0;
+      int t = 0;
+      for (; t + 8 <= ti.nt; t += 8) {
+        uint32_t c[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) c[z] = hrow[t + z];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+          total[q] += c[z];
+          before[q] += t + z < ti.t ? c[z] : 0u;
+        }
+      }
+      for (; t < ti.nt; ++t) {
+        const uint32_t c = hrow[t];
+        total[q] += c;
+        before[q] += t < ti.t ? c : 0u;
+      }
+    } else {
+      goff[q] = a.hist[(size_t)dgt * a.nt_max + blockIdx.x];
+    }
+  }
+
+  // ---- bag of every position of the tile, from the offsets
+  // b0 = the bag holding the tile's first position: last b with off[b] <= P0.
+  const int64_t* off = a.offsets + (int64_t)ti.k * (a.B + 1);
+  const int64_t P0 = ti.start - ti.tbl_start;
+  int lo = 0, hi = a.B;  // off[lo] <= P0 (off[0] = 0); the answer lies in [lo, hi)
+  while (hi - lo > 1) {   // 256-ary search, uniform
+    const int step = (hi - lo + kThreads - 1) / kThreads;
+    const int q = lo + (tid + 1) * step;
+    const int pred = (q < hi && off[q] <= P0) ? 1 : 0;
+    const int cnt = __syncthreads_count(pred);   // offsets are monotone: the first cnt probes pass
+    const int nlo = lo + cnt * step;
+    const int nhi = nlo + step < hi ? nlo + step : hi;
+    lo = nlo;
+    hi = nhi;
+  }
+  const int b0 = lo;
+  for (int i = tid; i < kTile; i += kThreads) skey[i] = 0;  // skey doubles as the bag-start counters
+  for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&wcnt[0][0])[i] = 0;
+  __syncthreads();
+  for (int base = b0 + 1;; base += kThreads) {  // bags that start inside the tile (after P0)
+    const int b = base + tid;
+    if (tid == 0) sflag[0] = (b >= a.B || off[b] >= P0 + ti.count) ? 1 : 0;
+    if (b < a.B) {
+      const int64_t ob = off[b];
+      if (ob < P0 + ti.count) atomicAdd(&skey[(int)(ob - P0)], 1u);
+    }
+    __syncthreads();
+    const int done = sflag[0];
+    __syncthreads();
+    // monotone offsets: once this round's first bag starts past the tile, every later one does;
+    // a round whose first bag is inside may still have later bags inside, so go on
+    if (done) break;
+  }
+  {  // inclusive prefix of the start counters, thread t owning positions [t*kItems, (t+1)*kItems)
+    uint32_t c[kItems], s = 0;
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      c[j] = skey[tid * kItems + j];
+      s += c[j];
+    }
+    uint32_t total;
+    uint32_t run = block_exclusive_scan<kThreads>(s, smem, &total);
+#pragma unroll
+    for (int j = 0; j < kItems; ++j) {
+      run += c[j];
+      sval[tid * kItems + j] = (uint32_t)b0 + run;
+    }
+  }
+  __syncthreads();
+
+  // ---- bags of this thread's (wave-striped) positions, then rank by partition digit
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
+    val[j] = ok[j] ? sval[li] : 0u;
+  }
+  rank_items<kItems, kMaxBuckets>(dg, ok, a.top_bits, wcnt, rnk);
+  __syncthreads();
+
+  // ---- destination offsets of this tile's digits
+  if (a.fused_scan) {
+    // few tiles: the raw counts of the table's tiles were summed above instead of a separate scan
+    uint32_t sum = 0, all;
+#pragma unroll
+    for (int q = 0; q < kDPT; ++q) sum += total[q];
+    uint32_t base = block_exclusive_scan<kThreads>(sum, smem, &all);
+#pragma unroll
+    for (int q = 0; q < kDPT; ++q) {
+      const int dgt = tid * kDPT + q;
+      goff[q] = (uint32_t)ti.tbl_start + base + before[q];
+      if (ti.t == 0 && dgt < nb) {
+        a.bucket_start[(size_t)ti.k * nb + dgt] = (uint32_t)ti.tbl_start + base;
+        if (total[q] > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(ti.k * nb + dgt);
+      }
+      base += total[q];
+    }
+  }
+  uint32_t lofs[kDPT], tot[kDPT];
+  digit_offsets<kMaxBuckets>(nb, wcnt, smem, lofs, tot);
+#pragma unroll
+  for (int q = 0; q < kDPT; ++q) {
+    const int dgt = tid * kDPT + q;
+    if (dgt < nb) gofs[dgt] = goff[q] - lofs[q];
+  }
+  __syncthreads();
+
+  // ---- stage in LDS in sorted order so that one digit's global writes are contiguous
+#pragma unroll
+  for (int j = 0; j < kItems; ++j) {
+    if (ok[j]) {
+      const uint32_t lp = wcnt[w][dg[j]] + rnk[j];
+      skey[lp] = key[j];
+      sval[lp] = val[j];
+    }
+  }
+  __syncthreads();
+  uint32_t* kout = a.keys[1];
+  uint32_t* vout = a.vals[1];
+  for (int lp = tid; lp < ti.count; lp += kThreads) {
+    const uint32_t kk = skey[lp];
+    const uint32_t dst = gofs[(kk >> shift) & mask] + (uint32_t)lp;
+    kout[dst] = kk;
+    vout[dst] = sval[lp];
+  }
+}
+
+
+int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_t st) {
+  hipLaunchKernelGGL(bucket_hist_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  DLRM_CHECK_LAUNCH();
+  if (!g.fused_scan) {
+    hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(1024), 0, st, g);
+    DLRM_CHECK_LAUNCH();
+  }
+  hipLaunchKernelGGL(bucket_scatter_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  DLRM_CHECK_LAUNCH();
+  return DLRM_OK;
+}
+
+}  // namespace dlrm
