@@ -4,8 +4,10 @@
 // HBM-bound gather.  A table row is d*e bytes; a lane moves 16 bytes
 // (global_load_dwordx4), so a row occupies a "lane group" of G = pow2(d*e/16)
 // lanes and a 64-wide wavefront carries S = 64/G rows per load instruction.
+//   * short kernel: every lane group owns 4 consecutive one-row bags (one-hot batches:
+//     a pure gather whose only parallelism is across bags).
 //   * group kernel: every lane group owns one bag and walks it with U loads in
-//     flight (one-hot and short bags: a pure gather).
+//     flight (short bags).
 //   * wave kernel : the whole wavefront owns one bag; its 64 indices per chunk are
 //     fetched with one coalesced load and handed to the lane groups through
 //     cross-lane reads; group s takes positions s, s+S, ...; the S partial sums
@@ -80,6 +82,63 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// One-hot and near one-hot batches: a bag is one row, so a lane group that owns a single bag
+// has one dependent chain (offsets -> index -> row) and nothing else in flight.  Here it owns
+// NB consecutive bags and walks their chains side by side.
+template <int DT, int G, int NB>
+__global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
+  constexpr int E = Tab<DT>::ELEMS;
+  constexpr int S = DLRM_WAVE / G;
+  const int lane = lane_id();
+  const int slot = lane / G, chunk = lane % G;
+  const uint32_t nbags = (uint32_t)a.K * (uint32_t)a.B;
+  const uint32_t bag0 = ((blockIdx.x * (blockDim.x >> 6) + wave_id()) * S + slot) * NB;
+  if (bag0 >= nbags || chunk >= a.chunks) return;  // no cross-lane ops below
+  const int64_t row_bytes = (int64_t)a.chunks * 16;
+  int k[NB], b[NB];
+  int64_t p0[NB], p1[NB];
+  const int64_t* idx[NB];
+  const char* W[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    const uint32_t bag = bag0 + j < nbags ? bag0 + j : nbags - 1;  // the tail repeats the last bag
+    k[j] = (int)(bag / (uint32_t)a.B);
+    b[j] = (int)(bag - (uint32_t)k[j] * (uint32_t)a.B);
+    const int64_t* off = a.offsets + (int64_t)k[j] * (a.B + 1);
+    p0[j] = off[b[j]];
+    p1[j] = off[b[j] + 1];
+    idx[j] = a.indices + a.tbl_off[k[j]];
+    W[j] = static_cast<const char*>(a.tables[k[j]]) + chunk * 16;
+  }
+  int64_t r[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    r[j] = 0;  // an empty bag fetches row 0 (every table has one) and drops it
+    if (p1[j] > p0[j]) r[j] = idx[j][p0[j]];
+  }
+  u32x4 v[NB];
+#pragma unroll
+  for (int j = 0; j < NB; ++j) v[j] = load16(W[j] + r[j] * row_bytes);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) {
+    if (bag0 + j >= nbags) continue;
+    float acc[E];
+    Tab<DT>::widen(v[j], acc);  // a one-index bag is a bit copy of its row
+    if (p1[j] <= p0[j]) {
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] = 0.0f;
+    }
+    for (int64_t p = p0[j] + 1; p < p1[j]; ++p) {  // the occasional longer bag
+      float f[E];
+      Tab<DT>::widen(load16(W[j] + idx[j][p] * row_bytes), f);
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] += f[i];
+    }
+    write_pooled<DT>(a.out + (int64_t)b[j] * a.stride_b + (int64_t)k[j] * a.stride_k + chunk * E, acc);
+  }
+}
+
+// ---------------------------------------------------------------------------
 template <int DT, int G, int U>
 __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
@@ -140,11 +199,17 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+constexpr int kShortBags = 4;  // bags per lane group of the short-bag kernel
+
 template <int DT, int G>
-static int launch_fwd(const FwdArgs& a, bool wave_mode, hipStream_t st) {
+static int launch_fwd(const FwdArgs& a, int mode, hipStream_t st) {
   constexpr int S = DLRM_WAVE / G;
   const int64_t bags = (int64_t)a.K * a.B;
-  if (wave_mode) {
+  const bool wave_mode = mode == 2;
+  if (mode == 0) {
+    const unsigned grid = div_up(bags, 4 * S * kShortBags);
+    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags>), dim3(grid), dim3(256), 0, st, a);
+  } else if (wave_mode) {
     // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
     hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
@@ -157,7 +222,7 @@ static int launch_fwd(const FwdArgs& a, bool wave_mode, hipStream_t st) {
 }
 
 template <int DT>
-static int dispatch_g(const FwdArgs& a, int G, bool wave_mode, hipStream_t st) {
+static int dispatch_g(const FwdArgs& a, int G, int wave_mode, hipStream_t st) {
   switch (G) {
     case 1: return launch_fwd<DT, 1>(a, wave_mode, st);
     case 2: return launch_fwd<DT, 2>(a, wave_mode, st);
@@ -198,7 +263,8 @@ extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int6
   const int S = DLRM_WAVE / G;
   // a wavefront per bag pays off once a bag keeps all S lane groups busy for a few rounds
   const double mean_len = (double)s->nnz_total / ((double)s->K * s->B);
-  const bool wave_mode = S > 1 ? mean_len >= 2.0 * S : mean_len >= 1e30;
+  // mode 0: several bags per lane group (mean bag <= 2), 1: a lane group per bag, 2: a wavefront per bag
+  const int wave_mode = mean_len <= 2.0 ? 0 : (S > 1 && mean_len >= 2.0 * S) ? 2 : 1;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   switch (s->table_dtype) {
     case DLRM_F32: return dispatch_g<DLRM_F32>(a, G, wave_mode, hs);
