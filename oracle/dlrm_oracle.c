@@ -14,6 +14,8 @@
  *   - backward of the two, by the chain rule (the paper prints no backward)
  *   - sparse SGD              W <- W - lr * dW on touched rows (Sec. 5.1: SGD,
  *                             no regularisation)
+ *   - weighted pooling        Eq. (2) in full, s = sum_p a_p W[idx_p], and its backward
+ *                             g_r = sum_{p: idx_p = r} a_p dS[bag(p)]
  *   - sparse Adagrad          the other optimizer Sec. 5.1 names, element-wise:
  *                             h <- h + dW^2, W <- W - lr * dW / (sqrt(h) + eps)
  *                             on touched rows
@@ -24,7 +26,9 @@
  * (the printed CSR example, one-hot == row gather, dense A^T W by a library
  * matmul, tril(T T^T), closed forms for F = 2, finite differences, count x g,
  * numpy.unique, exhaustive fp16 widening / RNE narrowing against numpy; Adagrad:
- * closed forms, the coalescing of duplicates, torch.optim.Adagrad on the CPU).
+ * closed forms, the coalescing of duplicates, torch.optim.Adagrad on the CPU;
+ * weighted pooling: the dense weighted matrix A through a library matmul, unit
+ * weights == the unweighted functions, a repeated index adds its weights).
  *
  * Optional OpenMP `parallel for` over the outermost independent loop is the only
  * concession to speed; oracle_set_threads(1) gives the single-thread run.
@@ -445,6 +449,103 @@ int oracle_emb_bag_bwd_adagrad(int32_t K, int32_t B, int32_t d, int32_t dtype, v
           state[k][r * d + c] = (float)h;
           double w = widen(tables[k], dtype, r * d + c);
           narrow_store(tables[k], dtype, r * d + c, w - lr * g / (sqrt(h) + eps));
+        }
+      }
+      if (bad) status = ORC_ERR_INDEX;
+    }
+  }
+  free(sorted_pos);
+  free(sorted_bag);
+  free(uniq);
+  free(seg);
+  free(nu);
+  return status;
+}
+
+/* ---------------- weighted pooling: Eq. (2) with its weights a ---------------- */
+
+/* S[b,k,:] = sum over the bag's positions p of weights[tbl_off[k] + p] * W_k[idx_p,:]
+ * (weights: fp32, parallel to indices).  Everything else as oracle_emb_bag_fwd. */
+int oracle_emb_bag_fwd_weighted(int32_t K, int32_t B, int32_t d, int32_t dtype, const void* const* tables,
+                                const int64_t* rows, const int64_t* indices, const int64_t* offsets,
+                                const int64_t* tbl_off, const float* weights, double* out,
+                                int64_t stride_b, int64_t stride_k) {
+  if (!tables || !rows || !offsets || !tbl_off || !weights || !out || K <= 0 || B <= 0 || d <= 0)
+    return ORC_ERR_ARG;
+  int status = ORC_OK;
+#ifdef _OPENMP
+#pragma omp parallel for collapse(2) schedule(static) num_threads(ORC_NT)
+#endif
+  for (int32_t k = 0; k < K; ++k) {
+    for (int32_t b = 0; b < B; ++b) {
+      const int64_t* off = offsets + (int64_t)k * (B + 1);
+      const int64_t* idx = indices + tbl_off[k];
+      const float* a = weights + tbl_off[k];
+      double* o = out + (int64_t)b * stride_b + (int64_t)k * stride_k;
+      for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+      for (int64_t p = off[b]; p < off[b + 1]; ++p) {
+        int64_t r = idx[p];
+        if (r < 0 || r >= rows[k]) {
+          status = ORC_ERR_INDEX;
+          continue;
+        }
+        for (int32_t c = 0; c < d; ++c) o[c] += (double)a[p] * widen(tables[k], dtype, r * d + c);
+      }
+    }
+  }
+  return status;
+}
+
+/* Backward of the weighted lookup with the row update: for every distinct row r of table k
+ *   g = sum over the positions p that look r up of weights[tbl_off[k] + p] * dS[bag(p), k, :]
+ * then, optimizer 0: W <- W - lr*g;  optimizer 1 (state != NULL): h <- h + g*g,
+ * W <- W - lr*g / (sqrt(h) + eps).  The weights themselves receive no gradient here. */
+int oracle_emb_bag_bwd_weighted(int32_t K, int32_t B, int32_t d, int32_t dtype, void* const* tables,
+                                float* const* state, const int64_t* rows, const int64_t* indices,
+                                const int64_t* offsets, const int64_t* tbl_off, const float* weights,
+                                const float* dS, int64_t stride_b, int64_t stride_k, double lr,
+                                double eps, int32_t optimizer) {
+  if (!tables || !rows || !offsets || !tbl_off || !weights || !dS || K <= 0 || B <= 0 || d <= 0 ||
+      (optimizer != 0 && optimizer != 1) || (optimizer == 1 && !state))
+    return ORC_ERR_ARG;
+  int64_t nnz_total = tbl_off[K];
+  size_t n = (size_t)(nnz_total > 0 ? nnz_total : 1);
+  int64_t* sorted_pos = (int64_t*)malloc(sizeof(int64_t) * n);
+  int32_t* sorted_bag = (int32_t*)malloc(sizeof(int32_t) * n);
+  int64_t* uniq = (int64_t*)malloc(sizeof(int64_t) * n);
+  int64_t* seg = (int64_t*)malloc(sizeof(int64_t) * n);
+  int64_t* nu = (int64_t*)malloc(sizeof(int64_t) * (size_t)K);
+  int status = ORC_ERR_MEM;
+  if (sorted_pos && sorted_bag && uniq && seg && nu)
+    status = oracle_group_rows(K, B, indices, offsets, tbl_off, sorted_pos, sorted_bag, uniq, seg, nu);
+  if (status == ORC_OK) {
+    for (int32_t k = 0; k < K; ++k) {
+      int64_t base = tbl_off[k], nnz = tbl_off[k + 1] - tbl_off[k];
+      int64_t U = nu[k];
+      int bad = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 64) num_threads(ORC_NT)
+#endif
+      for (int64_t u = 0; u < U; ++u) {
+        int64_t r = uniq[base + u];
+        if (r < 0 || r >= rows[k]) {
+          bad = 1;
+          continue;
+        }
+        int64_t t0 = seg[base + u], t1 = (u + 1 < U) ? seg[base + u + 1] : nnz;
+        for (int32_t c = 0; c < d; ++c) {
+          double g = 0.0;
+          for (int64_t t = t0; t < t1; ++t)
+            g += (double)weights[base + sorted_pos[base + t]] *
+                 (double)dS[(int64_t)sorted_bag[base + t] * stride_b + (int64_t)k * stride_k + c];
+          double w = widen(tables[k], dtype, r * d + c);
+          if (optimizer == 1) {
+            double h = (double)state[k][r * d + c] + g * g;
+            state[k][r * d + c] = (float)h;
+            narrow_store(tables[k], dtype, r * d + c, w - lr * g / (sqrt(h) + eps));
+          } else {
+            narrow_store(tables[k], dtype, r * d + c, w - lr * g);
+          }
         }
       }
       if (bad) status = ORC_ERR_INDEX;

@@ -241,3 +241,49 @@ def emb_bag_bwd_adagrad(tables: Sequence[np.ndarray], state: Sequence[np.ndarray
         C.c_double(float(eps)))
     if st != 0:
         raise ValueError("oracle_emb_bag_bwd_adagrad status %d" % st)
+
+
+def emb_bag_fwd_weighted(tables: Sequence[np.ndarray], dtype: int, indices, offsets, tbl_off,
+                         weights: np.ndarray) -> np.ndarray:
+    """Eq. (2) with its weights: float64 [B,K,d]; weights float32 parallel to indices."""
+    indices, offsets, tbl_off = _i64(indices), _i64(offsets), _i64(tbl_off)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    assert weights.shape == indices.shape
+    K, B1 = offsets.shape
+    B = B1 - 1
+    d = tables[0].shape[1]
+    rows = _i64([t.shape[0] for t in tables])
+    ptrs, keep = _table_ptrs(tables, dtype)
+    out = np.empty((B, K, d), dtype=np.float64)
+    st = lib().oracle_emb_bag_fwd_weighted(C.c_int32(K), C.c_int32(B), C.c_int32(d), C.c_int32(dtype), ptrs,
+                                           _p(rows), _p(indices), _p(offsets), _p(tbl_off), _p(weights),
+                                           _p(out), C.c_int64(K * d), C.c_int64(d))
+    if st != 0:
+        raise ValueError("oracle_emb_bag_fwd_weighted status %d" % st)
+    return out
+
+
+def emb_bag_bwd_weighted(tables: Sequence[np.ndarray], dtype: int, indices, offsets, tbl_off, weights,
+                         dS: np.ndarray, lr: float, state: Optional[Sequence[np.ndarray]] = None,
+                         eps: float = 0.0):
+    """Backward of the weighted lookup, tables (and Adagrad state, if given) updated in place."""
+    indices, offsets, tbl_off = _i64(indices), _i64(offsets), _i64(tbl_off)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    dS = np.ascontiguousarray(dS, dtype=np.float32)
+    K, B1 = offsets.shape
+    B = B1 - 1
+    d = tables[0].shape[1]
+    assert dS.shape == (B, K, d) and weights.shape == indices.shape
+    rows = _i64([t.shape[0] for t in tables])
+    ptrs, keep = _table_ptrs(tables, dtype)
+    sptrs = None
+    if state is not None:
+        for t, h in zip(tables, state):
+            assert h.dtype == np.float32 and h.shape == t.shape and h.flags["C_CONTIGUOUS"]
+        sptrs = (C.c_void_p * K)(*[h.ctypes.data for h in state])
+    st = lib().oracle_emb_bag_bwd_weighted(
+        C.c_int32(K), C.c_int32(B), C.c_int32(d), C.c_int32(dtype), ptrs, sptrs, _p(rows), _p(indices),
+        _p(offsets), _p(tbl_off), _p(weights), _p(dS), C.c_int64(K * d), C.c_int64(d), C.c_double(float(lr)),
+        C.c_double(float(eps)), C.c_int32(0 if state is None else 1))
+    if st != 0:
+        raise ValueError("oracle_emb_bag_bwd_weighted status %d" % st)

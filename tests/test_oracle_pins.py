@@ -508,3 +508,58 @@ def test_adagrad_fp16_tables_round_once_and_keep_untouched_rows():
     assert np.array_equal(W[0][1].view(np.uint16), want1.view(np.uint16))
     assert np.array_equal(W[0][[0, 2, 3]].view(np.uint16), W16[[0, 2, 3]].view(np.uint16))
     assert np.all(h[0][[0, 2, 3]] == 5.0)
+
+
+# ------------------------------------------------------------------ weighted pooling, Eq. (2) in full
+def test_weighted_pooling_is_the_dense_weighted_matrix_product():
+    w = gen.custom_workload("wp", K=3, B=20, d=6, rows=15, bag=("uniform", 0, 6))
+    b = gen.make_batch(w)
+    rng = np.random.default_rng(5)
+    tables = _rand_tables(rng, b.rows, w.d)
+    a = rng.uniform(-2, 2, size=b.indices.shape).astype(np.float32)
+    S = oracle.emb_bag_fwd_weighted(tables, gen.F32, b.indices, b.offsets, b.tbl_off, a)
+    dS = rng.standard_normal((w.B, w.K, w.d)).astype(np.float32)
+    upd = [t.copy() for t in tables]
+    oracle.emb_bag_bwd_weighted(upd, gen.F32, b.indices, b.offsets, b.tbl_off, a, dS, 1.0)
+    for k in range(w.K):
+        # A[i, b] = sum of the weights with which bag b looks row i up (Eq. (2): S = A^T W)
+        A = np.zeros((int(b.rows[k]), w.B))
+        off = b.offsets[k]
+        bag_of = np.repeat(np.arange(w.B), np.diff(off))
+        np.add.at(A, (b.indices_of(k), bag_of), a[b.tbl_off[k]:b.tbl_off[k + 1]].astype(np.float64))
+        assert np.allclose(S[:, k, :], A.T @ tables[k].astype(np.float64), rtol=1e-12, atol=1e-12)
+        want = tables[k].astype(np.float64) - A @ dS[:, k, :].astype(np.float64)
+        assert np.allclose(upd[k], want.astype(np.float32), rtol=0, atol=1e-6)
+
+
+def test_unit_weights_are_the_unweighted_functions_and_repeats_add_their_weights():
+    w = gen.custom_workload("wu", K=2, B=16, d=4, rows=9, bag=("uniform", 0, 5))
+    b = gen.make_batch(w)
+    rng = np.random.default_rng(6)
+    tables = _rand_tables(rng, b.rows, w.d)
+    ones = np.ones(b.indices.shape, dtype=np.float32)
+    assert np.array_equal(oracle.emb_bag_fwd_weighted(tables, gen.F32, b.indices, b.offsets, b.tbl_off, ones),
+                          oracle.emb_bag_fwd(tables, gen.F32, b.indices, b.offsets, b.tbl_off))
+    dS = b.dS()
+    t1 = [t.copy() for t in tables]
+    t2 = [t.copy() for t in tables]
+    oracle.emb_bag_bwd_sgd(t1, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 0.1)
+    oracle.emb_bag_bwd_weighted(t2, gen.F32, b.indices, b.offsets, b.tbl_off, ones, dS, 0.1)
+    for x, y in zip(t1, t2):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    h1 = [np.zeros_like(t) for t in tables]
+    h2 = [np.zeros_like(t) for t in tables]
+    oracle.emb_bag_bwd_adagrad(t1, h1, gen.F32, b.indices, b.offsets, b.tbl_off, dS, 0.1, 1e-8)
+    oracle.emb_bag_bwd_weighted(t2, gen.F32, b.indices, b.offsets, b.tbl_off, ones, dS, 0.1, state=h2, eps=1e-8)
+    for x, y in zip(t1 + h1, t2 + h2):
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    # one bag looks row 3 up twice, with weights 0.25 and -2: the row counts (0.25 - 2) times
+    bb = gen.batch_from_lists([5], [[[3, 1, 3]]], d=2)
+    W = [np.arange(10, dtype=np.float32).reshape(5, 2)]
+    a = np.array([0.25, 1.0, -2.0], dtype=np.float32)
+    S = oracle.emb_bag_fwd_weighted(W, gen.F32, bb.indices, bb.offsets, bb.tbl_off, a)
+    assert np.array_equal(S[0, 0], -1.75 * W[0][3].astype(np.float64) + W[0][1])
+    dS1 = np.array([[[1.0, 2.0]]], dtype=np.float32)
+    oracle.emb_bag_bwd_weighted(W, gen.F32, bb.indices, bb.offsets, bb.tbl_off, a, dS1, 1.0)
+    assert np.array_equal(W[0][3], np.array([6.0 + 1.75, 7.0 + 3.5], dtype=np.float32))
+    assert np.array_equal(W[0][1], np.array([2.0 - 1.0, 3.0 - 2.0], dtype=np.float32))

@@ -302,3 +302,9 @@ def batch_from_lists(rows: List[int], bags: List[List[List[int]]], d: int, dtype
     dR = rng.standard_normal((B, d + w.P), dtype=np.float32)
     return Batch(w, np.asarray(rows, dtype=np.int64), lengths, offsets, tbl_off, indices, x, dR,
                  seed=seed)
+
+
+def make_weights(batch: "Batch", seed: int = 0) -> np.ndarray:
+    """Per-lookup weights for Eq. (2), parallel to ``batch.indices``: float32 uniform in [0.5, 1.5)."""
+    rng = np.random.default_rng([seed, 77, batch.nnz])
+    return rng.uniform(0.5, 1.5, size=batch.indices.shape).astype(np.float32)
