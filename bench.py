@@ -36,6 +36,8 @@ def parse_args():
     ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adagrad"],
                     help="row update of the fused backward (the metric is quoted on sgd)")
+    ap.add_argument("--weighted", action="store_true",
+                    help="per-lookup weights (Eq. (2) in full) instead of sum pooling; the metric is quoted without")
     ap.add_argument("--no-overlap", action="store_true",
                     help="group the (row, bag) pairs inside the backward call instead of on a second "
                          "stream beside the forward pass")
@@ -103,9 +105,10 @@ def main():
         tables.append(t)
     dev_batches = []
     for b in batches:
+        wts = torch.from_numpy(gen.make_weights(b)).to(dev) if args.weighted else None
         sb = hot.SparseBatch(tables, w.dtype, torch.from_numpy(b.indices).to(dev),
                              torch.from_numpy(np.ascontiguousarray(b.offsets)).to(dev),
-                             torch.from_numpy(b.tbl_off).to(dev), b.nnz, max_rows=int(rows.max()))
+                             torch.from_numpy(b.tbl_off).to(dev), b.nnz, max_rows=int(rows.max()), weights=wts)
         dev_batches.append((sb, torch.from_numpy(b.x).to(dev), torch.from_numpy(b.dR).to(dev)))
     max_nnz = max(b.nnz for b in batches)
     ws_bytes = hot.dlrm_emb_bag_bwd_workspace_bytes(K, B, d, max_nnz, int(rows.max()), w.dtype)
@@ -266,7 +269,8 @@ def main():
         "config": {"workload": "%d:%s" % (args.config, w.name), "tables": K, "batch": B, "dim": d,
                    "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
                    "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
-                   "bwd_algo": args.algo, "optimizer": args.optimizer, "lr": w.lr,
+                   "bwd_algo": args.algo, "optimizer": args.optimizer, "pooling": "weighted" if args.weighted else "sum",
+                   "lr": w.lr,
                    "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
         "emb_fwd_bwd": {"ms": round(emb_ms, 5), "lookups_per_s": round(nnz_mean / (emb_ms * 1e-3), 1),
@@ -283,7 +287,7 @@ def main():
     }
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores, same workload
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.weighted:
         from oracle import oracle
         b = batches[0]
         host_tables = []

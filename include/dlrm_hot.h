@@ -76,6 +76,10 @@ typedef struct dlrm_sparse_batch {
   const int64_t* offsets;  /* [K*(B+1)] per-table local offsets; bag b of table k = positions
                               [offsets[k*(B+1)+b], offsets[k*(B+1)+b+1]); offsets[k*(B+1)+B] = nnz_k */
   const int64_t* tbl_off;  /* [K+1] start of table k's slice in `indices` */
+  const float* weights;    /* NULL, or [nnz_total] fp32 parallel to `indices`: the weight a of every
+                              lookup in Eq. (2).  NULL = all ones (sum pooling, what the five workloads
+                              use).  With weights, bag b of table k pools sum_p weights[p] * W_k[indices[p],:]
+                              and the backward sums weights[p] * dS[bag(p)]; the weights get no gradient. */
 } dlrm_sparse_batch;
 
 /* Library version (major*10000 + minor*100 + patch). */

@@ -29,7 +29,7 @@ class _SparseBatchC(C.Structure):
         ("K", C.c_int32), ("B", C.c_int32), ("d", C.c_int32), ("table_dtype", C.c_int32),
         ("nnz_total", C.c_int64), ("max_rows", C.c_int64),
         ("tables", C.c_void_p), ("rows", C.c_void_p), ("indices", C.c_void_p),
-        ("offsets", C.c_void_p), ("tbl_off", C.c_void_p),
+        ("offsets", C.c_void_p), ("tbl_off", C.c_void_p), ("weights", C.c_void_p),
     ]
 
 
@@ -106,7 +106,7 @@ class SparseBatch:
 
     def __init__(self, tables: Sequence[torch.Tensor], table_dtype: int, indices: torch.Tensor,
                  offsets: torch.Tensor, tbl_off: torch.Tensor, nnz_total: int,
-                 max_rows: Optional[int] = None):
+                 max_rows: Optional[int] = None, weights: Optional[torch.Tensor] = None):
         self.tables = list(tables)
         K = len(self.tables)
         d = int(self.tables[0].shape[1])
@@ -118,6 +118,9 @@ class SparseBatch:
         self.K, self.B, self.d = K, int(offsets.shape[1]) - 1, d
         self.table_dtype = table_dtype
         self.indices, self.offsets, self.tbl_off = indices, offsets, tbl_off
+        if weights is not None:
+            assert weights.dtype == torch.float32 and weights.is_contiguous() and weights.shape == indices.shape
+        self.weights = weights
         rows_host = [int(t.shape[0]) for t in self.tables]
         self.rows = torch.tensor(rows_host, dtype=torch.int64, device=dev)
         self.table_ptrs = torch.tensor([t.data_ptr() for t in self.tables], dtype=torch.int64,
@@ -127,7 +130,8 @@ class SparseBatch:
         self.c = _SparseBatchC(K, self.B, d, table_dtype, self.nnz_total, self.max_rows,
                                _ptr(self.table_ptrs), _ptr(self.rows),
                                _ptr(indices) if indices.numel() else None,
-                               _ptr(offsets), _ptr(tbl_off))
+                               _ptr(offsets), _ptr(tbl_off),
+                               _ptr(weights) if weights is not None and weights.numel() else None)
 
     def ref(self):
         return C.byref(self.c)

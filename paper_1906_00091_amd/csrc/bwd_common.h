@@ -9,7 +9,11 @@
 //   2. scan           : (digit, tile) counts -> destination offsets inside the table's slice
 //                       (folded into step 3 when the batch has few tiles)
 //   3. bucket_scatter : derives the bag of every position from the offsets, then moves the
-//                       (row, bag) pairs to their bucket, stably, staged through LDS
+//                       (row, bag) pairs to their bucket, stably, staged through LDS.
+//                       Weighted batches (Eq. (2) with its weights) move (row, position) pairs
+//                       instead and keep the bags in a side array in the original order: nothing
+//                       downstream looks inside the second member until a gradient row is
+//                       fetched, where bag and weight are looked up by position.
 //   4. bucket_reduce  : one workgroup per (table, top digit): stable LSD radix sort of the
 //                       bucket on the remaining low bits (in LDS when it fits), run heads,
 //                       then a lane group per run sums its dS rows in ascending position
@@ -140,6 +144,8 @@ struct GroupArgs {            // everything the grouping kernels need
   const int64_t* offsets;
   const int64_t* tbl_off;
   const int64_t* rows;
+  const float* weights;       // NULL, or the weight of every lookup (parallel to indices)
+  uint32_t* pos_bag;          // weighted batches: bag of every position, in the original order
   int32_t K, B;
   int32_t nt_max;
   int32_t top_bits;           // bits of the partition digit (0..kMaxTopBits)
@@ -459,6 +465,7 @@ inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.offsets = s->offsets;
   g.tbl_off = s->tbl_off;
   g.rows = s->rows;
+  g.weights = s->weights;
   g.K = s->K;
   g.B = s->B;
   g.nt_max = (int32_t)L.nt_max;
@@ -484,6 +491,7 @@ inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.bucket_start = reinterpret_cast<uint32_t*>(base + L.bucket_start);
   g.tile_heads = reinterpret_cast<uint32_t*>(base + L.tile_heads);
   g.seg_start = reinterpret_cast<uint32_t*>(base + L.seg_start);
+  g.pos_bag = g.seg_start;  // the export arrays are idle during an update
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
   g.hot_cnt = reinterpret_cast<uint32_t*>(base + L.hot_cnt);
@@ -513,8 +521,11 @@ inline int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout
 // and bucket_start the bucket boundaries
 int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_t st);
 // step 4 onwards with the SGD / Adagrad row update (bwd_reduce_sgd.hip, bwd_reduce_adagrad.hip)
+// (one translation unit per optimizer and per weighted / unweighted pooling)
 int run_reduce_sgd(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
 int run_reduce_adagrad(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
+int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
+int run_reduce_adagrad_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
 // bwd_tail.hip
 int launch_segment_sort(const GroupArgs& g, hipStream_t st);
 int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, hipStream_t st);

@@ -151,6 +151,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_export_groups(const dlrm_sparse_batch* s, vo
   if (s->nnz_total == 0) return DLRM_OK;
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
+  g.weights = nullptr;  // the export is about rows and bags; (row, bag) pairs whatever the batch carries
   st = enqueue_partition(s, g, hs);
   if (st != DLRM_OK) return st;
   hipLaunchKernelGGL(bucket_sort_only_kernel, dim3((unsigned)s->K << g.top_bits), dim3(kThreads), 0, hs, g);

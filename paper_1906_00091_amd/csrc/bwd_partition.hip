@@ -186,6 +186,10 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
   for (int j = 0; j < kItems; ++j) {
     const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
     val[j] = ok[j] ? sval[li] : 0u;
+    if (a.weights != nullptr && ok[j]) {  // uniform branch: weighted batch
+      a.pos_bag[ti.start + li] = val[j];
+      val[j] = (uint32_t)(P0 + li);       // position inside the table
+    }
   }
   rank_items<kItems, kMaxBuckets>(dg, ok, a.top_bits, wcnt, rnk);
   __syncthreads();

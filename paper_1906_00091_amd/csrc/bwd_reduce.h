@@ -1,33 +1,65 @@
 // Backward steps 4 / 4a and the row updates: sorted runs -> one read-modify-write per row.
-// Template code; bwd_reduce_sgd.hip and bwd_reduce_adagrad.hip instantiate it per optimizer.
+// Template code; bwd_reduce_{sgd,adagrad}[_weighted].hip instantiate it per optimizer and per
+// unweighted / weighted pooling.
 #pragma once
 #include "bwd_sort.h"
 
 namespace dlrm {
 
-// Sum dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from i0 + first;
-// U loads in flight, ascending order.  bags: LDS or global.
-template <int U>
-__device__ inline f32x4 sum_entries(const float* g, int64_t stride_b, const uint32_t* bags, uint32_t i0,
-                                    uint32_t i1, uint32_t first, uint32_t stride) {
+// The second member of a sorted pair is the bag itself (sum pooling) or, for a weighted batch,
+// the position inside the table, by which the bag and the weight a of Eq. (2) are looked up.
+struct Entry {
+  uint32_t bag;
+  float w;
+};
+template <bool WT>
+__device__ inline Entry entry_of(const GroupArgs& a, int64_t tbl, uint32_t val) {
+  Entry e;
+  if constexpr (WT) {
+    e.bag = a.pos_bag[tbl + val];
+    e.w = a.weights[tbl + val];
+  } else {
+    e.bag = val;
+    e.w = 1.0f;
+  }
+  return e;
+}
+
+// Sum (weight times) dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from
+// i0 + first; U loads in flight, ascending order.  vals: LDS or global.  tbl: start of the table
+// in the batch's index array.
+template <int U, bool WT>
+__device__ inline f32x4 sum_entries(const GroupArgs& a, int64_t tbl, const float* g, int64_t stride_b,
+                                    const uint32_t* vals, uint32_t i0, uint32_t i1, uint32_t first,
+                                    uint32_t stride) {
   f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
   for (uint32_t i = i0 + first; i < i1; i += U * stride) {
-    uint32_t bg[U];
+    Entry e[U];
     f32x4 v[U];
 #pragma unroll
-    for (int t = 0; t < U; ++t) bg[t] = bags[i + t * stride < i1 ? i + t * stride : i];
+    for (int t = 0; t < U; ++t) e[t] = entry_of<WT>(a, tbl, vals[i + t * stride < i1 ? i + t * stride : i]);
 #pragma unroll
-    for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)bg[t] * stride_b);
+    for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)e[t].bag * stride_b);
 #pragma unroll
-    for (int t = 0; t < U; ++t)
-      if (i + t * stride < i1) acc += v[t];
+    for (int t = 0; t < U; ++t) {
+      if (i + t * stride < i1) {
+        if constexpr (WT) {
+          acc.x = fmaf(e[t].w, v[t].x, acc.x);
+          acc.y = fmaf(e[t].w, v[t].y, acc.y);
+          acc.z = fmaf(e[t].w, v[t].z, acc.z);
+          acc.w = fmaf(e[t].w, v[t].w, acc.w);
+        } else {
+          acc += v[t];
+        }
+      }
+    }
   }
   return acc;
 }
 
 // keys/bags: the bucket's sorted pairs (n of them; LDS or global), heads: LDS list of run starts
 // with heads[nruns] = n.  gpos0: global position of the bucket's first pair.
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                    const uint32_t* keys, const uint32_t* bags, const uint32_t* heads,
                                    uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
@@ -42,6 +74,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
   constexpr int RU = OPT == kAdagrad ? 2 : 4;  // Adagrad also holds the state rows
   const int cchunk = col_ok ? chunk : 0;
   float* H = state_base<OPT>(u, b.k);
+  const int64_t tbl = WT ? a.tbl_off[b.k] : 0;
   for (uint32_t r0 = (uint32_t)grp * RU; r0 < nruns; r0 += NG * RU) {
     uint32_t i0[RU], i1[RU];
     RowRef wp[RU];
@@ -54,15 +87,22 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
       i1[t] = heads[rr + 1] - h0;
       wp[t] = row_ref<DT, OPT>(W, H, u.d, keys[i0[t]], cchunk);
     }
+    Entry e0[RU];
 #pragma unroll
-    for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)bags[i0[t]] * u.stride_b);
+    for (int t = 0; t < RU; ++t) e0[t] = entry_of<WT>(a, tbl, bags[i0[t]]);
+#pragma unroll
+    for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)e0[t].bag * u.stride_b);
 #pragma unroll
     for (int t = 0; t < RU; ++t) wv[t] = row_load<DT, OPT>(wp[t]);
+    if constexpr (WT) {
+#pragma unroll
+      for (int t = 0; t < RU; ++t) acc[t] *= e0[t].w;
+    }
 #pragma unroll
     for (int t = 0; t < RU; ++t) {
       const uint32_t len = i1[t] - i0[t];
       if (r0 + t >= nruns || len > (uint32_t)kLongRun) continue;
-      if (len > 1) acc[t] += sum_entries<4>(g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
+      if (len > 1) acc[t] += sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
       if (col_ok) row_update_store<DT, OPT>(wp[t], wv[t], acc[t], u);
     }
   }
@@ -85,7 +125,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
       }
       continue;
     }
-    const f32x4 acc = sum_entries<4>(g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
+    const f32x4 acc = sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
     __syncthreads();
     if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
     __syncthreads();
@@ -153,7 +193,7 @@ __device__ inline uint32_t run_end_search(const uint32_t* keys, uint32_t lo, uin
 
 // One window of kBktCap positions of a sorted pair list (global memory): the runs whose head
 // lies in the window are reduced and applied; a run may extend past the window.
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                      const uint32_t* keys, const uint32_t* bags, uint32_t w0, int src,
                                      SortLds& s, float* part) {
@@ -180,7 +220,7 @@ __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const
     if (tid == 0) s.heads[total] = e;
     __syncthreads();
     const uint32_t nlong = collect_long_runs(s, total);
-    reduce_runs<DT, G, OPT>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
+    reduce_runs<DT, G, OPT, WT>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
   }
   __syncthreads();
 }
@@ -210,7 +250,7 @@ __device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd) {
 
 // Pairs [bk.start, bk.start + bk.n) of pair buffer src, more than kBktCap of them, that no
 // shortcut applies to: queued as a segment when per-row counters fit LDS, else sorted here.
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, const Bucket& bk, char* W,
                                          int src, SortLds& s, float* part) {
   if (bk.low_bits <= kSegMaxBits && !a.no_tail) {
@@ -236,10 +276,10 @@ __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, c
   __syncthreads();
   const uint32_t* keys = a.keys[res] + bk.start;
   const uint32_t* bags = a.vals[res] + bk.start;
-  for (uint32_t w0 = 0; w0 < bk.n; w0 += kBktCap) reduce_window<DT, G, OPT>(a, u, bk, W, keys, bags, w0, res, s, part);
+  for (uint32_t w0 = 0; w0 < bk.n; w0 += kBktCap) reduce_window<DT, G, OPT, WT>(a, u, bk, W, keys, bags, w0, res, s, part);
 }
 
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                         SortLds& s, SplitLds& sp, float* part) {
   const int tid = threadIdx.x, lane = lane_id(), w = wave_id();
@@ -270,7 +310,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   __syncthreads();
   const uint32_t nc = sp.nc;
   if (nc == 0) {  // uniform
-    sort_reduce_large<DT, G, OPT>(a, u, b, W, 1, s, part);
+    sort_reduce_large<DT, G, OPT, WT>(a, u, b, W, 1, s, part);
     return;
   }
   uint32_t cd[kCand];
@@ -402,7 +442,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   // ---- candidate lists are runs: short ones summed here, those above kHugeRun queued as hot rows
   {
     const uint32_t nlong = collect_long_runs(s, nc);
-    reduce_runs<DT, G, OPT>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
+    reduce_runs<DT, G, OPT, WT>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
   }
   // ---- the rest
   Bucket rest = b;
@@ -411,16 +451,16 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   __syncthreads();
   if (rest.n == 0) return;  // uniform
   if (rest.n > (uint32_t)kBktCap) {
-    sort_reduce_large<DT, G, OPT>(a, u, rest, W, 0, s, part);
+    sort_reduce_large<DT, G, OPT, WT>(a, u, rest, W, 0, s, part);
     return;
   }
   sort_bucket_lds(a, rest, s, 0);
   const uint32_t nruns = compact_heads_lds(s, (int)rest.n);
   const uint32_t nlong = collect_long_runs(s, nruns);
-  reduce_runs<DT, G, OPT>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
+  reduce_runs<DT, G, OPT, WT>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
 }
 
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ SplitLds sp;
@@ -435,7 +475,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
     sort_bucket_lds(a, b, s);
     const uint32_t nruns = compact_heads_lds(s, (int)b.n);
     const uint32_t nlong = collect_long_runs(s, nruns);
-    reduce_runs<DT, G, OPT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
+    reduce_runs<DT, G, OPT, WT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
     return;
   }
   if (b.low_bits == 0) {  // the bucket holds one row: a single run, already in position order
@@ -445,15 +485,15 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
     }
     __syncthreads();
     const uint32_t nlong = collect_long_runs(s, 1);
-    reduce_runs<DT, G, OPT>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
+    reduce_runs<DT, G, OPT, WT>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
                        part);
     return;
   }
-  reduce_oversized<DT, G, OPT>(a, u, b, W, s, sp, part);
+  reduce_oversized<DT, G, OPT, WT>(a, u, b, W, s, sp, part);
 }
 
 
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ float part[kThreads * 4];
@@ -467,13 +507,13 @@ __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, U
   b.low_bits = 0;
   char* W = static_cast<char*>(u.tables[b.k]);
   const int dst = (int)(sg.src ^ 1u);
-  reduce_window<DT, G, OPT>(a, u, b, W, a.keys[dst] + sg.start, a.vals[dst] + sg.start, t * kBktCap, dst, s, part);
+  reduce_window<DT, G, OPT, WT>(a, u, b, W, a.keys[dst] + sg.start, a.vals[dst] + sg.start, t * kBktCap, dst, s, part);
 }
 
 
 // A lane group per hot run adds the run's partial sums in bag-group order and updates the row.
 // A launch of its own: the kernel boundary orders it after every partial, at no fence.
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdArgs u, int ngroups) {
   constexpr int S = DLRM_WAVE / G;
   const int k = blockIdx.y;
@@ -501,48 +541,48 @@ __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdAr
 }
 
 
-template <int DT, int G, int OPT>
+template <int DT, int G, int OPT, bool WT>
 static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
   const unsigned blocks = ((unsigned)K << g.top_bits) + (unsigned)g.max_over;
   if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return DLRM_ERR_HIP;
-  hipLaunchKernelGGL((bucket_reduce_kernel<DT, G, OPT>), dim3(blocks), dim3(kThreads), 0, st, g, u);
+  hipLaunchKernelGGL((bucket_reduce_kernel<DT, G, OPT, WT>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
   if (g.no_tail) return DLRM_OK;
   const unsigned seg_tiles = (unsigned)(g.seg_tiles_max);
   int rc = launch_segment_sort(g, st);
   if (rc != DLRM_OK) return rc;
-  hipLaunchKernelGGL((segment_reduce_kernel<DT, G, OPT>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
+  hipLaunchKernelGGL((segment_reduce_kernel<DT, G, OPT, WT>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   const int ng = hot_groups(g.B, u.d);
   rc = launch_hot_rows(g, u, G, K, ng, st);
   if (rc != DLRM_OK) return rc;
-  hipLaunchKernelGGL((hot_finish_kernel<DT, G, OPT>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
+  hipLaunchKernelGGL((hot_finish_kernel<DT, G, OPT, WT>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
 
-template <int DT, int OPT>
+template <int DT, int OPT, bool WT>
 static int dispatch_reduce(const GroupArgs& g, const UpdArgs& u, int G, int K, hipStream_t st) {
   switch (G) {
-    case 1: return launch_reduce<DT, 1, OPT>(g, u, K, st);
-    case 2: return launch_reduce<DT, 2, OPT>(g, u, K, st);
-    case 4: return launch_reduce<DT, 4, OPT>(g, u, K, st);
-    case 8: return launch_reduce<DT, 8, OPT>(g, u, K, st);
-    case 16: return launch_reduce<DT, 16, OPT>(g, u, K, st);
-    case 32: return launch_reduce<DT, 32, OPT>(g, u, K, st);
-    case 64: return launch_reduce<DT, 64, OPT>(g, u, K, st);
+    case 1: return launch_reduce<DT, 1, OPT, WT>(g, u, K, st);
+    case 2: return launch_reduce<DT, 2, OPT, WT>(g, u, K, st);
+    case 4: return launch_reduce<DT, 4, OPT, WT>(g, u, K, st);
+    case 8: return launch_reduce<DT, 8, OPT, WT>(g, u, K, st);
+    case 16: return launch_reduce<DT, 16, OPT, WT>(g, u, K, st);
+    case 32: return launch_reduce<DT, 32, OPT, WT>(g, u, K, st);
+    case 64: return launch_reduce<DT, 64, OPT, WT>(g, u, K, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
 
 
-template <int OPT>
+template <int OPT, bool WT>
 inline int run_reduce(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st) {
   switch (dtype) {
-    case DLRM_F32: return dispatch_reduce<DLRM_F32, OPT>(g, u, G, K, st);
-    case DLRM_F16: return dispatch_reduce<DLRM_F16, OPT>(g, u, G, K, st);
-    case DLRM_BF16: return dispatch_reduce<DLRM_BF16, OPT>(g, u, G, K, st);
+    case DLRM_F32: return dispatch_reduce<DLRM_F32, OPT, WT>(g, u, G, K, st);
+    case DLRM_F16: return dispatch_reduce<DLRM_F16, OPT, WT>(g, u, G, K, st);
+    case DLRM_BF16: return dispatch_reduce<DLRM_BF16, OPT, WT>(g, u, G, K, st);
   }
   return DLRM_ERR_BAD_DTYPE;
 }

@@ -3,6 +3,6 @@
 
 namespace dlrm {
 int run_reduce_sgd(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st) {
-  return run_reduce<kSgd>(g, u, dtype, G, K, st);
+  return run_reduce<kSgd, false>(g, u, dtype, G, K, st);
 }
 }  // namespace dlrm

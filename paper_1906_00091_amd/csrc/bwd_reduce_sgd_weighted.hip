@@ -1,0 +1,8 @@
+// Backward reduce kernels with the SGD row update, weighted pooling.
+#include "bwd_reduce.h"
+
+namespace dlrm {
+int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st) {
+  return run_reduce<kSgd, true>(g, u, dtype, G, K, st);
+}
+}  // namespace dlrm

@@ -116,7 +116,7 @@ __device__ inline uint32_t lane_entry(uint32_t v, uint32_t e, int slot) {
   }
 }
 
-template <int G>
+template <int G, bool WT>
 __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int ngroups) {
   constexpr int S = DLRM_WAVE / G;
   constexpr int MR = kHotRunsPerWave;
@@ -130,6 +130,8 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
   __shared__ uint32_t cursor[kNW * MR][NT + 1];  // first entry of a run at or after every tile boundary
   __shared__ uint32_t rsrc[kNW * MR];            // pair buffer holding the run
   __shared__ uint32_t wsc[kNW][DLRM_WAVE];       // per wavefront: compacted (offset, multiplicity) words
+  // weighted batches: a run lists positions; bag and weight are looked up by position
+  const int64_t tbl = WT ? a.tbl_off[blockIdx.y] : 0;
   const int k = blockIdx.y, g = blockIdx.x;
   const uint32_t nruns = a.hot_cnt[k];
   if (nruns == 0) return;  // uniform
@@ -158,7 +160,8 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
         uint32_t lo = 0, hi = hr.len;
         while (lo < hi) {
           const uint32_t mid = (lo + hi) >> 1;
-          if (bags[mid] < bound) lo = mid + 1; else hi = mid;
+          const uint32_t bm = WT ? a.pos_bag[tbl + bags[mid]] : bags[mid];
+          if (bm < bound) lo = mid + 1; else hi = mid;
         }
         c = hr.start + lo;
         if (tb == 0) rsrc[rl] = hr.src;
@@ -221,6 +224,33 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
           uint32_t nxt = 0;  // the next 64 bags travel while these are summed
           if (e0 + DLRM_WAVE + (uint32_t)lane < c1) nxt = bags[i][e0 + DLRM_WAVE + lane];
           const uint32_t cnt = c1 - e0 < (uint32_t)DLRM_WAVE ? c1 - e0 : (uint32_t)DLRM_WAVE;
+          if constexpr (WT) {
+            // every entry on its own: LDS offset of its bag's gradient row and its weight
+            uint32_t moff = (uint32_t)kHotTileFloats;  // entries past the end: the row of zeros, weight 0
+            float mw = 0.0f;
+            if ((uint32_t)lane < cnt) {
+              moff = (a.pos_bag[tbl + cur] - (uint32_t)tb0) * (uint32_t)u.d;
+              mw = a.weights[tbl + cur];
+            }
+            for (uint32_t e = 0; e < cnt; e += HU * S) {
+              f32x4 v[HU];
+              float m[HU];
+#pragma unroll
+              for (int q = 0; q < HU; ++q) {
+                v[q] = loadf4(tile + lane_entry<S>(moff, e + (uint32_t)(q * S), slot) + cchunk * 4);
+                m[q] = u2f(lane_entry<S>(f2u(mw), e + (uint32_t)(q * S), slot));
+              }
+#pragma unroll
+              for (int q = 0; q < HU; ++q) {
+                acc[i].x = fmaf(m[q], v[q].x, acc[i].x);
+                acc[i].y = fmaf(m[q], v[q].y, acc[i].y);
+                acc[i].z = fmaf(m[q], v[q].z, acc[i].z);
+                acc[i].w = fmaf(m[q], v[q].w, acc[i].w);
+              }
+            }
+            cur = nxt;
+            continue;
+          }
           // fold equal neighbours: the first entry of each distinct bag carries how many follow
           const uint32_t prev = (uint32_t)__shfl_up((int)cur, 1, DLRM_WAVE);
           const bool head = (uint32_t)lane < cnt && (lane == 0 || cur != prev);
@@ -280,7 +310,10 @@ int launch_segment_sort(const GroupArgs& g, hipStream_t st) {
 
 template <int G>
 static int launch_hot(const GroupArgs& g, const UpdArgs& u, int K, int ngroups, hipStream_t st) {
-  hipLaunchKernelGGL((hot_rows_kernel<G>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
+  if (g.weights != nullptr)
+    hipLaunchKernelGGL((hot_rows_kernel<G, true>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
+  else
+    hipLaunchKernelGGL((hot_rows_kernel<G, false>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }

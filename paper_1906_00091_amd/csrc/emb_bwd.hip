@@ -15,6 +15,7 @@ struct AtomArgs {
   const int64_t* indices;
   const int64_t* offsets;
   const int64_t* tbl_off;
+  const float* weights;  // NULL = sum pooling
   const float* dS;
   int64_t stride_b, stride_k;
   float lr;
@@ -33,15 +34,17 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
   const int64_t p0 = off[b], p1 = off[b + 1];
   if (p1 <= p0) return;
   const int64_t* idx = a.indices + a.tbl_off[k];
+  const float* wts = a.weights ? a.weights + a.tbl_off[k] : nullptr;
   float* W = static_cast<float*>(a.tables[k]) + chunk * 4;
   f32x4 g = loadf4(a.dS + (int64_t)b * a.stride_b + (int64_t)k * a.stride_k + chunk * 4);
   g *= -a.lr;
   for (int64_t p = p0; p < p1; ++p) {
     float* w = W + idx[p] * a.d;
-    unsafeAtomicAdd(w + 0, g.x);
-    unsafeAtomicAdd(w + 1, g.y);
-    unsafeAtomicAdd(w + 2, g.z);
-    unsafeAtomicAdd(w + 3, g.w);
+    const float ap = wts ? wts[p] : 1.0f;  // the lookup's weight in Eq. (2)
+    unsafeAtomicAdd(w + 0, ap * g.x);
+    unsafeAtomicAdd(w + 1, ap * g.y);
+    unsafeAtomicAdd(w + 2, ap * g.z);
+    unsafeAtomicAdd(w + 3, ap * g.w);
   }
 }
 
@@ -63,6 +66,9 @@ static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* wor
     st = enqueue_partition(s, g, hs);
     if (st != DLRM_OK) return st;
   }
+  if (g.weights != nullptr)
+    return OPT == kAdagrad ? run_reduce_adagrad_weighted(g, u, s->table_dtype, G, s->K, hs)
+                           : run_reduce_sgd_weighted(g, u, s->table_dtype, G, s->K, hs);
   return OPT == kAdagrad ? run_reduce_adagrad(g, u, s->table_dtype, G, s->K, hs)
                          : run_reduce_sgd(g, u, s->table_dtype, G, s->K, hs);
 }
@@ -120,6 +126,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
     a.indices = s->indices;
     a.offsets = s->offsets;
     a.tbl_off = s->tbl_off;
+    a.weights = s->weights;
     a.dS = dS;
     a.stride_b = stride_b;
     a.stride_k = stride_k;

@@ -1,5 +1,7 @@
-// Sum-pooled embedding lookup (Sec. 2.1.1, Eq. (1)-(2) with unit weights):
-// S_k[b,:] = sum over the positions of bag (k,b) of W_k[idx,:].
+// Pooled embedding lookup (Sec. 2.1.1, Eq. (1)-(2)):
+// S_k[b,:] = sum over the positions p of bag (k,b) of a_p W_k[idx_p,:]; the weights a are all
+// ones unless the batch brings them (WT kernels: one fused multiply-add per element instead
+// of an add).
 //
 // HBM-bound gather.  A table row is d*e bytes; a lane moves 16 bytes
 // (global_load_dwordx4), so a row occupies a "lane group" of G = pow2(d*e/16)
@@ -22,6 +24,7 @@ struct FwdArgs {
   const int64_t* indices;
   const int64_t* offsets;
   const int64_t* tbl_off;
+  const float* weights;  // NULL or parallel to indices
   float* out;
   int64_t stride_b, stride_k;
   int32_t K, B, d;
@@ -36,7 +39,7 @@ __device__ inline void write_pooled(float* o, const float* acc) {
 }
 
 // ---------------------------------------------------------------------------
-template <int DT, int G, int U>
+template <int DT, int G, int U, bool WT>
 __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -49,6 +52,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
   const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
   const int64_t p0 = off[b], p1 = off[b + 1];
   const int64_t* idx = a.indices + a.tbl_off[k];
+  const float* wts = WT ? a.weights + a.tbl_off[k] : nullptr;
   const char* W = static_cast<const char*>(a.tables[k]) + chunk * 16;
   const int64_t row_bytes = (int64_t)a.chunks * 16;
 
@@ -61,8 +65,13 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
     // tail re-reads the bag's last position (in cache) and is replaced by the identity
     int64_t r[U];
     u32x4 v[U];
+    float wt[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) r[u] = idx[p + u < p1 ? p + u : p1 - 1];
+    if constexpr (WT) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) wt[u] = wts[p + u < p1 ? p + u : p1 - 1];
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) v[u] = load16(W + r[u] * row_bytes);
 #pragma unroll
@@ -70,8 +79,14 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
       if (p + u >= p1) v[u] = Tab<DT>::ident();
       float f[E];
       Tab<DT>::widen(v[u], f);
+      if constexpr (WT) {
+        const float w1 = p + u >= p1 ? 1.0f : wt[u];  // 1 * (-0) leaves the sum alone
 #pragma unroll
-      for (int i = 0; i < E; ++i) acc[i] += f[i];
+        for (int i = 0; i < E; ++i) acc[i] = fmaf(w1, f[i], acc[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) acc[i] += f[i];
+      }
     }
   }
   if (p1 <= p0) {
@@ -85,7 +100,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
 // One-hot and near one-hot batches: a bag is one row, so a lane group that owns a single bag
 // has one dependent chain (offsets -> index -> row) and nothing else in flight.  Here it owns
 // NB consecutive bags and walks their chains side by side.
-template <int DT, int G, int NB>
+template <int DT, int G, int NB, bool WT>
 __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -111,10 +126,15 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     W[j] = static_cast<const char*>(a.tables[k[j]]) + chunk * 16;
   }
   int64_t r[NB];
+  float w0[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
     r[j] = 0;  // an empty bag fetches row 0 (every table has one) and drops it
-    if (p1[j] > p0[j]) r[j] = idx[j][p0[j]];
+    w0[j] = 1.0f;
+    if (p1[j] > p0[j]) {
+      r[j] = idx[j][p0[j]];
+      if constexpr (WT) w0[j] = a.weights[(idx[j] - a.indices) + p0[j]];
+    }
   }
   u32x4 v[NB];
 #pragma unroll
@@ -124,6 +144,10 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     if (bag0 + j >= nbags) continue;
     float acc[E];
     Tab<DT>::widen(v[j], acc);  // a one-index bag is a bit copy of its row
+    if constexpr (WT) {
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] *= w0[j];
+    }
     if (p1[j] <= p0[j]) {
 #pragma unroll
       for (int i = 0; i < E; ++i) acc[i] = 0.0f;
@@ -131,15 +155,16 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     for (int64_t p = p0[j] + 1; p < p1[j]; ++p) {  // the occasional longer bag
       float f[E];
       Tab<DT>::widen(load16(W[j] + idx[j][p] * row_bytes), f);
+      const float w1 = WT ? a.weights[(idx[j] - a.indices) + p] : 1.0f;
 #pragma unroll
-      for (int i = 0; i < E; ++i) acc[i] += f[i];
+      for (int i = 0; i < E; ++i) acc[i] = WT ? fmaf(w1, f[i], acc[i]) : acc[i] + f[i];
     }
     write_pooled<DT>(a.out + (int64_t)b[j] * a.stride_b + (int64_t)k[j] * a.stride_k + chunk * E, acc);
   }
 }
 
 // ---------------------------------------------------------------------------
-template <int DT, int G, int U>
+template <int DT, int G, int U, bool WT>
 __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -165,22 +190,33 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
     const int n = (int)((len - base) < DLRM_WAVE ? (len - base) : DLRM_WAVE);
     // one coalesced fetch of this chunk's indices; rows are < 2^31
     const uint32_t my_row = (uint32_t)idx[base + (lane < n ? lane : n - 1)];
+    float my_wt = 1.0f;
+    if constexpr (WT) my_wt = a.weights[(idx - a.indices) + base + (lane < n ? lane : n - 1)];
     const int iters = (n + S - 1) / S;
     for (int j = 0; j < iters; j += U) {
       u32x4 v[U];
+      float wt[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int e = (j + u) * S + slot;
         const uint32_t r = __shfl(my_row, e < n ? e : n - 1, DLRM_WAVE);
+        if constexpr (WT) wt[u] = __shfl(my_wt, e < n ? e : n - 1, DLRM_WAVE);
         v[u] = load16(W + (int64_t)r * row_bytes);   // branch-free: the tail re-reads position n-1
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        if ((j + u) * S + slot >= n) v[u] = Tab<DT>::ident();
+        const bool past = (j + u) * S + slot >= n;
+        if (past) v[u] = Tab<DT>::ident();
         float f[E];
         Tab<DT>::widen(v[u], f);
+        if constexpr (WT) {
+          const float w1 = past ? 1.0f : wt[u];
 #pragma unroll
-        for (int i = 0; i < E; ++i) acc[i] += f[i];
+          for (int i = 0; i < E; ++i) acc[i] = fmaf(w1, f[i], acc[i]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < E; ++i) acc[i] += f[i];
+        }
       }
     }
   }
@@ -201,21 +237,21 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
 // ---------------------------------------------------------------------------
 constexpr int kShortBags = 4;  // bags per lane group of the short-bag kernel
 
-template <int DT, int G>
+template <int DT, int G, bool WT>
 static int launch_fwd(const FwdArgs& a, int mode, hipStream_t st) {
   constexpr int S = DLRM_WAVE / G;
   const int64_t bags = (int64_t)a.K * a.B;
   const bool wave_mode = mode == 2;
   if (mode == 0) {
     const unsigned grid = div_up(bags, 4 * S * kShortBags);
-    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT>), dim3(grid), dim3(256), 0, st, a);
   } else if (wave_mode) {
     // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
-    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
   } else {
     const unsigned grid = div_up(bags, 4 * S);
-    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT>), dim3(grid), dim3(256), 0, st, a);
   }
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
@@ -224,13 +260,13 @@ static int launch_fwd(const FwdArgs& a, int mode, hipStream_t st) {
 template <int DT>
 static int dispatch_g(const FwdArgs& a, int G, int wave_mode, hipStream_t st) {
   switch (G) {
-    case 1: return launch_fwd<DT, 1>(a, wave_mode, st);
-    case 2: return launch_fwd<DT, 2>(a, wave_mode, st);
-    case 4: return launch_fwd<DT, 4>(a, wave_mode, st);
-    case 8: return launch_fwd<DT, 8>(a, wave_mode, st);
-    case 16: return launch_fwd<DT, 16>(a, wave_mode, st);
-    case 32: return launch_fwd<DT, 32>(a, wave_mode, st);
-    case 64: return launch_fwd<DT, 64>(a, wave_mode, st);
+    case 1: return a.weights ? launch_fwd<DT, 1, true>(a, wave_mode, st) : launch_fwd<DT, 1, false>(a, wave_mode, st);
+    case 2: return a.weights ? launch_fwd<DT, 2, true>(a, wave_mode, st) : launch_fwd<DT, 2, false>(a, wave_mode, st);
+    case 4: return a.weights ? launch_fwd<DT, 4, true>(a, wave_mode, st) : launch_fwd<DT, 4, false>(a, wave_mode, st);
+    case 8: return a.weights ? launch_fwd<DT, 8, true>(a, wave_mode, st) : launch_fwd<DT, 8, false>(a, wave_mode, st);
+    case 16: return a.weights ? launch_fwd<DT, 16, true>(a, wave_mode, st) : launch_fwd<DT, 16, false>(a, wave_mode, st);
+    case 32: return a.weights ? launch_fwd<DT, 32, true>(a, wave_mode, st) : launch_fwd<DT, 32, false>(a, wave_mode, st);
+    case 64: return a.weights ? launch_fwd<DT, 64, true>(a, wave_mode, st) : launch_fwd<DT, 64, false>(a, wave_mode, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
@@ -252,6 +288,7 @@ extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int6
   a.indices = s->indices;
   a.offsets = s->offsets;
   a.tbl_off = s->tbl_off;
+  a.weights = s->weights;
   a.out = out;
   a.stride_b = stride_b;
   a.stride_k = stride_k;

@@ -98,11 +98,12 @@ def device_hash_tables(batch: gen.Batch) -> List[torch.Tensor]:
     return out
 
 
-def make_sparse_batch(batch: gen.Batch, tables: Sequence[torch.Tensor]) -> hot.SparseBatch:
+def make_sparse_batch(batch: gen.Batch, tables: Sequence[torch.Tensor], weights=None) -> hot.SparseBatch:
     idx = torch.from_numpy(batch.indices).to(DEV)
     off = torch.from_numpy(np.ascontiguousarray(batch.offsets)).to(DEV)
     tbl = torch.from_numpy(batch.tbl_off).to(DEV)
-    return hot.SparseBatch(tables, batch.workload.dtype, idx, off, tbl, batch.nnz)
+    wts = None if weights is None else torch.from_numpy(np.ascontiguousarray(weights, dtype=np.float32)).to(DEV)
+    return hot.SparseBatch(tables, batch.workload.dtype, idx, off, tbl, batch.nnz, weights=wts)
 
 
 class Compact:

@@ -408,6 +408,125 @@ def test_emb_bag_bwd_adagrad_matches_oracle(case, fresh):
         assert torch.equal(state2[k], state[k])
 
 
+# ------------------------------------------------------------------ weighted pooling (Eq. (2) in full)
+def _abs_tables(host, dtype):
+    return [np.abs(widen_host(t, dtype)).astype(np.float32) for t in host]
+
+
+@pytest.mark.parametrize("case", [c for c in FWD_CASES if c[0] in (
+    "tiny-shape", "d4-wave", "d64-long-bags", "d64-short-bags", "d128-onehot", "d48-nonpow2",
+    "f16-d128-fixed32", "bf16-d64")], ids=lambda c: c[0])
+def test_weighted_emb_bag_fwd_matches_oracle(case):
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("weighted emb_bag_fwd " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=3)
+    b = gen.make_batch(w)
+    wts = gen.make_weights(b) * np.where(np.arange(b.nnz) % 3 == 0, -1.0, 1.0).astype(np.float32)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    sb = make_sparse_batch(b, tables, weights=wts)
+    F = K + 1
+    T = torch.full((B, F, d), 123.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+    torch.cuda.synchronize()
+    got = T.cpu().numpy()
+    want = oracle.emb_bag_fwd_weighted(host, dtype, b.indices, b.offsets, b.tbl_off, wts)
+    scale = oracle.emb_bag_fwd_weighted(_abs_tables(host, dtype), gen.F32, b.indices, b.offsets, b.tbl_off,
+                                        np.abs(wts))
+    assert np.all(got[:, 0, :] == 123.0)
+    assert rel_err(got[:, 1:, :], want, scale) <= 1e-5
+    # weights of one give the bits of the unweighted call
+    ones = make_sparse_batch(b, tables, weights=np.ones_like(wts))
+    T1 = torch.zeros_like(T)
+    T2 = torch.zeros_like(T)
+    hot.dlrm_emb_bag_fwd(ones, T1, F * d, d, out_offset=d)
+    hot.dlrm_emb_bag_fwd(make_sparse_batch(b, tables), T2, F * d, d, out_offset=d)
+    assert torch.equal(T1, T2)
+
+
+@pytest.mark.parametrize("opt", ["sgd", "adagrad"])
+@pytest.mark.parametrize("case", [c for c in BWD_CASES if c[0] in (
+    "tiny-shape", "multi-tile-ragged", "hot-rows", "d48-nonpow2", "f16-d128-fixed32", "many-hot-rows",
+    "dominant-rows-large-rest")], ids=lambda c: c[0])
+def test_weighted_emb_bag_bwd_matches_oracle(case, opt):
+    """g_r = sum_p a_p dS[bag(p)] followed by either row update; compared relative to the sum of the
+    terms' magnitudes, sum_p |a_p| |dS[bag(p)]| (and as in the Adagrad test for h and W there)."""
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("weighted emb_bag_bwd %s %s" % (name, opt))
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=9)
+    b = gen.make_batch(w)
+    wts = gen.make_weights(b) * np.where(np.arange(b.nnz) % 5 == 0, -1.0, 1.0).astype(np.float32)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    sb = make_sparse_batch(b, tables, weights=wts)
+    F = K + 1
+    dS = b.dS()
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+    ws = hot.alloc_workspace(sb)
+    lr, eps = float(np.float32(0.05)), float(np.float32(1e-8))
+    rng = np.random.default_rng(13)
+    h0 = [rng.uniform(0.01, 1.0, size=(int(r), d)).astype(np.float32) for r in b.rows]
+    ref_w = [t.copy() for t in host]
+    sg = [np.zeros((int(r), d), dtype=np.float32) for r in b.rows]       # S_g per row
+    oracle.emb_bag_bwd_weighted(sg, gen.F32, b.indices, b.offsets, b.tbl_off, np.abs(wts), np.abs(dS), -1.0)
+    uniq = [np.unique(b.indices_of(k)) for k in range(K)]
+    if opt == "sgd":
+        hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=hot.BWD_SORT, dS_offset=d)
+        oracle.emb_bag_bwd_weighted(ref_w, dtype, b.indices, b.offsets, b.tbl_off, wts, dS, lr)
+    else:
+        state = [torch.from_numpy(h.copy()).to(DEV) for h in h0]
+        hot.dlrm_emb_bag_bwd_adagrad(sb, hot.state_pointers(state), dT, F * d, d, lr, eps, ws, dS_offset=d)
+        ref_h = [h.copy() for h in h0]
+        oracle.emb_bag_bwd_weighted(ref_w, dtype, b.indices, b.offsets, b.tbl_off, wts, dS, lr, state=ref_h,
+                                    eps=eps)
+    torch.cuda.synchronize()
+    for k in range(K):
+        got_w = table_to_numpy(tables[k], dtype)
+        mask = np.ones(int(b.rows[k]), dtype=bool)
+        mask[uniq[k]] = False
+        assert np.array_equal(got_w[mask].view(np.uint8), host[k][mask].view(np.uint8))
+        if len(uniq[k]) == 0:
+            continue
+        u = uniq[k]
+        S = sg[k][u].astype(np.float64)
+        w0 = np.abs(widen_host(host[k][u], dtype)).astype(np.float64)
+        gw, rw = widen_host(got_w[u], dtype), widen_host(ref_w[k][u], dtype)
+        if opt == "sgd":
+            assert rel_err(gw, rw, w0 + lr * S, SCALE_FLOOR[dtype]) <= TOL[dtype]
+        else:
+            got_h = state[k].cpu().numpy()
+            assert np.array_equal(got_h[mask].view(np.uint32), h0[k][mask].view(np.uint32))
+            assert rel_err(got_h[u], ref_h[k][u], h0[k][u] + S * S) <= 1e-5
+            scale = w0 + lr * S / (np.sqrt(h0[k][u].astype(np.float64)) + eps)
+            assert rel_err(gw, rw, scale, SCALE_FLOOR[dtype]) <= TOL[dtype]
+    if opt == "sgd" and dtype == gen.F32:
+        # the atomic path honours the weights too
+        tables3 = upload_tables(host, dtype)
+        hot.dlrm_emb_bag_bwd_sgd(make_sparse_batch(b, tables3, weights=wts), dT, F * d, d, lr, None,
+                                 algo=hot.BWD_ATOMIC, dS_offset=d)
+        torch.cuda.synchronize()
+        for k in range(K):
+            if len(uniq[k]):
+                u = uniq[k]
+                scale = np.abs(host[k][u]).astype(np.float64) + lr * sg[k][u]
+                assert rel_err(tables3[k].cpu().numpy()[u], ref_w[k][u], scale) <= 1e-5
+    if opt == "sgd":
+        # same bits again, also with the grouping prepared ahead
+        tables2 = upload_tables(host, dtype)
+        sb2 = make_sparse_batch(b, tables2, weights=wts)
+        hot.dlrm_emb_bag_bwd_prepare(sb2, ws)
+        hot.dlrm_emb_bag_bwd_sgd(sb2, dT, F * d, d, lr, ws, algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+        # and the grouping exported from a weighted batch is the unweighted one
+        uq, seg, sbag, nu = _run_export(sb2, b.nnz, K)
+        want = oracle.group_rows(b.indices, b.offsets, b.tbl_off)
+        torch.cuda.synchronize()
+        for k in range(K):
+            assert torch.equal(tables2[k].view(torch.uint8), tables[k].view(torch.uint8))
+            a0, a1 = int(b.tbl_off[k]), int(b.tbl_off[k + 1])
+            assert np.array_equal(sbag[a0:a1], want[k][3])
+
+
 def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
     lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
     b = gen.batch_from_lists([8, 8, 8], lists, d=8)
