@@ -107,9 +107,10 @@ int32_t dlrm_lengths_to_offsets(const int32_t* lengths, int32_t K, int32_t B, in
 int32_t dlrm_validate_csr(const dlrm_sparse_batch* batch, int64_t* n_bad, void* stream);
 
 /*
- * Sum-pooled embedding lookup, Eq. (2) with unit weights (Eq. (1) when a bag has
- * one index):  out[b*stride_b + k*stride_k + c] = sum over the bag's positions p
- * of W_k[indices[p], c], c < d.  An index repeated inside a bag counts once per
+ * Pooled embedding lookup, Eq. (2) (Eq. (1) when a bag has one index):
+ * out[b*stride_b + k*stride_k + c] = sum over the bag's positions p of
+ * a_p * W_k[indices[p], c], c < d, with a_p = batch->weights[p], or 1 when the batch
+ * has no weights (sum pooling).  An index repeated inside a bag counts once per
  * occurrence; an empty bag gives zeros.  Sums are fp32, positions in ascending
  * order per lane group; a one-index bag is an exact copy of the row (widened).
  * out: fp32, strides in elements, stride_k >= d, 16-byte aligned rows

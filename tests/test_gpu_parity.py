@@ -1,7 +1,8 @@
 """GPU parity: every C-ABI entry point against the CPU oracle on the same seeded
 inputs.  Integer / index work must match bit for bit; floating point within
-1e-5 (fp32 tables) or 1e-2 (fp16/bf16 tables) max relative error with the
-denominator floored at 1e-3 of the tensor's peak magnitude."""
+1e-5 (fp32 tables) or 1e-2 (fp16/bf16 tables) max error relative to the magnitude
+of the sum that produced the element, sum_j |term_j| (the oracle run on absolute
+values; equal to |reference| where nothing cancels)."""
 import numpy as np
 import pytest
 import torch
