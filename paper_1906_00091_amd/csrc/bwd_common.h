@@ -361,9 +361,9 @@ __device__ inline char* row_chunk_ptr(char* W, int d, uint32_t row, int chunk) {
 template <int DT>
 __device__ inline u32x4 row_chunk_load(const char* p) {
   if constexpr (DT == DLRM_F32) {
-    return load16(p);
+    return load16_stream(p);
   } else {
-    const u32x2 b = *reinterpret_cast<const u32x2*>(p);
+    const u32x2 b = load8_stream(p);
     return u32x4{b.x, b.y, 0u, 0u};
   }
 }
@@ -375,7 +375,7 @@ __device__ inline void row_chunk_update_store(char* p, u32x4 raw, f32x4 g, float
     x.y = fmaf(-lr, g.y, u2f(raw.y));
     x.z = fmaf(-lr, g.z, u2f(raw.z));
     x.w = fmaf(-lr, g.w, u2f(raw.w));
-    storef4(reinterpret_cast<float*>(p), x);
+    store16_stream(p, u32x4{f2u(x.x), f2u(x.y), f2u(x.z), f2u(x.w)});
   } else {
     float x0, x1, x2, x3;
     if constexpr (DT == DLRM_F16) {
@@ -397,7 +397,7 @@ __device__ inline void row_chunk_update_store(char* p, u32x4 raw, f32x4 g, float
       b.x = float2_to_bf162(x0, x1);
       b.y = float2_to_bf162(x2, x3);
     }
-    *reinterpret_cast<u32x2*>(p) = b;
+    store8_stream(p, b);
   }
 }
 // The same 4 columns of a row together with their optimizer state (none for SGD).
@@ -422,7 +422,10 @@ __device__ inline RowVal row_load(const RowRef& r) {
   RowVal v;
   v.w = row_chunk_load<DT>(r.w);
   v.h = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  if constexpr (OPT == kAdagrad) v.h = loadf4(r.h);
+  if constexpr (OPT == kAdagrad) {
+    const u32x4 hb = load16_stream(r.h);
+    v.h = f32x4{u2f(hb.x), u2f(hb.y), u2f(hb.z), u2f(hb.w)};
+  }
   return v;
 }
 template <int DT, int OPT>
@@ -433,7 +436,7 @@ __device__ inline void row_update_store(const RowRef& r, const RowVal& v, f32x4 
     h.y = fmaf(g.y, g.y, v.h.y);
     h.z = fmaf(g.z, g.z, v.h.z);
     h.w = fmaf(g.w, g.w, v.h.w);
-    storef4(r.h, h);
+    store16_stream(r.h, u32x4{f2u(h.x), f2u(h.y), f2u(h.z), f2u(h.w)});
     step.x = u.lr * g.x / (sqrtf(h.x) + u.eps);
     step.y = u.lr * g.y / (sqrtf(h.y) + u.eps);
     step.z = u.lr * g.z / (sqrtf(h.z) + u.eps);

@@ -124,6 +124,20 @@ struct Tab<DLRM_BF16> {
 __device__ inline u32x4 load16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ inline void store16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ inline f32x4 loadf4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+// Streaming accesses: data touched once per launch (table rows) should not push reusable data
+// (gradient rows, pair lists) out of the L2.
+__device__ inline u32x4 load16_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ inline void store16_stream(void* p, u32x4 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+__device__ inline u32x2 load8_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+}
+__device__ inline void store8_stream(void* p, u32x2 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(p));
+}
 __device__ inline void storef4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
 
 __device__ inline int lane_id() { return threadIdx.x & (DLRM_WAVE - 1); }
