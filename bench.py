@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adagrad"],
                     help="row update of the fused backward (the metric is quoted on sgd)")
+    ap.add_argument("--index32", action="store_true", help="int32 index arrays instead of int64")
     ap.add_argument("--weighted", action="store_true",
                     help="per-lookup weights (Eq. (2) in full) instead of sum pooling; the metric is quoted without")
     ap.add_argument("--no-overlap", action="store_true",
@@ -50,13 +51,13 @@ def parse_args():
     return ap.parse_args()
 
 
-def algorithmic_bytes(w, batch, elem_bytes):
+def algorithmic_bytes(w, batch, elem_bytes, index_bytes=8, weighted=False):
     """Minimum HBM traffic of the embedding forward / backward for this batch (ideal cache:
     each touched row once, each index, offset, pooled vector and gradient once)."""
     import numpy as np
     U = sum(len(np.unique(batch.indices_of(k))) for k in range(w.K))
     nnz = batch.nnz
-    csr = nnz * 8 + w.K * (w.B + 1) * 8
+    csr = nnz * (index_bytes + (4 if weighted else 0)) + w.K * (w.B + 1) * 8
     pooled = w.K * w.B * w.d * 4
     fwd = U * w.d * elem_bytes + csr + pooled
     bwd = pooled + csr + 2 * U * w.d * elem_bytes
@@ -91,12 +92,12 @@ def main():
     # ---- inputs, resident in HBM before anything is timed
     rows = gen.table_rows(w)
     first = gen.make_batch(w, rows=rows)
-    ab0 = algorithmic_bytes(w, first, eb)
+    ab0 = algorithmic_bytes(w, first, eb, 4 if args.index32 else 8, args.weighted)
     nb = args.nbatches
     if nb <= 0:  # enough distinct batches that one batch's rows are out of the 256 MB cache again
         nb = int(min(32, max(2, -(-(1 << 30) // max(ab0["fwd"], 1)))))
     batches = [first] + [gen.make_batch(w, batch_id=i, rows=rows) for i in range(1, nb)]
-    abytes = [ab0] + [algorithmic_bytes(w, b, eb) for b in batches[1:]]
+    abytes = [ab0] + [algorithmic_bytes(w, b, eb, 4 if args.index32 else 8, args.weighted) for b in batches[1:]]
     tdt = {gen.F32: torch.float32, gen.F16: torch.float16, gen.BF16: torch.bfloat16}[w.dtype]
     tables = []
     for k in range(K):
@@ -106,7 +107,8 @@ def main():
     dev_batches = []
     for b in batches:
         wts = torch.from_numpy(gen.make_weights(b)).to(dev) if args.weighted else None
-        sb = hot.SparseBatch(tables, w.dtype, torch.from_numpy(b.indices).to(dev),
+        sb = hot.SparseBatch(tables, w.dtype,
+                             torch.from_numpy(b.indices.astype(np.int32) if args.index32 else b.indices).to(dev),
                              torch.from_numpy(np.ascontiguousarray(b.offsets)).to(dev),
                              torch.from_numpy(b.tbl_off).to(dev), b.nnz, max_rows=int(rows.max()), weights=wts)
         dev_batches.append((sb, torch.from_numpy(b.x).to(dev), torch.from_numpy(b.dR).to(dev)))
@@ -270,6 +272,7 @@ def main():
                    "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
                    "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
                    "bwd_algo": args.algo, "optimizer": args.optimizer, "pooling": "weighted" if args.weighted else "sum",
+                   "indices": "int32" if args.index32 else "int64",
                    "lr": w.lr,
                    "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),

@@ -43,6 +43,11 @@ extern "C" {
 #define DLRM_F16 1
 #define DLRM_BF16 2
 
+/* element type of a batch's index array (Sec. 5.1: the framework operators take int64
+ * or int32 indices) */
+#define DLRM_I64 0 /* int64 (what the five workloads use) */
+#define DLRM_I32 1 /* int32: 4 bytes less traffic per lookup */
+
 /* backward algorithms */
 #define DLRM_BWD_AUTO 0   /* library's measured choice for the shape */
 #define DLRM_BWD_SORT 1   /* group (row, bag) pairs by row, reduce, one update per row; deterministic */
@@ -72,7 +77,8 @@ typedef struct dlrm_sparse_batch {
   int64_t max_rows;        /* host upper bound on rows[k] over all k, 1 <= max_rows <= DLRM_MAX_ROWS */
   void* const* tables;     /* [K] base pointer of table k: [rows[k], d] row-major, 16-byte aligned */
   const int64_t* rows;     /* [K] m_k */
-  const int64_t* indices;  /* [nnz_total] table-major: table k owns [tbl_off[k], tbl_off[k+1]) */
+  const void* indices;     /* [nnz_total] int64 (or int32, see index_dtype), table-major: table k owns
+                              [tbl_off[k], tbl_off[k+1]) */
   const int64_t* offsets;  /* [K*(B+1)] per-table local offsets; bag b of table k = positions
                               [offsets[k*(B+1)+b], offsets[k*(B+1)+b+1]); offsets[k*(B+1)+B] = nnz_k */
   const int64_t* tbl_off;  /* [K+1] start of table k's slice in `indices` */
@@ -80,6 +86,7 @@ typedef struct dlrm_sparse_batch {
                               lookup in Eq. (2).  NULL = all ones (sum pooling, what the five workloads
                               use).  With weights, bag b of table k pools sum_p weights[p] * W_k[indices[p],:]
                               and the backward sums weights[p] * dS[bag(p)]; the weights get no gradient. */
+  int32_t index_dtype;     /* DLRM_I64 (0) or DLRM_I32: element type of `indices` */
 } dlrm_sparse_batch;
 
 /* Library version (major*10000 + minor*100 + patch). */

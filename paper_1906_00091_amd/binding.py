@@ -13,6 +13,7 @@ import torch
 from . import build as _build
 
 F32, F16, BF16 = 0, 1, 2
+I64, I32 = 0, 1
 BWD_AUTO, BWD_SORT, BWD_ATOMIC, BWD_SORT_PREPARED = 0, 1, 2, 3
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 _ELEM = {F32: 4, F16: 2, BF16: 2}
@@ -30,6 +31,7 @@ class _SparseBatchC(C.Structure):
         ("nnz_total", C.c_int64), ("max_rows", C.c_int64),
         ("tables", C.c_void_p), ("rows", C.c_void_p), ("indices", C.c_void_p),
         ("offsets", C.c_void_p), ("tbl_off", C.c_void_p), ("weights", C.c_void_p),
+        ("index_dtype", C.c_int32),
     ]
 
 
@@ -114,7 +116,8 @@ class SparseBatch:
         for t in self.tables:
             assert t.is_contiguous() and t.dtype == _TORCH_DTYPE[table_dtype] and t.shape[1] == d
         assert offsets.dtype == torch.int64 and offsets.is_contiguous() and offsets.shape[0] == K
-        assert indices.dtype == torch.int64 and tbl_off.dtype == torch.int64
+        assert indices.dtype in (torch.int64, torch.int32) and tbl_off.dtype == torch.int64
+        assert indices.is_contiguous()
         self.K, self.B, self.d = K, int(offsets.shape[1]) - 1, d
         self.table_dtype = table_dtype
         self.indices, self.offsets, self.tbl_off = indices, offsets, tbl_off
@@ -131,7 +134,8 @@ class SparseBatch:
                                _ptr(self.table_ptrs), _ptr(self.rows),
                                _ptr(indices) if indices.numel() else None,
                                _ptr(offsets), _ptr(tbl_off),
-                               _ptr(weights) if weights is not None and weights.numel() else None)
+                               _ptr(weights) if weights is not None and weights.numel() else None,
+                               I32 if indices.dtype == torch.int32 else I64)
 
     def ref(self):
         return C.byref(self.c)

@@ -140,10 +140,11 @@ inline WsLayout ws_layout(int32_t K, int32_t B, int32_t d, int64_t nnz) {
 
 // ---------------------------------------------------------------------------
 struct GroupArgs {            // everything the grouping kernels need
-  const int64_t* indices;
+  const void* indices;        // int64 or int32 (idx32)
   const int64_t* offsets;
   const int64_t* tbl_off;
   const int64_t* rows;
+  int32_t idx32;
   const float* weights;       // NULL, or the weight of every lookup (parallel to indices)
   uint32_t* pos_bag;          // weighted batches: bag of every position, in the original order
   int32_t K, B;
@@ -465,6 +466,7 @@ int check_batch(const dlrm_sparse_batch* s);  // util.hip
 inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLayout& L, void* ws) {
   char* base = static_cast<char*>(ws);
   g.indices = s->indices;
+  g.idx32 = s->index_dtype == DLRM_I32;
   g.offsets = s->offsets;
   g.tbl_off = s->tbl_off;
   g.rows = s->rows;

@@ -4,6 +4,7 @@
 namespace dlrm {
 
 // --- 1. per-tile histogram of the partition digit ----------------------------------
+template <typename IT>
 __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
   __shared__ uint32_t h[kMaxBuckets];
   __shared__ uint32_t smem[kNW + 1];
@@ -12,7 +13,7 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
   const int nb = 1 << a.top_bits;
   for (int i = threadIdx.x; i < nb; i += kThreads) h[i] = 0;
   __syncthreads();
-  const int64_t* idx = a.indices + ti.start;
+  const IT* idx = static_cast<const IT*>(a.indices) + ti.start;
   const int shift = top_shift(a, ti.k);
   const uint32_t mask = (uint32_t)nb - 1;
   for (int i = threadIdx.x; i < ti.count; i += kThreads)
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
 
 
 // --- 3. stable scatter into buckets ---------------------------------------------------
+template <typename IT>
 __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
   __shared__ uint32_t wcnt[kNW][kMaxBuckets];
   __shared__ uint32_t gofs[kMaxBuckets];
@@ -90,7 +92,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
 
   // ---- requested first so that their latency hides behind the bag search: the tile's row ids
   // (wave-striped) and, for small batches, this digit's counts in all tiles of the table
-  const int64_t* kin = a.indices + ti.start;
+  const IT* kin = static_cast<const IT*>(a.indices) + ti.start;
   const int shift = top_shift(a, ti.k);
   uint32_t key[kItems], val[kItems], dg[kItems], rnk[kItems];
   bool ok[kItems];
@@ -243,13 +245,19 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
 
 
 int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_t st) {
-  hipLaunchKernelGGL(bucket_hist_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  if (g.idx32)
+    hipLaunchKernelGGL(bucket_hist_kernel<int32_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  else
+    hipLaunchKernelGGL(bucket_hist_kernel<int64_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
   if (!g.fused_scan) {
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(1024), 0, st, g);
     DLRM_CHECK_LAUNCH();
   }
-  hipLaunchKernelGGL(bucket_scatter_kernel, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  if (g.idx32)
+    hipLaunchKernelGGL(bucket_scatter_kernel<int32_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  else
+    hipLaunchKernelGGL(bucket_scatter_kernel<int64_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }

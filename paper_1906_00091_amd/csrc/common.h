@@ -124,6 +124,12 @@ struct Tab<DLRM_BF16> {
 __device__ inline u32x4 load16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
 __device__ inline void store16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ inline f32x4 loadf4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+// Element i of a batch's index array, whose element type is a run-time property of the batch
+// (cold paths only; the hot kernels are compiled per index type).
+__device__ inline int64_t index_at(const void* indices, int is32, int64_t i) {
+  return is32 ? (int64_t)static_cast<const int32_t*>(indices)[i] : static_cast<const int64_t*>(indices)[i];
+}
+
 // Streaming accesses: data touched once per launch (table rows) should not push reusable data
 // (gradient rows, pair lists) out of the L2.
 __device__ inline u32x4 load16_stream(const void* p) {

@@ -12,7 +12,8 @@ hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 // --- ATOMIC path --------------------------------------------------------------------
 struct AtomArgs {
   void* const* tables;
-  const int64_t* indices;
+  const void* indices;
+  int32_t idx32;
   const int64_t* offsets;
   const int64_t* tbl_off;
   const float* weights;  // NULL = sum pooling
@@ -33,13 +34,13 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
   const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
   const int64_t p0 = off[b], p1 = off[b + 1];
   if (p1 <= p0) return;
-  const int64_t* idx = a.indices + a.tbl_off[k];
-  const float* wts = a.weights ? a.weights + a.tbl_off[k] : nullptr;
+  const int64_t tbl = a.tbl_off[k];
+  const float* wts = a.weights ? a.weights + tbl : nullptr;
   float* W = static_cast<float*>(a.tables[k]) + chunk * 4;
   f32x4 g = loadf4(a.dS + (int64_t)b * a.stride_b + (int64_t)k * a.stride_k + chunk * 4);
   g *= -a.lr;
   for (int64_t p = p0; p < p1; ++p) {
-    float* w = W + idx[p] * a.d;
+    float* w = W + index_at(a.indices, a.idx32, tbl + p) * a.d;
     const float ap = wts ? wts[p] : 1.0f;  // the lookup's weight in Eq. (2)
     unsafeAtomicAdd(w + 0, ap * g.x);
     unsafeAtomicAdd(w + 1, ap * g.y);
@@ -124,6 +125,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
     AtomArgs a;
     a.tables = s->tables;
     a.indices = s->indices;
+    a.idx32 = s->index_dtype == DLRM_I32;
     a.offsets = s->offsets;
     a.tbl_off = s->tbl_off;
     a.weights = s->weights;

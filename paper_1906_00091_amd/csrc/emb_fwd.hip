@@ -21,7 +21,7 @@ namespace dlrm {
 
 struct FwdArgs {
   void* const* tables;
-  const int64_t* indices;
+  const void* indices;   // int64 or int32: the kernels are compiled per index type IT
   const int64_t* offsets;
   const int64_t* tbl_off;
   const float* weights;  // NULL or parallel to indices
@@ -39,7 +39,7 @@ __device__ inline void write_pooled(float* o, const float* acc) {
 }
 
 // ---------------------------------------------------------------------------
-template <int DT, int G, int U, bool WT>
+template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
   const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
   const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
   const int64_t p0 = off[b], p1 = off[b + 1];
-  const int64_t* idx = a.indices + a.tbl_off[k];
+  const IT* idx = static_cast<const IT*>(a.indices) + a.tbl_off[k];
   const float* wts = WT ? a.weights + a.tbl_off[k] : nullptr;
   const char* W = static_cast<const char*>(a.tables[k]) + chunk * 16;
   const int64_t row_bytes = (int64_t)a.chunks * 16;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
 // One-hot and near one-hot batches: a bag is one row, so a lane group that owns a single bag
 // has one dependent chain (offsets -> index -> row) and nothing else in flight.  Here it owns
 // NB consecutive bags and walks their chains side by side.
-template <int DT, int G, int NB, bool WT>
+template <int DT, int G, int NB, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -112,7 +112,8 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
   const int64_t row_bytes = (int64_t)a.chunks * 16;
   int k[NB], b[NB];
   int64_t p0[NB], p1[NB];
-  const int64_t* idx[NB];
+  const IT* idx[NB];
+  int64_t tb[NB];
   const char* W[NB];
 #pragma unroll
   for (int j = 0; j < NB; ++j) {
@@ -122,7 +123,8 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     const int64_t* off = a.offsets + (int64_t)k[j] * (a.B + 1);
     p0[j] = off[b[j]];
     p1[j] = off[b[j] + 1];
-    idx[j] = a.indices + a.tbl_off[k[j]];
+    tb[j] = a.tbl_off[k[j]];
+    idx[j] = static_cast<const IT*>(a.indices) + tb[j];
     W[j] = static_cast<const char*>(a.tables[k[j]]) + chunk * 16;
   }
   int64_t r[NB];
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     w0[j] = 1.0f;
     if (p1[j] > p0[j]) {
       r[j] = idx[j][p0[j]];
-      if constexpr (WT) w0[j] = a.weights[(idx[j] - a.indices) + p0[j]];
+      if constexpr (WT) w0[j] = a.weights[tb[j] + p0[j]];
     }
   }
   u32x4 v[NB];
@@ -154,8 +156,8 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
     }
     for (int64_t p = p0[j] + 1; p < p1[j]; ++p) {  // the occasional longer bag
       float f[E];
-      Tab<DT>::widen(load16(W[j] + idx[j][p] * row_bytes), f);
-      const float w1 = WT ? a.weights[(idx[j] - a.indices) + p] : 1.0f;
+      Tab<DT>::widen(load16(W[j] + (int64_t)idx[j][p] * row_bytes), f);
+      const float w1 = WT ? a.weights[tb[j] + p] : 1.0f;
 #pragma unroll
       for (int i = 0; i < E; ++i) acc[i] = WT ? fmaf(w1, f[i], acc[i]) : acc[i] + f[i];
     }
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-template <int DT, int G, int U, bool WT>
+template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -175,7 +177,8 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
   const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
   const int64_t* off = a.offsets + (int64_t)k * (a.B + 1);
   const int64_t p0 = off[b], p1 = off[b + 1];
-  const int64_t* idx = a.indices + a.tbl_off[k] + p0;
+  const int64_t pos0 = a.tbl_off[k] + p0;
+  const IT* idx = static_cast<const IT*>(a.indices) + pos0;
   const bool col_ok = chunk < a.chunks;
   // lanes past the row's last chunk shadow chunk 0 (same address, no extra traffic) and never write
   const char* W = static_cast<const char*>(a.tables[k]) + (col_ok ? chunk : 0) * 16;
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
     // one coalesced fetch of this chunk's indices; rows are < 2^31
     const uint32_t my_row = (uint32_t)idx[base + (lane < n ? lane : n - 1)];
     float my_wt = 1.0f;
-    if constexpr (WT) my_wt = a.weights[(idx - a.indices) + base + (lane < n ? lane : n - 1)];
+    if constexpr (WT) my_wt = a.weights[pos0 + base + (lane < n ? lane : n - 1)];
     const int iters = (n + S - 1) / S;
     for (int j = 0; j < iters; j += U) {
       u32x4 v[U];
@@ -237,36 +240,43 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
 // ---------------------------------------------------------------------------
 constexpr int kShortBags = 4;  // bags per lane group of the short-bag kernel
 
-template <int DT, int G, bool WT>
+template <int DT, int G, bool WT, typename IT>
 static int launch_fwd(const FwdArgs& a, int mode, hipStream_t st) {
   constexpr int S = DLRM_WAVE / G;
   const int64_t bags = (int64_t)a.K * a.B;
   const bool wave_mode = mode == 2;
   if (mode == 0) {
     const unsigned grid = div_up(bags, 4 * S * kShortBags);
-    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT, IT>), dim3(grid), dim3(256), 0, st, a);
   } else if (wave_mode) {
     // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
-    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT, IT>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
   } else {
     const unsigned grid = div_up(bags, 4 * S);
-    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT, IT>), dim3(grid), dim3(256), 0, st, a);
   }
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
 
+template <int DT, int G>
+static int pick_fwd(const FwdArgs& a, bool idx32, int mode, hipStream_t st) {
+  if (a.weights)
+    return idx32 ? launch_fwd<DT, G, true, int32_t>(a, mode, st) : launch_fwd<DT, G, true, int64_t>(a, mode, st);
+  return idx32 ? launch_fwd<DT, G, false, int32_t>(a, mode, st) : launch_fwd<DT, G, false, int64_t>(a, mode, st);
+}
+
 template <int DT>
-static int dispatch_g(const FwdArgs& a, int G, int wave_mode, hipStream_t st) {
+static int dispatch_g(const FwdArgs& a, int G, bool idx32, int wave_mode, hipStream_t st) {
   switch (G) {
-    case 1: return a.weights ? launch_fwd<DT, 1, true>(a, wave_mode, st) : launch_fwd<DT, 1, false>(a, wave_mode, st);
-    case 2: return a.weights ? launch_fwd<DT, 2, true>(a, wave_mode, st) : launch_fwd<DT, 2, false>(a, wave_mode, st);
-    case 4: return a.weights ? launch_fwd<DT, 4, true>(a, wave_mode, st) : launch_fwd<DT, 4, false>(a, wave_mode, st);
-    case 8: return a.weights ? launch_fwd<DT, 8, true>(a, wave_mode, st) : launch_fwd<DT, 8, false>(a, wave_mode, st);
-    case 16: return a.weights ? launch_fwd<DT, 16, true>(a, wave_mode, st) : launch_fwd<DT, 16, false>(a, wave_mode, st);
-    case 32: return a.weights ? launch_fwd<DT, 32, true>(a, wave_mode, st) : launch_fwd<DT, 32, false>(a, wave_mode, st);
-    case 64: return a.weights ? launch_fwd<DT, 64, true>(a, wave_mode, st) : launch_fwd<DT, 64, false>(a, wave_mode, st);
+    case 1: return pick_fwd<DT, 1>(a, idx32, wave_mode, st);
+    case 2: return pick_fwd<DT, 2>(a, idx32, wave_mode, st);
+    case 4: return pick_fwd<DT, 4>(a, idx32, wave_mode, st);
+    case 8: return pick_fwd<DT, 8>(a, idx32, wave_mode, st);
+    case 16: return pick_fwd<DT, 16>(a, idx32, wave_mode, st);
+    case 32: return pick_fwd<DT, 32>(a, idx32, wave_mode, st);
+    case 64: return pick_fwd<DT, 64>(a, idx32, wave_mode, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
@@ -303,10 +313,11 @@ extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int6
   // mode 0: several bags per lane group (mean bag <= 2), 1: a lane group per bag, 2: a wavefront per bag
   const int wave_mode = mean_len <= 2.0 ? 0 : (S > 1 && mean_len >= 2.0 * S) ? 2 : 1;
   hipStream_t hs = static_cast<hipStream_t>(stream);
+  const bool idx32 = s->index_dtype == DLRM_I32;
   switch (s->table_dtype) {
-    case DLRM_F32: return dispatch_g<DLRM_F32>(a, G, wave_mode, hs);
-    case DLRM_F16: return dispatch_g<DLRM_F16>(a, G, wave_mode, hs);
-    case DLRM_BF16: return dispatch_g<DLRM_BF16>(a, G, wave_mode, hs);
+    case DLRM_F32: return dispatch_g<DLRM_F32>(a, G, idx32, wave_mode, hs);
+    case DLRM_F16: return dispatch_g<DLRM_F16>(a, G, idx32, wave_mode, hs);
+    case DLRM_BF16: return dispatch_g<DLRM_BF16>(a, G, idx32, wave_mode, hs);
   }
   return DLRM_ERR_BAD_DTYPE;
 }

@@ -17,6 +17,7 @@ int check_batch(const dlrm_sparse_batch* s) {
   if ((int64_t)s->K * (s->B + 1) > DLRM_MAX_NNZ) return DLRM_ERR_BAD_SHAPE;
   if (!s->tables || !s->rows || !s->offsets || !s->tbl_off) return DLRM_ERR_NULL;
   if (s->nnz_total > 0 && !s->indices) return DLRM_ERR_NULL;
+  if (s->index_dtype != DLRM_I64 && s->index_dtype != DLRM_I32) return DLRM_ERR_BAD_DTYPE;
   return DLRM_OK;
 }
 
@@ -57,11 +58,11 @@ __global__ __launch_bounds__(256) void tbl_off_kernel(const int64_t* __restrict_
 // ---------------------------------------------------------------------------
 struct ValArgs {
   const int64_t* rows;
-  const int64_t* indices;
+  const void* indices;
   const int64_t* offsets;
   const int64_t* tbl_off;
   int64_t nnz_total;
-  int32_t K, B;
+  int32_t K, B, idx32;
   unsigned long long* n_bad;
 };
 
@@ -96,7 +97,7 @@ __global__ __launch_bounds__(256) void validate_kernel(ValArgs a) {
       const int mid = (lo + hi) >> 1;
       if (a.tbl_off[mid] <= p) lo = mid; else hi = mid;
     }
-    const int64_t r = a.indices[p];
+    const int64_t r = index_at(a.indices, a.idx32, p);
     if (r < 0 || r >= a.rows[lo]) ++bad;
   }
   // wave reduction, one atomic per wavefront
@@ -195,6 +196,7 @@ extern "C" int32_t dlrm_validate_csr(const dlrm_sparse_batch* s, int64_t* n_bad,
   ValArgs a;
   a.rows = s->rows;
   a.indices = s->indices;
+  a.idx32 = s->index_dtype == DLRM_I32;
   a.offsets = s->offsets;
   a.tbl_off = s->tbl_off;
   a.nnz_total = s->nnz_total;

@@ -98,8 +98,9 @@ def device_hash_tables(batch: gen.Batch) -> List[torch.Tensor]:
     return out
 
 
-def make_sparse_batch(batch: gen.Batch, tables: Sequence[torch.Tensor], weights=None) -> hot.SparseBatch:
-    idx = torch.from_numpy(batch.indices).to(DEV)
+def make_sparse_batch(batch: gen.Batch, tables: Sequence[torch.Tensor], weights=None,
+                      index32: bool = False) -> hot.SparseBatch:
+    idx = torch.from_numpy(batch.indices.astype(np.int32) if index32 else batch.indices).to(DEV)
     off = torch.from_numpy(np.ascontiguousarray(batch.offsets)).to(DEV)
     tbl = torch.from_numpy(batch.tbl_off).to(DEV)
     wts = None if weights is None else torch.from_numpy(np.ascontiguousarray(weights, dtype=np.float32)).to(DEV)

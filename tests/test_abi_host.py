@@ -52,6 +52,13 @@ def test_forward_rejects_bad_arguments_on_the_host():
     assert L.dlrm_emb_bag_fwd(None, out, 64, 16, None) == -1
 
 
+def test_unknown_index_dtype_is_rejected():
+    L = hot.lib()
+    # (no output pointer: a known index type gets as far as that check, nothing is launched)
+    assert L.dlrm_emb_bag_fwd(C.byref(_batch(index_dtype=1)), None, 64, 16, None) == -1
+    assert L.dlrm_emb_bag_fwd(C.byref(_batch(index_dtype=2)), None, 64, 16, None) == -3
+
+
 def test_backward_rejects_bad_arguments_on_the_host():
     L = hot.lib()
     ds = C.c_void_p(0x1000)

@@ -528,6 +528,69 @@ def test_weighted_emb_bag_bwd_matches_oracle(case, opt):
             assert np.array_equal(sbag[a0:a1], want[k][3])
 
 
+# ------------------------------------------------------------------ int32 indices
+@pytest.mark.parametrize("case", [c for c in BWD_CASES if c[0] in (
+    "tiny-shape", "multi-tile-ragged", "hot-rows", "onehot-zipf", "f16-d128-fixed32", "many-hot-rows")],
+    ids=lambda c: c[0])
+def test_int32_indices_give_the_bits_of_int64_indices(case):
+    """Forward, validator, sort and atomic backward, grouping export: a batch whose index array is
+    int32 must give, bit for bit, what the same batch with int64 indices gives (itself checked against
+    the oracle by the other tests)."""
+    name, K, B, d, dtype, rows, bag, dist = case
+    _say("int32 indices " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=10)
+    b = gen.make_batch(w)
+    wts = gen.make_weights(b)
+    host = _host_tables(b)
+    F = K + 1
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(b.dS()).to(DEV)
+    lr = float(np.float32(w.lr))
+    results = []
+    for index32 in (False, True):
+        out = {}
+        for weights in (None, wts):
+            tables = upload_tables(host, dtype)
+            sb = make_sparse_batch(b, tables, weights=weights, index32=index32)
+            n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+            hot.dlrm_validate_csr(sb, n_bad)
+            assert int(n_bad.item()) == 0
+            T = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+            hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+            ws = hot.alloc_workspace(sb)
+            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=hot.BWD_SORT, dS_offset=d)
+            tag = "w" if weights is not None else "u"
+            out["T" + tag] = T
+            out["W" + tag] = tables
+        sb = make_sparse_batch(b, upload_tables(host, dtype), index32=index32)
+        out["export"] = _run_export(sb, b.nnz, K)
+        results.append(out)
+    torch.cuda.synchronize()
+    a64, a32 = results
+    for tag in ("u", "w"):
+        assert torch.equal(a64["T" + tag], a32["T" + tag])
+        for k in range(K):
+            assert torch.equal(a64["W" + tag][k].view(torch.uint8), a32["W" + tag][k].view(torch.uint8))
+    for x, y in zip(a64["export"], a32["export"]):
+        assert np.array_equal(x, y)
+    # a bad int32 index is counted like a bad int64 one
+    bad_idx = b.indices.copy()
+    bad_idx[0] = -1
+    bad = gen.Batch(b.workload, b.rows, b.lengths, b.offsets, b.tbl_off, bad_idx, b.x, b.dR)
+    n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    hot.dlrm_validate_csr(make_sparse_batch(bad, upload_tables(host, dtype), index32=True), n_bad)
+    assert int(n_bad.item()) == 1
+    if dtype == gen.F32:   # atomic path with int32 indices against the oracle
+        tables = upload_tables(host, dtype)
+        hot.dlrm_emb_bag_bwd_sgd(make_sparse_batch(b, tables, index32=True), dT, F * d, d, lr, None,
+                                 algo=hot.BWD_ATOMIC, dS_offset=d)
+        ref = [t.copy() for t in host]
+        oracle.emb_bag_bwd_sgd(ref, dtype, b.indices, b.offsets, b.tbl_off, b.dS(), lr)
+        scale = scale_sgd(host, dtype, b.indices, b.offsets, b.tbl_off, b.dS(), lr)
+        for k in range(K):
+            assert rel_err(tables[k].cpu().numpy(), ref[k], scale[k]) <= 1e-5
+
+
 def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
     lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
     b = gen.batch_from_lists([8, 8, 8], lists, d=8)
