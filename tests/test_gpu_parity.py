@@ -86,6 +86,8 @@ FWD_CASES = [
     ("f16-d8", 2, 50, 8, gen.F16, 64, ("uniform", 0, 6), ("uniform",)),
     ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
     ("one-row-table", 2, 20, 16, gen.F32, 1, ("uniform", 0, 5), ("uniform",)),
+    ("300-tables", 300, 40, 8, gen.F32, 60, ("uniform", 0, 6), ("zipf", 1.1)),
+    ("single-table-single-bag", 1, 1, 32, gen.F32, 500, ("fixed", 700), ("uniform",)),
     ("single-bag", 1, 1, 32, gen.F32, 10, ("fixed", 7), ("uniform",)),
 ]
 
@@ -183,6 +185,9 @@ BWD_CASES = [
     ("f16-d128-fixed32", 4, 300, 128, gen.F16, 20000, ("fixed", 32), ("zipf", 1.2)),
     ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
     ("one-row-table", 2, 5000, 16, gen.F32, 1, ("fixed", 1), ("uniform",)),
+    # more tables than a workgroup has threads (the tile map and the hot-row lists walk them in chunks)
+    ("300-tables", 300, 40, 8, gen.F32, 60, ("uniform", 0, 6), ("zipf", 1.1)),
+    ("single-table-single-bag", 1, 1, 32, gen.F32, 500, ("fixed", 700), ("uniform",)),
     # rarely taken routes of the sort path
     # 40 rows x ~4096 lookups each: more hot rows per table than one pass of the hot-row kernel holds
     ("many-hot-rows", 2, 4096, 32, gen.F32, 40, ("fixed", 40), ("uniform",)),
