@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--index32", action="store_true", help="int32 index arrays instead of int64")
     ap.add_argument("--weighted", action="store_true",
                     help="per-lookup weights (Eq. (2) in full) instead of sum pooling; the metric is quoted without")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each distinct batch's step in a HIP graph (through torch) and time replays")
     ap.add_argument("--no-overlap", action="store_true",
                     help="group the (row, bag) pairs inside the backward call instead of on a second "
                          "stream beside the forward pass")
@@ -162,10 +164,13 @@ def main():
         return ev
     red_ev = [(hip_event(), hip_event()) for _ in range(args.steps)] if args.algo != "atomic" else None
 
-    def step(i, ev=None, red=None, overlap=overlap):
+    def step(i, ev=None, red=None, overlap=overlap, capturing=False):
         sb, x, dR = dev_batches[i % nb]
         if overlap:
-            side.wait_event(upd_done)   # the previous step's update is done with the workspace
+            if capturing:  # inside a graph the second stream forks from the capturing one
+                side.wait_stream(torch.cuda.current_stream())
+            else:
+                side.wait_event(upd_done)   # the previous step's update is done with the workspace
             with torch.cuda.stream(side):
                 hot.dlrm_emb_bag_bwd_prepare(sb, ws)
                 prep_done.record(side)
@@ -188,7 +193,8 @@ def main():
         if overlap:
             torch.cuda.current_stream().wait_event(prep_done)
             backward(sb, hot.BWD_SORT_PREPARED)
-            upd_done.record()
+            if not capturing:
+                upd_done.record()
         else:
             backward(sb, algo)
         if ev is not None:
@@ -201,11 +207,30 @@ def main():
     # around the dominant backward kernel, on its launch stream
     upd_done.record()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i, red=red_ev[i] if red_ev is not None else None)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    if args.graph:
+        # one graph per distinct batch = one whole step (kernel launches only: the library allocates
+        # nothing, sets no memory and never synchronises); replays are what is timed
+        graphs = []
+        for bi in range(nb):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                step(bi, capturing=True)
+            graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(min(args.warmup, 2 * nb)):
+            graphs[i % nb].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % nb].replay()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i, red=red_ev[i] if red_ev is not None else None)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     hot.dlrm_profile_reduce_kernel(None, None)
     ids = [(args.warmup + i) % nb for i in range(args.steps)]
@@ -216,7 +241,10 @@ def main():
     nbk = min(args.steps, 100)
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(nbk)]
     for i in range(nbk):
-        step(args.warmup + i, ev=events[i], overlap=False)
+        # (with --graph the library's event pair cannot sit inside the replays: it is recorded here)
+        step(args.warmup + i, ev=events[i], overlap=False,
+             red=red_ev[i] if args.graph and red_ev is not None else None)
+    hot.dlrm_profile_reduce_kernel(None, None)
     torch.cuda.synchronize()
     stage_ms = {s: 0.0 for s in stages}
     for ev in events:
@@ -237,11 +265,12 @@ def main():
     # bucket_reduce kernel is timed by the library's event hook.
     red_ms = 0.0
     if red_ev is not None:
-        for a, b_ in red_ev:
+        n_red = nbk if args.graph else args.steps
+        for a, b_ in red_ev[:n_red]:
             ms = ctypes.c_float()
             assert hip.hipEventElapsedTime(ctypes.byref(ms), a, b_) == 0
             red_ms += ms.value
-        red_ms /= args.steps
+        red_ms /= n_red
     # algorithmic bytes of one bucket_reduce launch: the sorted (row, bag) pairs (8 B per lookup),
     # every pooled-vector gradient once, every touched row read and written once
     # (Adagrad: plus every touched row of the fp32 state read and written once)
@@ -272,7 +301,7 @@ def main():
                    "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
                    "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
                    "bwd_algo": args.algo, "optimizer": args.optimizer, "pooling": "weighted" if args.weighted else "sum",
-                   "indices": "int32" if args.index32 else "int64",
+                   "indices": "int32" if args.index32 else "int64", "launch": "hip graph replays" if args.graph else "eager",
                    "lr": w.lr,
                    "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),

@@ -596,6 +596,75 @@ def test_int32_indices_give_the_bits_of_int64_indices(case):
             assert rel_err(tables[k].cpu().numpy(), ref[k], scale[k]) <= 1e-5
 
 
+def test_a_captured_step_replays_to_the_eager_bits():
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a caller can
+    capture a whole step in a HIP graph.  Three replays, with eager work and synchronisations in
+    between, each against the eager step's bits (sort path: bitwise reproducible)."""
+    w = gen.custom_workload("graph", K=4, B=300, d=32, dtype=gen.F32, rows=20000, bag=("uniform", 0, 30),
+                            dist=("zipf", 1.2), seed=11)
+    b = gen.make_batch(w)
+    K, B, d, F, P = w.K, w.B, w.d, w.F, w.P
+    host = _host_tables(b)
+    x = torch.from_numpy(b.x).to(DEV)
+    dR = torch.from_numpy(b.dR).to(DEV)
+    lr = float(np.float32(w.lr))
+
+    def buffers():
+        return (torch.zeros((B, F, d), dtype=torch.float32, device=DEV),
+                torch.zeros((B, d + P), dtype=torch.float32, device=DEV),
+                torch.zeros((B, F, d), dtype=torch.float32, device=DEV))
+
+    def step(sb, ws, T, R, dT, side=None):
+        if side is not None:
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                hot.dlrm_emb_bag_bwd_prepare(sb, ws)
+        hot.dlrm_place_dense(x, T)
+        hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+        hot.dlrm_interact_dot_fwd(T, R)
+        hot.dlrm_interact_dot_bwd(T, dR, dT)
+        if side is not None:
+            torch.cuda.current_stream().wait_stream(side)
+            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+        else:
+            hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=hot.BWD_SORT, dS_offset=d)
+
+    # eager: three consecutive steps, the tables after each
+    tables_e = upload_tables(host, gen.F32)
+    sb_e = make_sparse_batch(b, tables_e)
+    ws_e = hot.alloc_workspace(sb_e)
+    Te, Re, dTe = buffers()
+    eager = []
+    for _ in range(3):
+        step(sb_e, ws_e, Te, Re, dTe)
+        torch.cuda.synchronize()
+        eager.append(([t.clone() for t in tables_e], Re.clone(), dTe.clone()))
+    # captured once, replayed three times on tables of its own
+    tables_g = upload_tables(host, gen.F32)
+    sb_g = make_sparse_batch(b, tables_g)
+    ws_g = hot.alloc_workspace(sb_g)
+    Tg, Rg, dTg = buffers()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(sb_g, ws_g, Tg, Rg, dTg, side=side)
+    torch.cuda.synchronize()
+    for t, h in zip(tables_g, host):        # the capture itself ran nothing
+        assert np.array_equal(t.cpu().numpy(), h)
+    for r in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        want_tables, want_R, want_dT = eager[r]
+        assert torch.equal(Rg, want_R) and torch.equal(dTg, want_dT), "replay %d" % r
+        for k in range(K):
+            assert torch.equal(tables_g[k], want_tables[k]), "replay %d table %d" % (r, k)
+        # the program's own eager work between replays
+        scratch = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+        hot.dlrm_emb_bag_fwd(sb_e, scratch, F * d, d, out_offset=d)
+        torch.cuda.synchronize()
+
+
 def test_backward_with_a_table_nobody_looks_up_and_lr_zero():
     lists = [[[1, 1, 3], [], [3]], [[], [], []], [[0], [0], [0]]]
     b = gen.batch_from_lists([8, 8, 8], lists, d=8)
