@@ -151,6 +151,21 @@ def interact_dot_fwd(T: np.ndarray) -> np.ndarray:
     return R
 
 
+def emb_interact_fwd(tables: Sequence[np.ndarray], dtype: int, indices, offsets, tbl_off,
+                     x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """The forward of the sparse side in one call (Sec. 2.2: the processed dense vector and the
+    pooled vectors of Eq. (2) are the F = K + 1 inputs of the dot interaction).
+    x float32 [B,d] -> (T float32 [B,F,d], R float64 [B, d + F(F-1)/2]); T[:,0] = x,
+    T[:,k+1] = the pooled vectors of table k rounded to fp32 (the type T is handed over in)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    S = emb_bag_fwd(tables, dtype, indices, offsets, tbl_off)
+    B, K, d = S.shape
+    T = np.empty((B, K + 1, d), dtype=np.float32)
+    T[:, 0] = x
+    T[:, 1:] = S.astype(np.float32)
+    return T, interact_dot_fwd(T)
+
+
 def interact_dot_bwd(T: np.ndarray, dR: np.ndarray) -> np.ndarray:
     """-> dT float64 [B,F,d]."""
     T = np.ascontiguousarray(T, dtype=np.float32)

@@ -211,6 +211,26 @@ def test_interaction_F2_closed_forms():
     np.testing.assert_allclose(dT[:, 1], g * T64[:, 0], rtol=1e-14, atol=1e-14)
 
 
+def test_pooled_interaction_is_the_gram_of_dense_AtW_and_x():
+    # the one-call forward against dense linear algebra: T_b = [x_b; (A_k^t W_k)_b], R = its Gram
+    rng = np.random.default_rng(61)
+    wl = gen.custom_workload("pi", K=3, B=5, d=8, rows=9, bag=("uniform", 0, 3))
+    batch = gen.make_batch(wl)
+    tables = _rand_tables(rng, batch.rows, wl.d)
+    x = rng.standard_normal((wl.B, wl.d)).astype(np.float32)
+    T, R = oracle.emb_interact_fwd(tables, gen.F32, batch.indices, batch.offsets, batch.tbl_off, x)
+    assert T.dtype == np.float32 and np.array_equal(T[:, 0].view(np.uint32), x.view(np.uint32))
+    il, jl = np.tril_indices(wl.K + 1, -1)
+    for b in range(wl.B):
+        rows = [x[b].astype(np.float64)]
+        for k in range(wl.K):
+            rows.append((_dense_A(batch, k, int(batch.rows[k])).T @ tables[k].astype(np.float64))[b])
+        V = np.stack(rows)
+        np.testing.assert_allclose(T[b], V, rtol=2e-7, atol=1e-7)
+        np.testing.assert_allclose(R[b, wl.d:], (V @ V.T)[il, jl], rtol=2e-6, atol=2e-6)
+        assert np.array_equal(R[b, :wl.d].astype(np.float32).view(np.uint32), x[b].view(np.uint32))
+
+
 def test_interaction_backward_matches_finite_differences():
     rng = np.random.default_rng(7)
     B, F, d = 3, 5, 6
