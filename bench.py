@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--index32", action="store_true", help="int32 index arrays instead of int64")
     ap.add_argument("--weighted", action="store_true",
                     help="per-lookup weights (Eq. (2) in full) instead of sum pooling; the metric is quoted without")
+    ap.add_argument("--split-fwd", action="store_true",
+                    help="forward as three calls (place_dense, emb_bag_fwd, interact_dot_fwd) even where the "
+                         "one-launch forward applies (short bags)")
     ap.add_argument("--graph", action="store_true",
                     help="capture each distinct batch's step in a HIP graph (through torch) and time replays")
     ap.add_argument("--no-overlap", action="store_true",
@@ -128,6 +131,10 @@ def main():
         state_ptrs = hot.state_pointers(state)
         eps = 1e-8
 
+    # the library's own rule for dlrm_emb_interact_fwd(DLRM_FWD_AUTO), spelled out so the line says which ran
+    fused_fwd = (not args.split_fwd and not args.weighted and K <= 64
+                 and sum(b.nnz for b in batches) / (len(batches) * K * B) <= 4.0)
+
     def backward(sb, algo_code):
         if adagrad:
             hot.dlrm_emb_bag_bwd_adagrad(sb, state_ptrs, dT, F * d, d, lr, eps, ws, algo=algo_code, dS_offset=d)
@@ -176,15 +183,18 @@ def main():
                 prep_done.record(side)
         if ev is not None:
             ev[0].record()
-        hot.dlrm_place_dense(x, T)
-        if ev is not None:
-            ev[1].record()
-        hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
-        if ev is not None:
-            ev[2].record()
-        hot.dlrm_interact_dot_fwd(T, R)
-        if ev is not None:
-            ev[3].record()
+        if fused_fwd and ev is None:
+            hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED)
+        else:
+            hot.dlrm_place_dense(x, T)
+            if ev is not None:
+                ev[1].record()
+            hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
+            if ev is not None:
+                ev[2].record()
+            hot.dlrm_interact_dot_fwd(T, R)
+            if ev is not None:
+                ev[3].record()
         hot.dlrm_interact_dot_bwd(T, dR, dT)
         if ev is not None:
             ev[4].record()
@@ -239,6 +249,7 @@ def main():
     # with an event on either side (grouping inside the backward call), same batches in the
     # same order.  Its sum is a little above the step time of an overlapped run.
     nbk = min(args.steps, 100)
+    step(args.warmup, ev=None if not fused_fwd else [torch.cuda.Event() for _ in range(6)], overlap=False)  # first use of the separate forward kernels is not timed
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(nbk)]
     for i in range(nbk):
         # (with --graph the library's event pair cannot sit inside the replays: it is recorded here)
@@ -252,6 +263,17 @@ def main():
             stage_ms[s] += ev[j].elapsed_time(ev[j + 1])
     for s in stages:
         stage_ms[s] /= nbk
+
+    fused_ms = None
+    if fused_fwd:  # the one-launch forward by itself, same batches
+        fe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nbk)]
+        for i in range(nbk):
+            sb, x, _ = dev_batches[(args.warmup + i) % nb]
+            fe[i][0].record()
+            hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED)
+            fe[i][1].record()
+        torch.cuda.synchronize()
+        fused_ms = sum(a.elapsed_time(b_) for a, b_ in fe) / nbk
 
     mean = lambda key: float(np.mean([abytes[i][key] for i in ids]))
     nnz_mean = mean("nnz")
@@ -303,12 +325,14 @@ def main():
                    "bwd_algo": args.algo, "optimizer": args.optimizer, "pooling": "weighted" if args.weighted else "sum",
                    "indices": "int32" if args.index32 else "int64", "launch": "hip graph replays" if args.graph else "eager",
                    "lr": w.lr,
+                   "forward": "one launch (emb_interact_fwd)" if fused_fwd else "place_dense, emb_bag_fwd, interact_dot_fwd",
                    "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
         "emb_fwd_bwd": {"ms": round(emb_ms, 5), "lookups_per_s": round(nnz_mean / (emb_ms * 1e-3), 1),
                         "algorithmic_GBps": round(emb_bytes / (emb_ms * 1e-3) / 1e9, 1),
                         "frac_of_hbm_peak": round(emb_bytes / (emb_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
+        "emb_interact_fwd_ms": None if fused_ms is None else round(fused_ms, 5),
         "stage_ms_source": "separate single-stream pass of %d steps after the timed region" % nbk,
         "stage_algorithmic_GBps": {
             "emb_bag_fwd": round(mean("fwd") / (stage_ms["emb_bag_fwd"] * 1e-3) / 1e9, 1),

@@ -33,7 +33,7 @@ extern "C" {
 #define DLRM_ERR_BAD_SHAPE (-2) /* K, B, d, F, strides, nnz or max_rows outside the supported range */
 #define DLRM_ERR_BAD_DTYPE (-3) /* unknown table dtype, or dtype not supported by the chosen algo */
 #define DLRM_ERR_WORKSPACE (-4) /* workspace NULL, misaligned or smaller than the query says */
-#define DLRM_ERR_BAD_ALGO (-5)  /* unknown backward algorithm */
+#define DLRM_ERR_BAD_ALGO (-5)  /* unknown algorithm, or one that cannot take this batch */
 #define DLRM_ERR_HIP (-6)       /* a HIP call / kernel launch failed */
 
 /* table storage types.  The paper uses fp32 parameters (Sec. 5); fp16/bf16
@@ -53,6 +53,11 @@ extern "C" {
 #define DLRM_BWD_SORT 1   /* group (row, bag) pairs by row, reduce, one update per row; deterministic */
 #define DLRM_BWD_ATOMIC 2 /* fp32 tables only: one hardware fp32 atomic add per looked-up element */
 #define DLRM_BWD_SORT_PREPARED 3 /* DLRM_BWD_SORT whose grouping dlrm_emb_bag_bwd_prepare already did */
+
+/* forward paths of dlrm_emb_interact_fwd */
+#define DLRM_FWD_AUTO 0  /* fused for short bags (mean <= 4 rows) without weights and K <= 64, else split */
+#define DLRM_FWD_FUSED 1 /* one launch: a wavefront pools a sample's K bags and multiplies them */
+#define DLRM_FWD_SPLIT 2 /* dlrm_place_dense, dlrm_emb_bag_fwd, dlrm_interact_dot_fwd in turn */
 
 /* supported ranges */
 #define DLRM_MAX_ROW_BYTES 1024         /* d * sizeof(element) <= 1024, multiple of 16 */
@@ -145,6 +150,22 @@ int32_t dlrm_place_dense(const float* x, int32_t B, int32_t d, float* T, int32_t
  */
 int32_t dlrm_interact_dot_fwd(const float* T, int32_t B, int32_t F, int32_t d, float* R,
                               void* stream);
+
+/*
+ * The forward of the sparse side in one call (Sec. 2.2: the processed dense vector and the
+ * pooled vectors of Eq. (2) are the F = K + 1 vectors the dot interaction pairs up):
+ *   T[b,0,:] = x[b,:];  T[b,k+1,:] = pooled vector of bag (k,b);  R = interaction of T
+ * with the values dlrm_place_dense, dlrm_emb_bag_fwd(out = T + d, stride_b = F*d,
+ * stride_k = d) and dlrm_interact_dot_fwd define; T is written because the backward reads it.
+ * x: [B,d] fp32, T: [B,F,d] fp32, R: [B, d + F(F-1)/2] fp32, all device, contiguous, x and T
+ * 16-byte aligned.  Requires K + 1 <= DLRM_MAX_INTERACT_F and d a multiple of 4.
+ * algo: DLRM_FWD_FUSED needs a batch without weights and K <= 64 (else DLRM_ERR_BAD_ALGO); it
+ * adds a bag's rows one by one in ascending position order (a one-index bag is an exact copy
+ * of its row), each lane walking one bag, so it is meant for bags of a few rows;
+ * DLRM_FWD_AUTO takes it up to a mean bag length of 4.  The paths differ in rounding order only.
+ */
+int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* batch, const float* x, float* T, float* R,
+                              int32_t algo, void* stream);
 
 /*
  * Backward of the above by the chain rule (the paper prints none).  With

@@ -15,6 +15,7 @@ from . import build as _build
 F32, F16, BF16 = 0, 1, 2
 I64, I32 = 0, 1
 BWD_AUTO, BWD_SORT, BWD_ATOMIC, BWD_SORT_PREPARED = 0, 1, 2, 3
+FWD_AUTO, FWD_FUSED, FWD_SPLIT = 0, 1, 2
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 _ELEM = {F32: 4, F16: 2, BF16: 2}
 
@@ -62,6 +63,8 @@ def lib() -> C.CDLL:
         L.dlrm_place_dense.argtypes = [vp, i32, i32, vp, i32, vp]
         L.dlrm_interact_dot_fwd.restype = i32
         L.dlrm_interact_dot_fwd.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.dlrm_emb_interact_fwd.restype = i32
+        L.dlrm_emb_interact_fwd.argtypes = [sb, vp, vp, vp, i32, vp]
         L.dlrm_interact_dot_bwd.restype = i32
         L.dlrm_interact_dot_bwd.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.dlrm_emb_bag_bwd_workspace_bytes.restype = sz
@@ -169,6 +172,12 @@ def dlrm_place_dense(x: torch.Tensor, T: torch.Tensor):
 def dlrm_interact_dot_fwd(T: torch.Tensor, R: torch.Tensor):
     B, F, d = T.shape
     _check("dlrm_interact_dot_fwd", lib().dlrm_interact_dot_fwd(_ptr(T), B, F, d, _ptr(R), _stream()))
+
+
+def dlrm_emb_interact_fwd(batch: SparseBatch, x: torch.Tensor, T: torch.Tensor, R: torch.Tensor,
+                          algo: int = FWD_AUTO):
+    _check("dlrm_emb_interact_fwd",
+           lib().dlrm_emb_interact_fwd(batch.ref(), _ptr(x), _ptr(T), _ptr(R), algo, _stream()))
 
 
 def dlrm_interact_dot_bwd(T: torch.Tensor, dR: torch.Tensor, dT: torch.Tensor):

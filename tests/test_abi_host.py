@@ -52,6 +52,22 @@ def test_forward_rejects_bad_arguments_on_the_host():
     assert L.dlrm_emb_bag_fwd(None, out, 64, 16, None) == -1
 
 
+def test_one_call_forward_rejects_bad_arguments_on_the_host():
+    L = hot.lib()
+    p = C.c_void_p(0x1000)
+    call = lambda b, x=p, T=p, R=p, algo=0: L.dlrm_emb_interact_fwd(C.byref(b), x, T, R, algo, None)
+    assert call(_batch(tables=None)) == -1
+    assert call(_batch(), x=None) == -1
+    assert call(_batch(), T=None) == -1
+    assert call(_batch(), R=None) == -1
+    assert call(_batch(K=128)) == -2                  # F = 129 vectors
+    assert call(_batch(), x=C.c_void_p(0x1004)) == -2
+    assert call(_batch(), T=C.c_void_p(0x1008)) == -2
+    assert call(_batch(), algo=3) == -5
+    assert call(_batch(K=65), algo=1) == -5           # the one-launch kernel takes up to 64 tables
+    assert call(_batch(weights=0x1000), algo=1) == -5  # and no pooling weights
+
+
 def test_unknown_index_dtype_is_rejected():
     L = hot.lib()
     # (no output pointer: a known index type gets as far as that check, nothing is launched)

@@ -162,6 +162,88 @@ def test_interact_dot_fwd_bwd_match_oracle(B, F, d):
     assert rel_err(dT.cpu().numpy(), oracle.interact_dot_bwd(T, dR), scale_interact_bwd(T, dR)) <= 1e-5
 
 
+# ------------------------------------------------------------------ pooled lookup + interaction in one call
+PI_CASES = [
+    # name, K, B, d, dtype, rows, bag, dist, index32
+    ("tiny-shape", 8, 128, 16, gen.F32, 1000, ("uniform", 1, 4), ("uniform",), False),
+    ("onehot-26x16", 26, 300, 16, gen.F32, 500, ("fixed", 1), ("zipf", 1.05), False),
+    ("onehot-26x128", 26, 131, 128, gen.F32, 3000, ("fixed", 1), ("zipf", 1.05), True),
+    ("k16-d20", 16, 45, 20, gen.F32, 90, ("uniform", 0, 3), ("uniform",), False),
+    ("k17-d12", 17, 33, 12, gen.F32, 90, ("uniform", 0, 3), ("uniform",), False),
+    ("k33-f16-d40", 33, 21, 40, gen.F16, 70, ("uniform", 0, 4), ("uniform",), False),
+    ("k64-bf16-d8", 64, 18, 8, gen.BF16, 70, ("uniform", 0, 2), ("uniform",), True),
+    ("k48-d256", 48, 9, 256, gen.F32, 40, ("fixed", 1), ("uniform",), False),
+    ("k1-b1-d4", 1, 1, 4, gen.F32, 3, ("fixed", 2), ("uniform",), False),
+    ("mostly-empty", 5, 66, 32, gen.F32, 30, ("uniform", 0, 1), ("uniform",), False),
+    ("long-bags-forced", 3, 20, 64, gen.F32, 400, ("uniform", 0, 40), ("uniform",), False),
+]
+
+
+@pytest.mark.parametrize("case", PI_CASES, ids=[c[0] for c in PI_CASES])
+def test_emb_interact_fwd_fused_matches_oracle_and_the_separate_calls(case):
+    name, K, B, d, dtype, rows, bag, dist, index32 = case
+    _say("emb_interact_fwd " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=5)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    sb = make_sparse_batch(b, tables, index32=index32)
+    F, P = K + 1, (K + 1) * K // 2
+    x = np.random.default_rng(K * 100 + d).standard_normal((B, d)).astype(np.float32)
+    xd = torch.from_numpy(x).to(DEV)
+    got = {}
+    for algo in (hot.FWD_FUSED, hot.FWD_SPLIT, hot.FWD_AUTO):
+        T = torch.full((B, F, d), 123.0, dtype=torch.float32, device=DEV)
+        R = torch.full((B, d + P), -5.0, dtype=torch.float32, device=DEV)
+        hot.dlrm_emb_interact_fwd(sb, xd, T, R, algo)
+        torch.cuda.synchronize()
+        got[algo] = (T.cpu().numpy(), R.cpu().numpy())
+    wantT, wantR = oracle.emb_interact_fwd(host, dtype, b.indices, b.offsets, b.tbl_off, x)
+    scaleT = scale_emb_fwd(host, dtype, b.indices, b.offsets, b.tbl_off)
+    for algo, (T, R) in got.items():
+        assert np.array_equal(T[:, 0].view(np.uint32), x.view(np.uint32))          # the dense vector, bit for bit
+        assert np.array_equal(R[:, :d].view(np.uint32), x.view(np.uint32))
+        assert rel_err(T[:, 1:], wantT[:, 1:].astype(np.float64), scaleT) <= 1e-5
+        # the pairs are products of the fp32 T this path wrote
+        assert rel_err(R, oracle.interact_dot_fwd(T), scale_interact_fwd(T)) <= 1e-5
+        assert rel_err(R, wantR, scale_interact_fwd(scaleT_pad(scaleT, x))) <= 1e-5
+    if bag[-1] <= 4:   # short bags: both paths add a bag's rows one by one in position order
+        assert np.array_equal(got[hot.FWD_FUSED][0].view(np.uint32), got[hot.FWD_SPLIT][0].view(np.uint32))
+    for k, bb in np.argwhere(b.lengths == 0):
+        assert np.all(got[hot.FWD_FUSED][0][bb, k + 1].view(np.uint32) == 0)     # +0.0 exactly
+
+
+def scaleT_pad(scaleT, x):
+    """|x| and the pooled magnitude scales laid out like T."""
+    return np.concatenate([np.abs(x)[:, None, :].astype(np.float64), scaleT], axis=1).astype(np.float32)
+
+
+def test_emb_interact_fwd_fused_refuses_what_it_cannot_do_and_auto_takes_the_separate_calls():
+    _say("emb_interact_fwd refusals")
+    for K, weighted in ((65, False), (4, True)):
+        w = gen.custom_workload("r", K=K, B=6, d=8, rows=20, bag=("uniform", 0, 3), seed=2)
+        b = gen.make_batch(w)
+        host = _host_tables(b)
+        tables = upload_tables(host, gen.F32)
+        wts = gen.make_weights(b, seed=1) if weighted else None
+        sb = make_sparse_batch(b, tables, weights=wts)
+        F, P = K + 1, (K + 1) * K // 2
+        x = np.random.default_rng(K).standard_normal((6, 8)).astype(np.float32)
+        xd = torch.from_numpy(x).to(DEV)
+        T = torch.empty((6, F, 8), dtype=torch.float32, device=DEV)
+        R = torch.empty((6, 8 + P), dtype=torch.float32, device=DEV)
+        with pytest.raises(hot.DlrmError):
+            hot.dlrm_emb_interact_fwd(sb, xd, T, R, hot.FWD_FUSED)
+        hot.dlrm_emb_interact_fwd(sb, xd, T, R, hot.FWD_AUTO)
+        torch.cuda.synchronize()
+        if weighted:
+            S = oracle.emb_bag_fwd_weighted(host, gen.F32, b.indices, b.offsets, b.tbl_off, wts)
+        else:
+            S = oracle.emb_bag_fwd(host, gen.F32, b.indices, b.offsets, b.tbl_off)
+        Tw = np.concatenate([x[:, None, :], S.astype(np.float32)], axis=1)
+        assert rel_err(R.cpu().numpy(), oracle.interact_dot_fwd(Tw), scale_interact_fwd(Tw) + 1e-30) <= 2e-5
+
+
 def test_place_dense_is_an_exact_copy():
     rng = np.random.default_rng(1)
     B, F, d = 333, 9, 64
