@@ -47,6 +47,9 @@ def _check_config(cfg_id, algo=hot.BWD_AUTO, sample_untouched=20000):
     hot.dlrm_place_dense(torch.from_numpy(b.x).to(DEV), T)
     hot.dlrm_emb_bag_fwd(sb, T, F * d, d, out_offset=d)
     hot.dlrm_interact_dot_fwd(T, R)
+    # a2 + a3 + a4 as one call, as bench.py issues them (one launch where the bags are short)
+    T1, R1 = torch.empty_like(T), torch.empty_like(R)
+    hot.dlrm_emb_interact_fwd(sb, torch.from_numpy(b.x).to(DEV), T1, R1)
     _say("backward")
     hot.dlrm_interact_dot_bwd(T, dR, dT)
     hot.dlrm_emb_bag_bwd_sgd(sb, dT, F * d, d, lr, ws, algo=algo, dS_offset=d)
@@ -71,7 +74,12 @@ def _check_config(cfg_id, algo=hot.BWD_AUTO, sample_untouched=20000):
     _say("interact fwd rel err %.2e" % e)
     assert e <= 1e-5
     assert np.array_equal(R_h[:, :d].view(np.uint32), b.x.view(np.uint32))
-    del R_ref, R_h
+    # the one-call forward
+    assert torch.equal(T1.view(torch.int32), T.view(torch.int32))       # same sums in the same order
+    e = rel_err(R1.cpu().numpy(), R_ref, scale_interact_fwd(T_h))
+    _say("one-call forward rel err %.2e" % e)
+    assert e <= 1e-5
+    del R_ref, R_h, T1, R1
     # a5: interaction backward
     dT_h = dT.cpu().numpy()
     dT_ref = oracle.interact_dot_bwd(T_h, b.dR)
