@@ -53,6 +53,7 @@ constexpr int kSortBuckets = 1 << kSortBits;
 constexpr int kBktItems = 8;                    // positions per thread in a bucket-sort tile
 constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size are sorted in LDS
 constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
+constexpr int kLongRunMin = 16;                 // ... 16 where a workgroup has >= 32 lane groups
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
 constexpr int kHotTileFloats = 16384;            // 64 KB of LDS: gradient rows of one bag tile
 constexpr int kHotZeroRow = 256;                // floats of the widest gradient row

@@ -25,6 +25,13 @@ __device__ inline Entry entry_of(const GroupArgs& a, int64_t tbl, uint32_t val) 
   return e;
 }
 
+// Runs longer than this are summed by the whole workgroup.  With many lane groups per workgroup
+// (narrow rows) a medium run left to one lane group is the critical path of the bucket sooner.
+template <int G>
+__device__ constexpr uint32_t long_run() {
+  return kThreads / G >= 32 ? (uint32_t)kLongRunMin : (uint32_t)kLongRun;
+}
+
 // Sum (weight times) dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from
 // i0 + first; U loads in flight, ascending order.  vals: LDS or global.  tbl: start of the table
 // in the batch's index array.
@@ -101,13 +108,13 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
 #pragma unroll
     for (int t = 0; t < RU; ++t) {
       const uint32_t len = i1[t] - i0[t];
-      if (r0 + t >= nruns || len > (uint32_t)kLongRun) continue;
+      if (r0 + t >= nruns || len > long_run<G>()) continue;
       if (len > 1) acc[t] += sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
       if (col_ok) row_update_store<DT, OPT>(wp[t], wv[t], acc[t], u);
     }
   }
   // long runs: the whole workgroup per run, lane group s taking entries s, s+NG, ...; the NG
-  // partial sums are added in group order
+  // partial sums are added in group order (in two levels of fixed shape when NG > 16)
   for (uint32_t q = 0; q < nlong; ++q) {  // uniform
     const uint32_t r = longs[q];
     const uint32_t i0 = heads[r] - h0, i1 = heads[r + 1] - h0;
@@ -125,15 +132,30 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
       }
       continue;
     }
+    // the row is requested first: its latency hides behind the gather
+    const bool upd = grp == 0 && col_ok;
+    RowRef wr = row_ref<DT, OPT>(W, H, u.d, keys[i0], cchunk);
+    RowVal wv{};
+    if (upd) wv = row_load<DT, OPT>(wr);
     const f32x4 acc = sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
     __syncthreads();
     if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
     __syncthreads();
-    if (grp == 0 && col_ok) {
+    constexpr int L1 = NG > 16 ? 8 : 1;  // many lane groups: sums of L1 consecutive partials first
+    if constexpr (L1 > 1) {
+      if (grp < NG / L1 && col_ok) {
+        f32x4 t = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int s = 0; s < L1; ++s) t += loadf4(part + (grp * L1 + s) * (G * 4) + chunk * 4);
+        storef4(part + grp * L1 * (G * 4) + chunk * 4, t);  // a slot only this lane reads above
+      }
+      __syncthreads();
+    }
+    if (upd) {
       f32x4 tot = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-      for (int s = 0; s < NG; ++s) tot += loadf4(part + s * (G * 4) + chunk * 4);
-      row_update<DT, OPT>(W, H, u, keys[i0], chunk, tot);
+      for (int s = 0; s < NG / L1; ++s) tot += loadf4(part + s * L1 * (G * 4) + chunk * 4);
+      row_update_store<DT, OPT>(wr, wv, tot, u);
     }
   }
 }
@@ -162,13 +184,14 @@ __device__ inline uint32_t compact_heads_lds(SortLds& s, int n) {
   return total;
 }
 
-// Lists the runs longer than kLongRun among s.heads[0..nruns] (any order: each is a different
-// row).  At most kBktCap/kLongRun + 1 of them have their head inside a window of kBktCap positions.
-__device__ inline uint32_t collect_long_runs(SortLds& s, uint32_t nruns) {
+// Lists the runs longer than `longer_than` (>= kLongRunMin) among s.heads[0..nruns] (any order: each is a
+// different row).  At most kBktCap/kLongRunMin + 1 of them have their head inside a window of kBktCap
+// positions.
+__device__ inline uint32_t collect_long_runs(SortLds& s, uint32_t nruns, uint32_t longer_than) {
   if (threadIdx.x == 0) s.nlong = 0;
   __syncthreads();
   for (uint32_t r = threadIdx.x; r < nruns; r += kThreads) {
-    if (s.heads[r + 1] - s.heads[r] > (uint32_t)kLongRun) s.longs[atomicAdd(&s.nlong, 1u)] = r;
+    if (s.heads[r + 1] - s.heads[r] > longer_than) s.longs[atomicAdd(&s.nlong, 1u)] = r;
   }
   __syncthreads();
   return s.nlong;
@@ -219,7 +242,7 @@ __device__ inline void reduce_window(const GroupArgs& a, const UpdArgs& u, const
     const uint32_t e = run_end_search(keys, w0 + (uint32_t)cnt, b.n, keys[s.heads[total - 1]]);
     if (tid == 0) s.heads[total] = e;
     __syncthreads();
-    const uint32_t nlong = collect_long_runs(s, total);
+    const uint32_t nlong = collect_long_runs(s, total, long_run<G>());
     reduce_runs<DT, G, OPT, WT>(a, u, b, W, keys, bags, s.heads, 0u, total, s.longs, nlong, src, part);
   }
   __syncthreads();
@@ -441,7 +464,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   __syncthreads();
   // ---- candidate lists are runs: short ones summed here, those above kHugeRun queued as hot rows
   {
-    const uint32_t nlong = collect_long_runs(s, nc);
+    const uint32_t nlong = collect_long_runs(s, nc, long_run<G>());
     reduce_runs<DT, G, OPT, WT>(a, u, b, W, kout, vout, s.heads, 0u, nc, s.longs, nlong, 0, part);
   }
   // ---- the rest
@@ -456,7 +479,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
   }
   sort_bucket_lds(a, rest, s, 0);
   const uint32_t nruns = compact_heads_lds(s, (int)rest.n);
-  const uint32_t nlong = collect_long_runs(s, nruns);
+  const uint32_t nlong = collect_long_runs(s, nruns, long_run<G>());
   reduce_runs<DT, G, OPT, WT>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
 }
 
@@ -474,7 +497,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
   if (b.n <= (uint32_t)kBktCap) {
     sort_bucket_lds(a, b, s);
     const uint32_t nruns = compact_heads_lds(s, (int)b.n);
-    const uint32_t nlong = collect_long_runs(s, nruns);
+    const uint32_t nlong = collect_long_runs(s, nruns, long_run<G>());
     reduce_runs<DT, G, OPT, WT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
     return;
   }
@@ -484,7 +507,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
       s.heads[1] = b.n;
     }
     __syncthreads();
-    const uint32_t nlong = collect_long_runs(s, 1);
+    const uint32_t nlong = collect_long_runs(s, 1, long_run<G>());
     reduce_runs<DT, G, OPT, WT>(a, u, b, W, a.keys[1] + b.start, a.vals[1] + b.start, s.heads, 0u, 1, s.longs, nlong, 1,
                        part);
     return;

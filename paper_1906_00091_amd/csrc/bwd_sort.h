@@ -50,7 +50,7 @@ struct SortLds {
   uint32_t heads[kBktCap + 1];
   uint32_t base[kSortBuckets];
   uint32_t smem[kNW + 1];
-  uint32_t longs[kBktCap / kLongRun + 2];   // runs longer than kLongRun among the current heads
+  uint32_t longs[kBktCap / kLongRunMin + 2];   // runs longer than the threshold among the current heads
   uint32_t nlong;
 };
 

@@ -29,7 +29,25 @@ struct FwdArgs {
   int64_t stride_b, stride_k;
   int32_t K, B, d;
   int32_t chunks;  // 16-byte chunks per table row
+  // optional rider: workgroups past bag_blocks copy the dense vectors x[B,d] to dense_out + b*stride_b
+  // (row 0 of the interaction input), which saves the launch of its own that copy would take
+  const float* dense;
+  float* dense_out;
+  uint32_t bag_blocks;
 };
+
+// true for the rider workgroups, after they have done their copy
+__device__ inline bool dense_rider(const FwdArgs& a) {
+  if (a.dense == nullptr || blockIdx.x < a.bag_blocks) return false;
+  const int d4 = a.d / 4;
+  const int64_t n4 = (int64_t)a.B * d4;
+  const int64_t nthreads = (int64_t)(gridDim.x - a.bag_blocks) * blockDim.x;
+  for (int64_t i = (int64_t)(blockIdx.x - a.bag_blocks) * blockDim.x + threadIdx.x; i < n4; i += nthreads) {
+    const int64_t b = i / d4, c4 = i - b * d4;
+    storef4(a.dense_out + b * a.stride_b + c4 * 4, loadf4(a.dense + i * 4));
+  }
+  return true;
+}
 
 template <int DT>
 __device__ inline void write_pooled(float* o, const float* acc) {
@@ -41,6 +59,7 @@ __device__ inline void write_pooled(float* o, const float* acc) {
 // ---------------------------------------------------------------------------
 template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
+  if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
   const int lane = lane_id();
@@ -102,6 +121,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
 // NB consecutive bags and walks their chains side by side.
 template <int DT, int G, int NB, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
+  if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
   const int lane = lane_id();
@@ -168,6 +188,7 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
 // ---------------------------------------------------------------------------
 template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
+  if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
   const int lane = lane_id();
@@ -241,20 +262,28 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
 constexpr int kShortBags = 4;  // bags per lane group of the short-bag kernel
 
 template <int DT, int G, bool WT, typename IT>
-static int launch_fwd(const FwdArgs& a, int mode, hipStream_t st) {
+static int launch_fwd(const FwdArgs& a_in, int mode, hipStream_t st) {
   constexpr int S = DLRM_WAVE / G;
-  const int64_t bags = (int64_t)a.K * a.B;
+  const int64_t bags = (int64_t)a_in.K * a_in.B;
   const bool wave_mode = mode == 2;
+  FwdArgs a = a_in;
+  unsigned riders = 0;
+  if (a.dense != nullptr) {
+    riders = div_up((int64_t)a.B * (a.d / 4), 256);
+    if (riders > 1024) riders = 1024;
+  }
   if (mode == 0) {
-    const unsigned grid = div_up(bags, 4 * S * kShortBags);
-    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT, IT>), dim3(grid), dim3(256), 0, st, a);
+    a.bag_blocks = div_up(bags, 4 * S * kShortBags);
+    hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0,
+                       st, a);
   } else if (wave_mode) {
     // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
-    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT, IT>), dim3(div_up(bags, 4)), dim3(256), 0, st, a);
+    a.bag_blocks = div_up(bags, 4);
+    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a);
   } else {
-    const unsigned grid = div_up(bags, 4 * S);
-    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT, IT>), dim3(grid), dim3(256), 0, st, a);
+    a.bag_blocks = div_up(bags, 4 * S);
+    hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a);
   }
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
@@ -285,9 +314,11 @@ int check_batch(const dlrm_sparse_batch* s);  // util.hip
 
 }  // namespace dlrm
 
-extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int64_t stride_b,
-                                    int64_t stride_k, void* stream) {
-  using namespace dlrm;
+namespace dlrm {
+// The pooled lookup; with x != NULL the same launch also copies x[B,d] to out - d + b*stride_b
+// (the dense vector into row 0 of an interaction input whose rows 1..K are `out`).
+int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, int64_t stride_k, const float* x,
+                    void* stream) {
   int st = check_batch(s);
   if (st != DLRM_OK) return st;
   if (!out) return DLRM_ERR_NULL;
@@ -306,6 +337,9 @@ extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int6
   a.B = s->B;
   a.d = s->d;
   a.chunks = s->d * elem_bytes(s->table_dtype) / 16;
+  a.dense = x;
+  a.dense_out = x ? out - s->d : nullptr;
+  a.bag_blocks = 0;
   const int G = pow2_ceil(a.chunks);
   const int S = DLRM_WAVE / G;
   // a wavefront per bag pays off once a bag keeps all S lane groups busy for a few rounds
@@ -320,4 +354,10 @@ extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int6
     case DLRM_BF16: return dispatch_g<DLRM_BF16>(a, G, idx32, wave_mode, hs);
   }
   return DLRM_ERR_BAD_DTYPE;
+}
+}  // namespace dlrm
+
+extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int64_t stride_b,
+                                    int64_t stride_k, void* stream) {
+  return dlrm::emb_fwd_enqueue(s, out, stride_b, stride_k, nullptr, stream);
 }

@@ -213,6 +213,8 @@ static int dispatch_it(const PiArgs& a, bool idx32, hipStream_t st) {
 }
 
 int check_batch(const dlrm_sparse_batch* s);  // util.hip
+int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, int64_t stride_k, const float* x,
+                    void* stream);            // emb_fwd.hip
 
 }  // namespace dlrm
 
@@ -233,9 +235,8 @@ extern "C" int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* s, const float
     algo = can_fuse && mean_len <= kPiMaxMeanBag ? DLRM_FWD_FUSED : DLRM_FWD_SPLIT;
   }
   if (algo == DLRM_FWD_SPLIT) {
-    st = dlrm_place_dense(x, s->B, s->d, T, F, stream);
-    if (st != DLRM_OK) return st;
-    st = dlrm_emb_bag_fwd(s, T + s->d, (int64_t)F * s->d, s->d, stream);
+    // the dense vectors ride along in the pooling launch
+    st = emb_fwd_enqueue(s, T + s->d, (int64_t)F * s->d, s->d, x, stream);
     if (st != DLRM_OK) return st;
     return dlrm_interact_dot_fwd(T, s->B, F, s->d, R, stream);
   }
