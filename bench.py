@@ -46,6 +46,9 @@ def parse_args():
                     help="the library's event pair around the dominant kernel is recorded on every N-th timed step")
     ap.add_argument("--graph", action="store_true",
                     help="capture each distinct batch's step in a HIP graph (through torch) and time replays")
+    ap.add_argument("--no-flat", action="store_true",
+                    help="always enqueue the segment / hot-row launches of the backward, instead of reading the "
+                         "prepared batch's count of oversized row groups on the host and leaving them out at zero")
     ap.add_argument("--no-overlap", action="store_true",
                     help="group the (row, bag) pairs inside the backward call instead of on a second "
                          "stream beside the forward pass")
@@ -137,7 +140,7 @@ def main():
     fused_fwd = (not args.split_fwd and not args.weighted and K <= 64
                  and sum(b.nnz for b in batches) / (len(batches) * K * B) <= 4.0)
 
-    def backward(sb, algo_code):
+    def backward(sb, algo_code, ws=ws):
         if adagrad:
             hot.dlrm_emb_bag_bwd_adagrad(sb, state_ptrs, dT, F * d, d, lr, eps, ws, algo=algo_code, dS_offset=d)
         else:
@@ -152,6 +155,25 @@ def main():
     side = torch.cuda.Stream() if overlap else None     # default priority
     prep_done = torch.cuda.Event()
     upd_done = torch.cuda.Event()
+    use_flat = overlap and not args.no_flat and not args.graph
+    # With the count in use the grouping runs one step ahead, in the other of two workspaces (the indices
+    # of the next batch are there early, Sec. 4.1), so that the host never waits for it.
+    ws2 = [ws, torch.empty_like(ws)] if use_flat else [ws]
+    n_over = torch.zeros(2, dtype=torch.int32).pin_memory()   # written by the device, read by the host
+    n_over_np = n_over.numpy()
+    prep_done2 = [torch.cuda.Event(), torch.cuda.Event()]
+    upd_done2 = [torch.cuda.Event(), torch.cuda.Event()]
+
+    def prepare_ahead(i):
+        """Grouping of step i's batch on the side stream, in workspace i % 2, with its oversized count."""
+        p = i % 2
+        side.wait_event(upd_done2[p])   # step i - 2 is done with this workspace
+        n_over_np[p] = -1
+        with torch.cuda.stream(side):
+            hot.dlrm_emb_bag_bwd_prepare(dev_batches[i % nb][0], ws2[p])
+            hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[i % nb][0], ws2[p], n_over, index=p)
+            prep_done2[p].record(side)
+    flat_steps = [0]
 
     if args.copy_calib:  # 2^22 x 64 fp32 = 1 GiB read + 1 GiB written by a plain copy kernel
         src = torch.empty((1 << 22, 64), dtype=torch.float32, device=dev).normal_()
@@ -175,7 +197,8 @@ def main():
 
     def step(i, ev=None, red=None, overlap=overlap, capturing=False):
         sb, x, dR = dev_batches[i % nb]
-        if overlap:
+        ahead = overlap and mode["ahead"] and not capturing and ev is None
+        if overlap and not ahead:
             if capturing:  # inside a graph the second stream forks from the capturing one
                 side.wait_stream(torch.cuda.current_stream())
             else:
@@ -205,7 +228,19 @@ def main():
             hot.dlrm_profile_reduce_kernel(red[0], red[1])
         elif red_ev is not None and not capturing:
             hot.dlrm_profile_reduce_kernel(None, None)
-        if overlap:
+        if ahead:
+            p = i % 2
+            while n_over_np[p] < 0:   # pinned memory the device wrote a step ago: no driver call, no sleep
+                pass
+            code = hot.BWD_SORT_PREPARED
+            if n_over_np[p] == 0:
+                code = hot.BWD_SORT_PREPARED_FLAT
+                flat_steps[0] += 1
+            torch.cuda.current_stream().wait_event(prep_done2[p])
+            backward(sb, code, ws2[p])
+            upd_done2[p].record()
+            prepare_ahead(i + 1)
+        elif overlap:
             torch.cuda.current_stream().wait_event(prep_done)
             backward(sb, hot.BWD_SORT_PREPARED)
             if not capturing:
@@ -215,8 +250,16 @@ def main():
         if ev is not None:
             ev[5].record()
 
+    mode = {"ahead": use_flat}
+    if use_flat:
+        prepare_ahead(0)
     for i in range(args.warmup):
         step(i)
+    if use_flat and flat_steps[0] == 0:
+        # every warm-up batch had oversized row groups (heavy hitters): the count buys nothing, and the
+        # grouping overlaps better with the forward pass of its own step than with the previous update
+        mode["ahead"] = False
+    flat_before = flat_steps[0]
     torch.cuda.synchronize()
     # ---- timed region: exactly --steps steps; the only events inside are the library's pair
     # around the dominant backward kernel, on its launch stream
@@ -337,7 +380,11 @@ def main():
                    "forward": ("emb_interact_fwd, one launch" if fused_fwd else
                                "place_dense, emb_bag_fwd, interact_dot_fwd" if args.split_fwd else
                                "emb_interact_fwd, two launches (pooling with the dense copy, interaction)"),
-                   "grouping": "second stream, beside the forward pass" if overlap else "inside the backward call"},
+                   "grouping": ("second stream, one step ahead (two workspaces)" if mode["ahead"] else
+                                "second stream, beside the forward pass" if overlap else "inside the backward call"),
+                   "backward_tail": ("left out on steps whose prepared batch reports no oversized row group "
+                                     "(%d of the %d timed steps)" % (flat_steps[0] - flat_before, args.steps))
+                                    if mode["ahead"] else "always enqueued"},
         "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
         "emb_fwd_bwd": {"ms": round(emb_ms, 5), "lookups_per_s": round(nnz_mean / (emb_ms * 1e-3), 1),
                         "algorithmic_GBps": round(emb_bytes / (emb_ms * 1e-3) / 1e9, 1),

@@ -53,6 +53,8 @@ extern "C" {
 #define DLRM_BWD_SORT 1   /* group (row, bag) pairs by row, reduce, one update per row; deterministic */
 #define DLRM_BWD_ATOMIC 2 /* fp32 tables only: one hardware fp32 atomic add per looked-up element */
 #define DLRM_BWD_SORT_PREPARED 3 /* DLRM_BWD_SORT whose grouping dlrm_emb_bag_bwd_prepare already did */
+#define DLRM_BWD_SORT_PREPARED_FLAT 4 /* ... for a prepared batch without oversized buckets: the reduce launch
+                                         alone (see dlrm_emb_bag_bwd_prepared_oversized) */
 
 /* forward paths of dlrm_emb_interact_fwd */
 #define DLRM_FWD_AUTO 0  /* fused for short bags (mean <= 4 rows) without weights and K <= 64, else split */
@@ -215,8 +217,8 @@ int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, in
  * [rows[k], d], 16-byte aligned, owned and initialised by the caller (zeros for a fresh
  * optimizer), updated in place.  Rows that are not looked up keep W and h bit for bit.
  * Arithmetic is fp32; fp16/bf16 tables are widened, updated and rounded once.
- * eps must be > 0 (else DLRM_ERR_BAD_SHAPE).  algo: DLRM_BWD_AUTO, DLRM_BWD_SORT or
- * DLRM_BWD_SORT_PREPARED (else DLRM_ERR_BAD_ALGO); bitwise reproducible.  Everything else
+ * eps must be > 0 (else DLRM_ERR_BAD_SHAPE).  algo: DLRM_BWD_AUTO, DLRM_BWD_SORT,
+ * DLRM_BWD_SORT_PREPARED or DLRM_BWD_SORT_PREPARED_FLAT (else DLRM_ERR_BAD_ALGO); bitwise reproducible.  Everything else
  * as for dlrm_emb_bag_bwd_sgd.
  */
 int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* batch, void* const* state, const float* dS,
@@ -238,6 +240,23 @@ int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* batch, void* const* st
  */
 int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* batch, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/*
+ * After dlrm_emb_bag_bwd_prepare (same batch, same workspace, same stream or ordered after
+ * it): writes to *n_oversized the number of row groups of the batch that are too large for
+ * one workgroup's sort in LDS (more than 2048 lookups falling into one of the row ranges the
+ * grouping cuts a table into: heavy-hitter rows, or tables much smaller than the batch).
+ * n_oversized: one uint32 the device can write, e.g. pinned host memory, which the caller
+ * reads once the stream has passed this call.
+ * Zero means the update needs none of its segment / hot-row launches (four launches that
+ * would find nothing to do): DLRM_BWD_SORT_PREPARED_FLAT then enqueues the reduce kernel
+ * alone and gives the same bits as DLRM_BWD_SORT_PREPARED.  With oversized groups FLAT is
+ * still correct, but each is handled by a single workgroup (slow for heavy hitters) and long
+ * runs are summed in another order; a caller that picks FLAT exactly when the count is zero
+ * keeps results a function of the batch alone.
+ */
+int32_t dlrm_emb_bag_bwd_prepared_oversized(const dlrm_sparse_batch* batch, void* workspace,
+                                            size_t workspace_bytes, uint32_t* n_oversized, void* stream);
 
 /*
  * Runs only the grouping stage of DLRM_BWD_SORT and exports it in canonical

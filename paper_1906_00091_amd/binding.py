@@ -14,7 +14,7 @@ from . import build as _build
 
 F32, F16, BF16 = 0, 1, 2
 I64, I32 = 0, 1
-BWD_AUTO, BWD_SORT, BWD_ATOMIC, BWD_SORT_PREPARED = 0, 1, 2, 3
+BWD_AUTO, BWD_SORT, BWD_ATOMIC, BWD_SORT_PREPARED, BWD_SORT_PREPARED_FLAT = 0, 1, 2, 3, 4
 FWD_AUTO, FWD_FUSED, FWD_SPLIT = 0, 1, 2
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 _ELEM = {F32: 4, F16: 2, BF16: 2}
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_adagrad.argtypes = [sb, vp, vp, i64, i64, f32, f32, vp, sz, i32, vp]
         L.dlrm_emb_bag_bwd_prepare.restype = i32
         L.dlrm_emb_bag_bwd_prepare.argtypes = [sb, vp, sz, vp]
+        L.dlrm_emb_bag_bwd_prepared_oversized.restype = i32
+        L.dlrm_emb_bag_bwd_prepared_oversized.argtypes = [sb, vp, sz, vp, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
         L.dlrm_emb_bag_bwd_export_groups.argtypes = [sb, vp, sz, vp, vp, vp, vp, vp]
         L.dlrm_profile_reduce_kernel.restype = i32
@@ -223,6 +225,17 @@ def dlrm_emb_bag_bwd_prepare(batch: SparseBatch, workspace: torch.Tensor):
     ws_bytes = workspace.numel() * workspace.element_size()
     _check("dlrm_emb_bag_bwd_prepare",
            lib().dlrm_emb_bag_bwd_prepare(batch.ref(), _ptr(workspace), ws_bytes, _stream()))
+
+
+def dlrm_emb_bag_bwd_prepared_oversized(batch: SparseBatch, workspace: torch.Tensor, out: torch.Tensor,
+                                        index: int = 0):
+    """out: int32 tensor the device can write (device memory, or host memory allocated pinned);
+    element `index` receives the count once the stream has passed this call."""
+    assert out.dtype == torch.int32 and (out.is_cuda or out.is_pinned()) and 0 <= index < out.numel()
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check("dlrm_emb_bag_bwd_prepared_oversized",
+           lib().dlrm_emb_bag_bwd_prepared_oversized(batch.ref(), _ptr(workspace), ws_bytes,
+                                                     _ptr(out) + 4 * index, _stream()))
 
 
 def dlrm_emb_bag_bwd_export_groups(batch: SparseBatch, workspace: torch.Tensor,

@@ -52,9 +52,12 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
 
 // The sort path behind both optimizers' entry points: grouping (unless prepared), then the
 // reduce launches with the row update OPT.
+__global__ void copy_u32_kernel(const uint32_t* src, uint32_t* dst) { *dst = src ? *src : 0u; }
+
 template <int OPT>
 static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* workspace, size_t workspace_bytes,
-                         bool prepared, hipStream_t hs) {
+                         int algo, hipStream_t hs) {
+  const bool prepared = algo == DLRM_BWD_SORT_PREPARED || algo == DLRM_BWD_SORT_PREPARED_FLAT;
   const int G = pow2_ceil(s->d / 4);  // lanes per fp32 gradient row
   if (G > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
   WsLayout L;
@@ -67,6 +70,7 @@ static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* wor
     st = enqueue_partition(s, g, hs);
     if (st != DLRM_OK) return st;
   }
+  if (algo == DLRM_BWD_SORT_PREPARED_FLAT) g.no_tail = 1;  // the grouping itself does not depend on it
   if (g.weights != nullptr)
     return OPT == kAdagrad ? run_reduce_adagrad_weighted(g, u, s->table_dtype, G, s->K, hs)
                            : run_reduce_sgd_weighted(g, u, s->table_dtype, G, s->K, hs);
@@ -112,7 +116,8 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   if ((s->d & 3) || stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0)
     return DLRM_ERR_BAD_SHAPE;
   if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
-  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_ATOMIC && algo != DLRM_BWD_SORT_PREPARED)
+  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_ATOMIC && algo != DLRM_BWD_SORT_PREPARED &&
+      algo != DLRM_BWD_SORT_PREPARED_FLAT)
     return DLRM_ERR_BAD_ALGO;
   if (algo == DLRM_BWD_ATOMIC && s->table_dtype != DLRM_F32) return DLRM_ERR_BAD_DTYPE;
   if (algo == DLRM_BWD_AUTO) algo = DLRM_BWD_SORT;
@@ -157,7 +162,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   u.lr = lr;
   u.eps = 0.0f;
   u.d = s->d;
-  return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo == DLRM_BWD_SORT_PREPARED, hs);
+  return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo, hs);
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* const* state, const float* dS,
@@ -171,7 +176,10 @@ extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* co
     return DLRM_ERR_BAD_SHAPE;
   if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
   if (!(eps > 0.0f)) return DLRM_ERR_BAD_SHAPE;  // h = 0 and g = 0 would divide 0 by 0
-  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_SORT_PREPARED) return DLRM_ERR_BAD_ALGO;
+  if (algo != DLRM_BWD_AUTO && algo != DLRM_BWD_SORT && algo != DLRM_BWD_SORT_PREPARED &&
+      algo != DLRM_BWD_SORT_PREPARED_FLAT)
+    return DLRM_ERR_BAD_ALGO;
+  if (algo == DLRM_BWD_AUTO) algo = DLRM_BWD_SORT;
   UpdArgs u;
   u.tables = s->tables;
   u.state = state;
@@ -181,8 +189,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* co
   u.lr = lr;
   u.eps = eps;
   u.d = s->d;
-  return run_sort_path<kAdagrad>(s, u, workspace, workspace_bytes, algo == DLRM_BWD_SORT_PREPARED,
-                                 static_cast<hipStream_t>(stream));
+  return run_sort_path<kAdagrad>(s, u, workspace, workspace_bytes, algo, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* workspace,
@@ -197,4 +204,24 @@ extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* wo
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
   return enqueue_partition(s, g, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_prepared_oversized(const dlrm_sparse_batch* s, void* workspace,
+                                                       size_t workspace_bytes, uint32_t* n_oversized,
+                                                       void* stream) {
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  if (!n_oversized) return DLRM_ERR_NULL;
+  if ((s->d & 3) || pow2_ceil(s->d / 4) > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
+  WsLayout L;
+  st = check_ws(s, workspace, workspace_bytes, &L);
+  if (st != DLRM_OK) return st;
+  GroupArgs g;
+  fill_group_args(g, s, L, workspace);
+  // (an empty batch was never partitioned: the counter may hold anything, and nothing is oversized)
+  if (s->nnz_total == 0) g.over_cnt = nullptr;
+  hipLaunchKernelGGL(copy_u32_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), g.over_cnt,
+                     n_oversized);
+  DLRM_CHECK_LAUNCH();
+  return DLRM_OK;
 }

@@ -88,6 +88,10 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert call(_batch(), C.c_void_p(0x1000), need, 9) == -5
     assert call(_batch(), None, 0, hot.BWD_SORT_PREPARED) == -4
     prep = lambda b, ws, n: L.dlrm_emb_bag_bwd_prepare(C.byref(b), ws, n, None)
+    over = lambda b, ws, n, o: L.dlrm_emb_bag_bwd_prepared_oversized(C.byref(b), ws, n, o, None)
+    assert over(_batch(), C.c_void_p(0x1000), 1 << 30, None) == -1
+    assert over(_batch(), None, 1 << 30, C.c_void_p(0x1000)) == -4
+    assert over(_batch(d=6), C.c_void_p(0x1000), 1 << 30, C.c_void_p(0x1000)) == -2
     assert prep(_batch(), None, 0) == -4
     assert prep(_batch(), C.c_void_p(0x1000), need - 1) == -4
     assert prep(_batch(K=0), C.c_void_p(0x1000), need) != 0

@@ -414,6 +414,59 @@ def test_prepare_on_a_second_stream_then_update_gives_the_same_bits(case):
         assert torch.equal(one[k].view(torch.uint8), two[k].view(torch.uint8))
 
 
+FLAT_CASES = [
+    # name, K, B, d, dtype, rows, bag, dist, any oversized row group?
+    ("uniform-large", 2, 1500, 16, gen.F32, 1000000, ("fixed", 40), ("uniform",), False),
+    ("onehot-zipf-large", 26, 4096, 32, gen.F32, 3000000, ("fixed", 1), ("zipf", 1.05), False),
+    ("hot-rows-large", 2, 4096, 32, gen.F32, 50000, ("fixed", 16), ("zipf", 1.4), True),
+    ("many-hot-rows", 2, 4096, 32, gen.F32, 40, ("fixed", 40), ("uniform",), True),
+    ("small-batch", 3, 100, 16, gen.F16, 500, ("uniform", 0, 6), ("uniform",), False),
+]
+
+
+@pytest.mark.parametrize("case", FLAT_CASES, ids=lambda c: c[0])
+def test_oversized_count_and_the_reduce_launch_alone(case):
+    """dlrm_emb_bag_bwd_prepared_oversized into pinned host memory; DLRM_BWD_SORT_PREPARED_FLAT gives the
+    bits of DLRM_BWD_SORT_PREPARED when the count is zero and the oracle's result (other summation
+    order) when it is not."""
+    name, K, B, d, dtype, rows, bag, dist, oversized = case
+    _say("emb_bag_bwd flat %s" % name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=8)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    one, two = upload_tables(host, dtype), upload_tables(host, dtype)
+    F = K + 1
+    dS = b.dS()
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+    lr = float(np.float32(w.lr))
+    sb1, sb2 = make_sparse_batch(b, one), make_sparse_batch(b, two)
+    ws = hot.alloc_workspace(sb1)
+    count = torch.full((3,), -1, dtype=torch.int32).pin_memory()
+    hot.dlrm_emb_bag_bwd_prepare(sb1, ws)
+    hot.dlrm_emb_bag_bwd_prepared_oversized(sb1, ws, count, index=1)
+    hot.dlrm_emb_bag_bwd_sgd(sb1, dT, F * d, d, lr, ws, algo=hot.BWD_SORT_PREPARED, dS_offset=d)
+    torch.cuda.synchronize()
+    assert count[0] == -1 and count[2] == -1
+    assert (int(count[1]) > 0) == oversized
+    hot.dlrm_emb_bag_bwd_prepare(sb2, ws)
+    hot.dlrm_emb_bag_bwd_sgd(sb2, dT, F * d, d, lr, ws, algo=hot.BWD_SORT_PREPARED_FLAT, dS_offset=d)
+    torch.cuda.synchronize()
+    if not oversized:
+        for k in range(K):
+            assert torch.equal(one[k].view(torch.uint8), two[k].view(torch.uint8))
+    ref = [t.copy() for t in host]
+    uniq, _ = oracle.emb_bag_bwd_sgd(ref, dtype, b.indices, b.offsets, b.tbl_off, dS, lr, want_grad=True)
+    scale = scale_sgd(host, dtype, b.indices, b.offsets, b.tbl_off, dS, lr)
+    for k in range(K):
+        got = table_to_numpy(two[k], dtype)
+        mask = np.ones(int(b.rows[k]), dtype=bool)
+        mask[uniq[k]] = False
+        assert np.array_equal(got[mask].view(np.uint8), host[k][mask].view(np.uint8))
+        assert rel_err(widen_host(got[uniq[k]], dtype), widen_host(ref[k][uniq[k]], dtype), scale[k][uniq[k]],
+                       SCALE_FLOOR[dtype]) <= TOL[dtype]
+
+
 ADAGRAD_CASES = [c for c in BWD_CASES if c[0] in (
     "tiny-shape", "multi-tile-ragged", "hot-rows", "d48-nonpow2", "f16-d128-fixed32", "bf16-d64",
     "many-hot-rows", "dominant-rows-large-rest")]
