@@ -72,6 +72,9 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
                                    uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
                                    int src, float* part) {
   constexpr int NG = kThreads / G;
+  // gradient rows a lane group keeps in flight while the workgroup sums a long run: few lane groups
+  // (wide rows) need more each to keep the same number of bytes in flight
+  constexpr int kLongU = (NG >= 32 || WT) ? 4 : 8;
   const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
   const bool col_ok = chunk * 4 < u.d;
   // lanes past the last column shadow column group 0 (same addresses) and never write
@@ -137,7 +140,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     RowRef wr = row_ref<DT, OPT>(W, H, u.d, keys[i0], cchunk);
     RowVal wv{};
     if (upd) wv = row_load<DT, OPT>(wr);
-    const f32x4 acc = sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
+    const f32x4 acc = sum_entries<kLongU, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
     __syncthreads();
     if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
     __syncthreads();
