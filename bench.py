@@ -23,8 +23,8 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by the same counters on the 1 GiB --copy-calib kernel;
 # the summaries are under profiles/.  Keyed by (workload, kernel).
-MEASURED_TRAFFIC = {(3, "bucket_reduce_kernel"): 806.7e6, (3, "emb_fwd_kernel"): 440.0e6,
-                    (5, "bucket_reduce_kernel"): 8.33e9, (5, "emb_fwd_kernel"): 2.28e9}
+MEASURED_TRAFFIC = {(3, "bucket_reduce_kernel"): 806.7e6, (3, "emb_fwd_kernel"): 440.6e6,
+                    (5, "bucket_reduce_kernel"): 8.28e9, (5, "emb_fwd_kernel"): 2.29e9}
 
 
 def parse_args():
