@@ -44,6 +44,9 @@ def parse_args():
                          "one-launch forward applies (short bags)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="the library's event pair around the dominant kernel is recorded on every N-th timed step")
+    ap.add_argument("--self-check", type=int, default=0, metavar="N",
+                    help="before anything is timed, run N steps the way they are timed and N steps call by call "
+                         "on one stream from the same tables and require identical tables")
     ap.add_argument("--graph", action="store_true",
                     help="capture each distinct batch's step in a HIP graph (through torch) and time replays")
     ap.add_argument("--no-flat", action="store_true",
@@ -153,27 +156,53 @@ def main():
     # (measured: the 53K-lookup click-log batch loses 40 us per step to it, the 213K one gains 14).
     overlap = args.algo != "atomic" and not args.no_overlap and max_nnz >= 200_000
     side = torch.cuda.Stream() if overlap else None     # default priority
-    prep_done = torch.cuda.Event()
-    upd_done = torch.cuda.Event()
+    prep_done = torch.cuda.Event()   # (inside a captured graph only)
     use_flat = overlap and not args.no_flat and not args.graph
+    # raw HIP events (ctypes): the pair the library records around its dominant kernel, and the events
+    # that order the two streams.  Neither needs what a default event does when it completes, a
+    # system-scope fence with its cache write-back and invalidation (≈ 5 us of idle device per record,
+    # measured): the timing pair is created with hipEventDisableSystemFence, the ordering events with
+    # hipEventDisableTiming | hipEventReleaseToDevice (both ends are kernels on this device).
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventCreateWithFlags.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipStreamWaitEvent.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint]
+    EV_TIMING, EV_ORDER = 0x20000000, 0x2 | 0x40000000
+
+    def hip_event(flags=EV_TIMING):
+        ev = ctypes.c_void_p()
+        assert hip.hipEventCreateWithFlags(ctypes.byref(ev), flags) == 0
+        return ev
+
+    def ev_record(ev, stream):
+        assert hip.hipEventRecord(ev, ctypes.c_void_p(stream.cuda_stream)) == 0
+
+    def ev_wait(stream, ev):
+        assert hip.hipStreamWaitEvent(ctypes.c_void_p(stream.cuda_stream), ev, 0) == 0
+
     # With the count in use the grouping runs one step ahead, in the other of two workspaces (the indices
     # of the next batch are there early, Sec. 4.1), so that the host never waits for it.
     ws2 = [ws, torch.empty_like(ws)] if use_flat else [ws]
     n_over = torch.zeros(2, dtype=torch.int32).pin_memory()   # written by the device, read by the host
     n_over_np = n_over.numpy()
-    prep_done2 = [torch.cuda.Event(), torch.cuda.Event()]
-    upd_done2 = [torch.cuda.Event(), torch.cuda.Event()]
+    prep_done2 = [hip_event(EV_ORDER), hip_event(EV_ORDER)]
+    upd_done2 = [hip_event(EV_ORDER), hip_event(EV_ORDER)]
+    prep_done_r, upd_done_r = hip_event(EV_ORDER), hip_event(EV_ORDER)
+    main = torch.cuda.current_stream()
 
     def prepare_ahead(i):
         """Grouping of step i's batch on the side stream, in workspace i % 2, with its oversized count."""
         p = i % 2
-        side.wait_event(upd_done2[p])   # step i - 2 is done with this workspace
+        ev_wait(side, upd_done2[p])   # step i - 2 is done with this workspace
         n_over_np[p] = -1
         with torch.cuda.stream(side):
             hot.dlrm_emb_bag_bwd_prepare(dev_batches[i % nb][0], ws2[p])
             hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[i % nb][0], ws2[p], n_over, index=p)
-            prep_done2[p].record(side)
+            ev_record(prep_done2[p], side)
     flat_steps = [0]
+    t_poll = [0.0]
 
     if args.copy_calib:  # 2^22 x 64 fp32 = 1 GiB read + 1 GiB written by a plain copy kernel
         src = torch.empty((1 << 22, 64), dtype=torch.float32, device=dev).normal_()
@@ -183,16 +212,6 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # raw HIP events for the kernel inside dlrm_emb_bag_bwd_sgd (recorded by the library on the
-    # launch stream, around its dominant kernel)
-    import ctypes
-    hip = ctypes.CDLL("libamdhip64.so")
-    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-
-    def hip_event():
-        ev = ctypes.c_void_p()
-        assert hip.hipEventCreate(ctypes.byref(ev)) == 0
-        return ev
     red_ev = [(hip_event(), hip_event()) for _ in range(args.steps)] if args.algo != "atomic" else None
 
     def step(i, ev=None, red=None, overlap=overlap, capturing=False):
@@ -202,10 +221,13 @@ def main():
             if capturing:  # inside a graph the second stream forks from the capturing one
                 side.wait_stream(torch.cuda.current_stream())
             else:
-                side.wait_event(upd_done)   # the previous step's update is done with the workspace
+                ev_wait(side, upd_done_r)   # the previous step's update is done with the workspace
             with torch.cuda.stream(side):
                 hot.dlrm_emb_bag_bwd_prepare(sb, ws)
-                prep_done.record(side)
+                if capturing:
+                    prep_done.record(side)
+                else:
+                    ev_record(prep_done_r, side)
         if ev is not None:
             ev[0].record()
         if not args.split_fwd and ev is None:
@@ -230,27 +252,72 @@ def main():
             hot.dlrm_profile_reduce_kernel(None, None)
         if ahead:
             p = i % 2
+            spins = 0
             while n_over_np[p] < 0:   # pinned memory the device wrote a step ago: no driver call, no sleep
-                pass
+                spins += 1
+                if spins % (1 << 20) == 0 and time.perf_counter() - t_poll[0] > 20.0:
+                    raise RuntimeError("the oversized count of step %d never arrived" % i)
+                if spins == 1:
+                    t_poll[0] = time.perf_counter()
             code = hot.BWD_SORT_PREPARED
             if n_over_np[p] == 0:
                 code = hot.BWD_SORT_PREPARED_FLAT
                 flat_steps[0] += 1
-            torch.cuda.current_stream().wait_event(prep_done2[p])
+            ev_wait(main, prep_done2[p])
             backward(sb, code, ws2[p])
-            upd_done2[p].record()
+            ev_record(upd_done2[p], main)
             prepare_ahead(i + 1)
         elif overlap:
-            torch.cuda.current_stream().wait_event(prep_done)
+            if capturing:
+                torch.cuda.current_stream().wait_event(prep_done)
+            else:
+                ev_wait(main, prep_done_r)
             backward(sb, hot.BWD_SORT_PREPARED)
             if not capturing:
-                upd_done.record()
+                ev_record(upd_done_r, main)
         else:
             backward(sb, algo)
         if ev is not None:
             ev[5].record()
 
     mode = {"ahead": use_flat}
+    if args.self_check:
+        # The steps as they are timed (two streams, events without system fence, the count read from
+        # pinned memory, one-call forward) against the same steps issued call by call on one stream:
+        # the sort path is bit-reproducible, so the tables must come out identical.
+        n_chk = args.self_check
+        saved = [t.clone() for t in tables]
+        saved_state = [h.clone() for h in state] if adagrad else None
+        for ahead_mode in ([True, False] if use_flat else [False]):
+            mode["ahead"] = ahead_mode
+            if ahead_mode:
+                prepare_ahead(0)
+            for i in range(n_chk):
+                step(i)
+            torch.cuda.synchronize()
+            piped = [t.clone() for t in tables]
+            for t, t0 in zip(tables, saved):
+                t.copy_(t0)
+            if adagrad:
+                for h, h0 in zip(state, saved_state):
+                    h.copy_(h0)
+            for i in range(n_chk):
+                step(i, ev=[torch.cuda.Event() for _ in range(6)], overlap=False)
+            torch.cuda.synchronize()
+            for k in range(K):
+                if not torch.equal(piped[k].view(torch.uint8), tables[k].view(torch.uint8)):
+                    raise SystemExit("bench.py --self-check: table %d differs between the timed step "
+                                     "sequence (ahead=%s) and the call-by-call one" % (k, ahead_mode))
+            for t, t0 in zip(tables, saved):
+                t.copy_(t0)
+            if adagrad:
+                for h, h0 in zip(state, saved_state):
+                    h.copy_(h0)
+            del piped
+        del saved, saved_state
+        mode["ahead"] = use_flat
+        flat_steps[0] = 0
+        print("bench.py --self-check: %d steps, tables identical" % n_chk, file=sys.stderr, flush=True)
     if use_flat:
         prepare_ahead(0)
     for i in range(args.warmup):
@@ -263,7 +330,7 @@ def main():
     torch.cuda.synchronize()
     # ---- timed region: exactly --steps steps; the only events inside are the library's pair
     # around the dominant backward kernel, on its launch stream
-    upd_done.record()
+    ev_record(upd_done_r, main)
     torch.cuda.synchronize()
     if args.graph:
         # one graph per distinct batch = one whole step (kernel launches only: the library allocates
