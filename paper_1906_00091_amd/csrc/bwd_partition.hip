@@ -32,8 +32,11 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
 // --- 2. per-table scan (large batches only): counts -> destination offsets ------------
 // One workgroup per table walks (digit, tile) in digit-major order with a running carry
 // that starts at the table's slice, so every table is scattered inside its own slice.
-__global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
-  __shared__ uint32_t smem[1024 / DLRM_WAVE + 1];
+// (256 threads: a 1024-thread workgroup is not placed on a compute unit while the forward kernel,
+// which runs beside this one, keeps filling every freed slot with its own 256-thread workgroups --
+// measured: the scan then only starts when the forward kernel drains)
+__global__ __launch_bounds__(kThreads) void bucket_scan_kernel(GroupArgs a) {
+  __shared__ uint32_t smem[kThreads / DLRM_WAVE + 1];
   const int k = blockIdx.x;
   // first tile of table k = tiles of all earlier tables
   uint32_t t0 = 0;
@@ -42,31 +45,48 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(GroupArgs a) {
   const int nb = 1 << a.top_bits;
   uint32_t carry = (uint32_t)a.tbl_off[k];
   if (nt <= 0) {
-    for (int i = threadIdx.x; i < nb; i += 1024) a.bucket_start[(size_t)k * nb + i] = carry;
+    for (int i = threadIdx.x; i < nb; i += kThreads) a.bucket_start[(size_t)k * nb + i] = carry;
     return;
   }
-  const int64_t n = (int64_t)nt * nb;
-  for (int64_t e0 = 0; e0 < n; e0 += 1024) {
-    const int64_t e = e0 + threadIdx.x;
-    uint32_t v = 0;
-    size_t addr = 0;
-    int digit = 0, t = 0;
-    if (e < n) {
-      digit = (int)(e / nt);
-      t = (int)(e - (int64_t)digit * nt);
-      addr = (size_t)digit * a.nt_max + t0 + t;
-      v = a.hist[addr];
+  // kScanItems consecutive entries per thread and round: their loads are in flight together and a
+  // round costs one workgroup scan (the kernel shares the machine with the forward pass, where every
+  // dependent round trip to memory is several microseconds)
+  constexpr int kScanItems = 16;
+  const uint32_t n = (uint32_t)nt * (uint32_t)nb;   // < 2^31: nt <= nnz / kTile + 1, nb <= 1024
+  for (uint32_t e0 = 0; e0 < n; e0 += kThreads * kScanItems) {
+    uint32_t v[kScanItems], digit[kScanItems], t[kScanItems];
+    size_t addr[kScanItems];
+    uint32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+      const uint32_t e = e0 + threadIdx.x * kScanItems + j;
+      v[j] = 0;
+      digit[j] = t[j] = 0;
+      addr[j] = 0;
+      if (e < n) {
+        digit[j] = e / (uint32_t)nt;
+        t[j] = e - digit[j] * (uint32_t)nt;
+        addr[j] = (size_t)digit[j] * a.nt_max + t0 + t[j];
+        v[j] = a.hist[addr[j]];
+      }
     }
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) sum += v[j];
     uint32_t total;
-    const uint32_t ex = block_exclusive_scan<1024>(v, smem, &total);
-    if (e < n) {
-      a.hist[addr] = carry + ex;
-      if (t == 0) a.bucket_start[(size_t)k * nb + digit] = carry + ex;
+    uint32_t run = carry + block_exclusive_scan<kThreads>(sum, smem, &total);
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+      const uint32_t e = e0 + threadIdx.x * kScanItems + j;
+      if (e < n) {
+        a.hist[addr[j]] = run;
+        if (t[j] == 0) a.bucket_start[(size_t)k * nb + digit[j]] = run;
+        run += v[j];
+      }
     }
     carry += total;
   }
   __syncthreads();  // this workgroup's bucket_start writes are visible to it
-  for (int dg = threadIdx.x; dg < nb; dg += 1024) {
+  for (int dg = threadIdx.x; dg < nb; dg += kThreads) {
     const uint32_t st = a.bucket_start[(size_t)k * nb + dg];
     const uint32_t en = dg + 1 < nb ? a.bucket_start[(size_t)k * nb + dg + 1] : (uint32_t)a.tbl_off[k + 1];
     if (en - st > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(k * nb + dg);
@@ -251,7 +271,7 @@ int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_
     hipLaunchKernelGGL(bucket_hist_kernel<int64_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
   if (!g.fused_scan) {
-    hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(1024), 0, st, g);
+    hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(kThreads), 0, st, g);
     DLRM_CHECK_LAUNCH();
   }
   if (g.idx32)
