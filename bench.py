@@ -159,10 +159,10 @@ def main():
     prep_done = torch.cuda.Event()   # (inside a captured graph only)
     use_flat = overlap and not args.no_flat and not args.graph
     # raw HIP events (ctypes): the pair the library records around its dominant kernel, and the events
-    # that order the two streams.  Neither needs what a default event does when it completes, a
-    # system-scope fence with its cache write-back and invalidation (≈ 5 us of idle device per record,
-    # measured): the timing pair is created with hipEventDisableSystemFence, the ordering events with
-    # hipEventDisableTiming | hipEventReleaseToDevice (both ends are kernels on this device).
+    # that order the two streams.  Neither needs the system-scope fence a default event ends in: the
+    # timing pair is created with hipEventDisableSystemFence, the ordering events with
+    # hipEventDisableTiming | hipEventReleaseToDevice (both ends are kernels on this device).  (An A/B on
+    # one box showed no difference in step time against default events.)
     import ctypes
     hip = ctypes.CDLL("libamdhip64.so")
     hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
