@@ -53,6 +53,7 @@ constexpr int kSortBuckets = 1 << kSortBits;
 constexpr int kBktItems = 8;                    // positions per thread in a bucket-sort tile
 constexpr int kBktCap = kThreads * kBktItems;   // 2048: buckets up to this size are sorted in LDS
 constexpr int kLongRun = 32;                    // longer runs are summed by the whole workgroup
+constexpr int kBigMin = 256;                     // smallest bucket size that can count as heavy (see GroupArgs::big)
 constexpr int kLongRunMin = 16;                 // ... 16 where a workgroup has >= 32 lane groups
 constexpr int kHugeRun = 2048;                  // longer runs are split over workgroups
 constexpr int kHotTileFloats = 16384;            // 64 KB of LDS: gradient rows of one bag tile
@@ -81,9 +82,9 @@ struct WsLayout {
   size_t seg_start;          // uint32[nnz + 1]      (export only)
   size_t seg_tbl;            // uint32[nnz]          (export only)
   size_t n_seg;              // uint32[4]            (export only)
-  size_t huge_ctr;           // uint32[4]: [2] = oversized-bucket count
+  size_t huge_ctr;           // uint32[4]: [2] = listed (heavy) buckets, [3] = oversized buckets among them
   size_t hot_cnt;            // uint32[K]: queued hot runs per table
-  size_t over_list;          // uint32[nnz / kBktCap + 1]: buckets too large for the LDS sort
+  size_t over_list;          // uint32[nnz / kBigMin + 1]: heavy buckets, handed to the first workgroups
   size_t segs;               // SegInfo[nnz / kBktCap + 2]: those of them sorted by many workgroups
   size_t seg_meta;           // uint32[8]: segment tiles, segments
   size_t huge_runs;          // HugeRun[nnz / kHugeRun + K]: table k's list starts at sum_{j<k}(nnz_j/kHugeRun + 1)
@@ -130,7 +131,7 @@ inline WsLayout ws_layout(int32_t K, int32_t B, int32_t d, int64_t nnz) {
   L.n_seg = o;        o = align256(o + 16);
   L.huge_ctr = o;     o = align256(o + 16);
   L.hot_cnt = o;      o = align256(o + (size_t)K * 4);
-  L.over_list = o;    o = align256(o + ((size_t)(nnz / kBktCap) + 1) * 4);
+  L.over_list = o;    o = align256(o + ((size_t)(nnz / kBigMin) + 1) * 4);
   L.segs = o;         o = align256(o + ((size_t)(nnz / kBktCap) + 2) * sizeof(SegInfo));
   L.seg_meta = o;     o = align256(o + 32);
   L.huge_runs = o;    o = align256(o + (size_t)L.max_huge * sizeof(HugeRun));
@@ -163,9 +164,11 @@ struct GroupArgs {            // everything the grouping kernels need
   uint32_t* seg_tbl;
   uint32_t* n_seg;
   uint32_t* hot_cnt;
-  uint32_t* over_cnt;
+  uint32_t* list_cnt;         // heavy buckets listed by the partition (more than `big` pairs)
+  uint32_t* over_cnt;         // those of them with more than kBktCap pairs (oversized)
   uint32_t* over_list;
-  int32_t max_over;           // workgroups reserved at the front of the bucket grid for oversized buckets
+  int32_t max_over;           // workgroups reserved at the front of the bucket grid for the listed buckets
+  uint32_t big;               // a bucket with more pairs is heavy: 4 x the mean bucket, within [kBigMin, kBktCap]
   SegInfo* segs;
   int32_t seg_tiles_max;      // upper bound on the number of segment tiles
   uint32_t* seg_meta;         // [0] segment tiles, [1] segments (one 64-bit counter)
@@ -306,18 +309,19 @@ struct Bucket {
   int low_bits;        // row-id bits below the partition digit
 };
 
-// Buckets larger than the LDS sort take much longer than the rest: they are listed during the
-// partition and handed to the FIRST workgroups of the grid, so that they start early and run
-// beside everything else.  Returns false if this workgroup has nothing to do.
-__device__ inline bool bucket_id_of_block(const GroupArgs& a, uint32_t* id, bool* oversized) {
+// Heavy buckets (hot rows: long runs, or more pairs than the LDS sort holds) take much longer than
+// the rest: they are listed during the partition and handed to the FIRST workgroups of the grid, so
+// that they start at once and run beside everything else; the workgroup a heavy bucket would get by
+// its index leaves it alone.  Returns false if this workgroup has nothing to do.
+__device__ inline bool bucket_id_of_block(const GroupArgs& a, uint32_t* id, bool* listed) {
   if (blockIdx.x < (uint32_t)a.max_over) {
-    if (blockIdx.x >= *a.over_cnt) return false;
+    if (blockIdx.x >= *a.list_cnt) return false;
     *id = a.over_list[blockIdx.x];
-    *oversized = true;
+    *listed = true;
     return true;
   }
   *id = blockIdx.x - (uint32_t)a.max_over;
-  *oversized = false;
+  *listed = false;
   return true;
 }
 
@@ -501,14 +505,20 @@ inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
   g.hot_cnt = reinterpret_cast<uint32_t*>(base + L.hot_cnt);
-  g.over_cnt = reinterpret_cast<uint32_t*>(base + L.huge_ctr + 8);
+  g.list_cnt = reinterpret_cast<uint32_t*>(base + L.huge_ctr + 8);
+  g.over_cnt = reinterpret_cast<uint32_t*>(base + L.huge_ctr + 12);
   g.over_list = reinterpret_cast<uint32_t*>(base + L.over_list);
   g.segs = reinterpret_cast<SegInfo*>(base + L.segs);
   g.seg_meta = reinterpret_cast<uint32_t*>(base + L.seg_meta);
   {
-    const int64_t nbk = (int64_t)s->K << tb, cap = s->nnz_total / kBktCap + 1;
+    const int64_t nbk = (int64_t)s->K << tb;
+    int64_t big = 4 * (s->nnz_total / nbk);
+    if (big < kBigMin) big = kBigMin;
+    if (big > kBktCap) big = kBktCap;
+    g.big = (uint32_t)big;
+    const int64_t cap = s->nnz_total / big + 1, cap_over = s->nnz_total / kBktCap + 1;
     g.max_over = (int32_t)(nbk < cap ? nbk : cap);
-    g.seg_tiles_max = (int32_t)(s->nnz_total / kBktCap + g.max_over);
+    g.seg_tiles_max = (int32_t)(s->nnz_total / kBktCap + (nbk < cap_over ? nbk : cap_over));
   }
   g.huge_runs = reinterpret_cast<HugeRun*>(base + L.huge_runs);
   g.huge_part = reinterpret_cast<float*>(base + L.huge_part);

@@ -22,6 +22,7 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
   for (int i = threadIdx.x; i < nb; i += kThreads) a.hist[(size_t)i * a.nt_max + blockIdx.x] = h[i];
   if (blockIdx.x == 0 && threadIdx.x == 0) {  // consumed by later launches of the same call
     *a.over_cnt = 0u;
+    *a.list_cnt = 0u;
     for (int k = 0; k < a.K; ++k) a.hot_cnt[k] = 0u;
     a.seg_meta[0] = 0u;
     a.seg_meta[1] = 0u;
@@ -89,7 +90,8 @@ __global__ __launch_bounds__(kThreads) void bucket_scan_kernel(GroupArgs a) {
   for (int dg = threadIdx.x; dg < nb; dg += kThreads) {
     const uint32_t st = a.bucket_start[(size_t)k * nb + dg];
     const uint32_t en = dg + 1 < nb ? a.bucket_start[(size_t)k * nb + dg + 1] : (uint32_t)a.tbl_off[k + 1];
-    if (en - st > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(k * nb + dg);
+    if (en - st > a.big) a.over_list[atomicAdd(a.list_cnt, 1u)] = (uint32_t)(k * nb + dg);
+    if (en - st > (uint32_t)kBktCap) atomicAdd(a.over_cnt, 1u);
   }
 }
 
@@ -229,7 +231,8 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
       goff[q] = (uint32_t)ti.tbl_start + base + before[q];
       if (ti.t == 0 && dgt < nb) {
         a.bucket_start[(size_t)ti.k * nb + dgt] = (uint32_t)ti.tbl_start + base;
-        if (total[q] > (uint32_t)kBktCap) a.over_list[atomicAdd(a.over_cnt, 1u)] = (uint32_t)(ti.k * nb + dgt);
+        if (total[q] > a.big) a.over_list[atomicAdd(a.list_cnt, 1u)] = (uint32_t)(ti.k * nb + dgt);
+        if (total[q] > (uint32_t)kBktCap) atomicAdd(a.over_cnt, 1u);
       }
       base += total[q];
     }

@@ -492,10 +492,10 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
   __shared__ SplitLds sp;
   __shared__ float part[kThreads * 4];
   uint32_t bid;
-  bool oversized;
-  if (!bucket_id_of_block(a, &bid, &oversized)) return;
+  bool listed;
+  if (!bucket_id_of_block(a, &bid, &listed)) return;
   const Bucket b = bucket_of_block(a, bid);
-  if (b.n == 0 || (!oversized && b.n > (uint32_t)kBktCap)) return;
+  if (b.n == 0 || (!listed && b.n > a.big)) return;   // a heavy bucket belongs to one of the first workgroups
   char* W = static_cast<char*>(u.tables[b.k]);
   if (b.n <= (uint32_t)kBktCap) {
     sort_bucket_lds(a, b, s);

@@ -7,7 +7,7 @@ namespace dlrm {
 
 __device__ inline void prepare_segments(const GroupArgs& a, uint32_t* smem) {
   const int nb = 1 << a.top_bits;
-  const uint32_t n_over = atomicAdd(a.over_cnt, 0u);
+  const uint32_t n_over = atomicAdd(a.list_cnt, 0u);   // heavy buckets; the oversized ones are among them
   uint32_t nseg = 0, ntiles = 0;
   for (uint32_t e0 = 0; e0 < n_over; e0 += kThreads) {
     const uint32_t e = e0 + threadIdx.x;
@@ -21,7 +21,7 @@ __device__ inline void prepare_segments(const GroupArgs& a, uint32_t* smem) {
       sg.n = end - sg.start;
       sg.k = (uint32_t)k;
       sg.low_bits = (uint32_t)top_shift(a, k);
-      ok = sg.low_bits >= 1 && sg.low_bits <= (uint32_t)kSegMaxBits ? 1u : 0u;
+      ok = sg.n > (uint32_t)kBktCap && sg.low_bits >= 1 && sg.low_bits <= (uint32_t)kSegMaxBits ? 1u : 0u;
       nt = ok ? (sg.n + kBktCap - 1) / kBktCap : 0u;
     }
     uint32_t tot_s, tot_t;
