@@ -379,6 +379,26 @@ def main():
     for s in stages:
         stage_ms[s] /= nbk
 
+    # the update on a batch whose grouping is already done (what the timed steps run after the two
+    # streams have met), by itself: grouped outside the interval, same algo choice as in the timed steps
+    prepared_ms = None
+    if overlap:
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nbk)]
+        chk = torch.zeros(1, dtype=torch.int32, device=dev)
+        for i in range(nbk):
+            sb = dev_batches[(args.warmup + i) % nb][0]
+            hot.dlrm_emb_bag_bwd_prepare(sb, ws)
+            code = hot.BWD_SORT_PREPARED
+            if mode["ahead"]:
+                hot.dlrm_emb_bag_bwd_prepared_oversized(sb, ws, chk)
+                if int(chk.item()) == 0:
+                    code = hot.BWD_SORT_PREPARED_FLAT
+            pe[i][0].record()
+            backward(sb, code)
+            pe[i][1].record()
+        torch.cuda.synchronize()
+        prepared_ms = sum(a.elapsed_time(b_) for a, b_ in pe) / nbk
+
     fused_ms = None
     if fused_fwd:  # the one-launch forward by itself, same batches
         fe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nbk)]
@@ -458,6 +478,14 @@ def main():
                         "frac_of_hbm_peak": round(emb_bytes / (emb_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
         "emb_interact_fwd_ms": None if fused_ms is None else round(fused_ms, 5),
+        "emb_bag_bwd_prepared_ms": None if prepared_ms is None else round(prepared_ms, 5),
+        "emb_fwd_bwd_prepared": None if prepared_ms is None else {
+            "ms": round(stage_ms["emb_bag_fwd"] + prepared_ms, 5),
+            "algorithmic_GBps": round(emb_bytes / ((stage_ms["emb_bag_fwd"] + prepared_ms) * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(emb_bytes / ((stage_ms["emb_bag_fwd"] + prepared_ms) * 1e-3) / 1e9
+                                      / HBM_PEAK_GBPS, 4),
+            "note": "forward call + update call on an already grouped batch (the grouping runs on the second "
+                    "stream in the timed steps)"},
         "stage_ms_source": "separate single-stream pass of %d steps after the timed region" % nbk,
         "stage_algorithmic_GBps": {
             "emb_bag_fwd": round(mean("fwd") / (stage_ms["emb_bag_fwd"] * 1e-3) / 1e9, 1),
