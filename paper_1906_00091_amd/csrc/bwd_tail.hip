@@ -117,7 +117,7 @@ __device__ inline uint32_t lane_entry(uint32_t v, uint32_t e, int slot) {
 }
 
 template <int G, bool WT>
-__global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int ngroups) {
+__global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs u, int ngroups, int dense_from) {
   constexpr int S = DLRM_WAVE / G;
   constexpr int MR = kHotRunsPerWave;
   constexpr int NT = kHotTilesPerGroup;
@@ -135,6 +135,7 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
   const int k = blockIdx.y, g = blockIdx.x;
   const uint32_t nruns = a.hot_cnt[k];
   if (nruns == 0) return;  // uniform
+  if (dense_from > 0 && nruns >= (uint32_t)dense_from) return;  // hot_rows_dense_kernel has this table
   const uint32_t base = hot_list_base(a, k);
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
   const int slot = lane / G, chunk = lane % G;
@@ -302,6 +303,199 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
 }
 
 
+// --- 5b. many hot rows in one table: the same pass as a dense product on the matrix cores -----------
+// With many hot rows per table (a skewed table: the hottest few are in nearly every bag) the kernel
+// above reads a gradient row from LDS once per (hot row, bag) that meets, and LDS reads are what it
+// spends its time on.  Here the multiplicities of kDenseRuns hot rows against the bags of a tile
+// are first counted into a small matrix C[bag][run] in LDS (integer atomics: exact, order-free);
+// then G_hot[run][col] += sum_bag C[bag][run] * dS[bag][col] is a dense contraction over the bags
+// of the tile, done with v_mfma_f32_16x16x4_f32: runs are the M index (two blocks of 16), columns
+// the N index (blocks of 16, dealt to the wavefronts), four bags per instruction.  Every gradient
+// row is read from LDS once per tile, and the accumulators are the instruction's result registers.
+// The same workgroup grid, bag groups, run lists and partial-sum layout as hot_rows_kernel (which
+// keeps the tables with few hot rows and the weighted batches); hot_finish_kernel follows.
+//   16x16x4 layout: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16] and holds
+//   D[m = 4*(l/16) + v][n = l%16] in element v of its accumulator.
+constexpr int kDenseRuns = 32;     // hot rows per pass of a workgroup
+constexpr int kDenseFrom = 8;      // tables with at least this many hot rows take this kernel
+constexpr int kDenseStage = 8;     // float4 registers per thread holding the next tile
+constexpr int kDenseTileFloats = 8192;
+constexpr int kDenseDeep = 4;      // 64-entry chunks of one run's list in flight while counting
+
+template <int G>
+__global__ __launch_bounds__(kThreads) void hot_rows_dense_kernel(GroupArgs a, UpdArgs u, int ngroups) {
+  constexpr int R = kDenseRuns;
+  constexpr int NG = kThreads / G;                 // lane groups = gradient rows staged per pass
+  constexpr int NP = G < kDenseStage ? G : kDenseStage;   // float4 staging registers: tiles of at most 256 bags
+  constexpr int TB = NG * NP;                      // bags per tile: TB * d <= kDenseTileFloats
+  constexpr int GB = NG * kHotStagePasses * kHotTilesPerGroup;  // bags per workgroup, as in hot_rows_kernel
+  constexpr int RW = R / kNW;                      // runs whose entries one wavefront counts
+  constexpr int NBLK = (G * 4 + 15) / 16;          // 16-column blocks of a gradient row (d <= 4G)
+  constexpr int NBW = (NBLK + kNW - 1) / kNW;      // of which a wavefront takes blocks w, w + kNW, ...
+  static_assert(TB * G * 4 <= kDenseTileFloats, "tile");
+  __shared__ float tile[kDenseTileFloats];
+  __shared__ uint32_t cmat[TB][R];                 // multiplicity of run r in bag tb0 + b
+  __shared__ uint32_t rpos[R], rend[R], rsrc[R];   // first entry of a run for this workgroup's bags, its end, its pair buffer
+  const int k = blockIdx.y, g = blockIdx.x;
+  const uint32_t nruns = a.hot_cnt[k];
+  if (nruns < (uint32_t)kDenseFrom) return;  // uniform: hot_rows_kernel has this table
+  const uint32_t base = hot_list_base(a, k);
+  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
+  const int chunk = lane % G;
+  const int grp = tid / G;
+  const bool col_ok = chunk * 4 < u.d;
+  const int cchunk = col_ok ? chunk : 0;  // lanes past the last column shadow column group 0, never store
+  const int bag_lo = g * GB;
+  const int bag_hi = bag_lo + GB < a.B ? bag_lo + GB : a.B;
+  if (bag_lo >= bag_hi) return;  // uniform
+  const float* gk = u.dS + (int64_t)k * u.stride_k + cchunk * 4;
+  const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (uint32_t r0 = 0; r0 < nruns; r0 += R) {  // uniform
+    __syncthreads();
+    // where each run's entries for this workgroup's bags begin (one binary search per run; the tile
+    // boundaries are found on the way, a run's bags ascend) and where the run ends
+    for (int rl = tid; rl < R; rl += kThreads) {
+      const uint32_t r = r0 + (uint32_t)rl;
+      uint32_t c = 0, e = 0, src = 0;
+      if (r < nruns) {
+        const HugeRun hr = a.huge_runs[base + r];
+        const uint32_t* bags = (hr.src ? a.vals[1] : a.vals[0]) + hr.start;
+        uint32_t lo = 0, hi = hr.len;
+        while (lo < hi) {
+          const uint32_t mid = (lo + hi) >> 1;
+          if (bags[mid] < (uint32_t)bag_lo) lo = mid + 1; else hi = mid;
+        }
+        c = hr.start + lo;
+        e = hr.start + hr.len;
+        src = hr.src;
+      }
+      rpos[rl] = c;   // runs past the last one: empty
+      rend[rl] = e;
+      rsrc[rl] = src;
+    }
+    __syncthreads();
+    uint32_t pos[RW], end[RW];   // wave-uniform: next entry / end of the runs this wavefront counts
+    const uint32_t* rb[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      const int rl = w + kNW * i;
+      pos[i] = rpos[rl];
+      end[i] = rend[rl];
+      rb[i] = rsrc[rl] ? a.vals[1] : a.vals[0];
+    }
+    f32x4 acc[2][NBW];   // [run block][column block of this wavefront]
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) acc[0][j] = acc[1][j] = zero;
+    f32x4 stage[NP];
+    {
+      const int nb = bag_hi - bag_lo < TB ? bag_hi - bag_lo : TB;
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const int bb = p * NG + grp < nb ? p * NG + grp : nb - 1;
+        stage[p] = loadf4(gk + (int64_t)(bag_lo + bb) * u.stride_b);
+      }
+    }
+    int t = 0;
+    for (int tb0 = bag_lo; tb0 < bag_hi; tb0 += TB, ++t) {  // uniform
+      const int nb = bag_hi - tb0 < TB ? bag_hi - tb0 : TB;
+      __syncthreads();  // the previous tile and its counts have been consumed
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        const int bb = p * NG + grp;
+        if (col_ok) storef4(tile + bb * u.d + chunk * 4, bb < nb ? stage[p] : zero);  // no stale rows
+      }
+      for (int i = tid; i < TB * R; i += kThreads) (&cmat[0][0])[i] = 0u;
+      __syncthreads();
+      if (tb0 + TB < bag_hi) {  // uniform: the next tile travels while this one is used
+        const int nn = bag_hi - (tb0 + TB) < TB ? bag_hi - (tb0 + TB) : TB;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const int bb = p * NG + grp < nn ? p * NG + grp : nn - 1;
+          stage[p] = loadf4(gk + (int64_t)(tb0 + TB + bb) * u.stride_b);
+        }
+      }
+      // count: wavefront w takes the entries of runs w, w + 4, ... that fall into this tile (a prefix
+      // of what is left of the run); the next 64 entries of all its runs are requested together
+      {
+        const uint32_t bound = (uint32_t)(tb0 + nb);
+        uint32_t first[RW];
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+          first[i] = 0xFFFFFFFFu;
+          if (pos[i] + (uint32_t)lane < end[i]) first[i] = rb[i][pos[i] + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+          const int rl = w + kNW * i;
+          {
+            const bool in = first[i] < bound;
+            if (in) atomicAdd(&cmat[first[i] - (uint32_t)tb0][rl], 1u);
+            const uint32_t n = (uint32_t)__popcll(__ballot(in));
+            pos[i] += n;
+            if (n < (uint32_t)DLRM_WAVE) continue;   // wave-uniform: the run's entries for this tile are done
+          }
+          while (true) {   // a run with many entries per tile: kDenseDeep x 64 entries in flight per round
+            uint32_t bag[kDenseDeep];
+#pragma unroll
+            for (int q = 0; q < kDenseDeep; ++q) {
+              const uint32_t e = pos[i] + (uint32_t)(q * DLRM_WAVE + lane);
+              bag[q] = 0xFFFFFFFFu;
+              if (e < end[i]) bag[q] = rb[i][e];
+            }
+            uint32_t n = 0;
+#pragma unroll
+            for (int q = 0; q < kDenseDeep; ++q) {   // ascending bags: those inside the tile are a prefix
+              const bool in = bag[q] < bound;
+              if (in) atomicAdd(&cmat[bag[q] - (uint32_t)tb0][rl], 1u);
+              n += (uint32_t)__popcll(__ballot(in));
+            }
+            pos[i] += n;
+            if (n < (uint32_t)(kDenseDeep * DLRM_WAVE)) break;
+          }
+        }
+      }
+      __syncthreads();
+      // contract over the bags of the tile, four per instruction
+      {
+        const int m = lane & 15, kk = lane >> 4;
+#pragma unroll 2
+        for (int k0 = 0; k0 < TB; k0 += 4) {
+          const float a0 = (float)cmat[k0 + kk][m];
+          const float a1 = (float)cmat[k0 + kk][16 + m];
+          const float* trow = tile + (k0 + kk) * u.d;
+#pragma unroll
+          for (int j = 0; j < NBW; ++j) {
+            const int col = (w + kNW * j) * 16 + m;
+            if ((w + kNW * j) * 16 < u.d) {  // wave-uniform
+              const float b = col < u.d ? trow[col] : 0.0f;
+              acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b, acc[0][j], 0, 0, 0);
+              acc[1][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b, acc[1][j], 0, 0, 0);
+            }
+          }
+        }
+      }
+    }
+    // D[m = 4*(l/16) + v][n = l%16]: run r0 + 16*mb + m, column 16*(w + kNW*j) + n
+    {
+      const int n = lane & 15, mq = (lane >> 4) * 4;
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+        for (int j = 0; j < NBW; ++j) {
+          const int col = (w + kNW * j) * 16 + n;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const uint32_t run = r0 + (uint32_t)(mb * 16 + mq + v);
+            if (run < nruns && col < u.d)
+              a.huge_part[((size_t)(base + run) * ngroups + g) * u.d + col] = acc[mb][j][v];
+          }
+        }
+      }
+    }
+  }
+}
+
+
 int launch_segment_sort(const GroupArgs& g, hipStream_t st) {
   hipLaunchKernelGGL(segment_sort_kernel, dim3((unsigned)g.seg_tiles_max), dim3(kThreads), 0, st, g);
   DLRM_CHECK_LAUNCH();
@@ -310,10 +504,15 @@ int launch_segment_sort(const GroupArgs& g, hipStream_t st) {
 
 template <int G>
 static int launch_hot(const GroupArgs& g, const UpdArgs& u, int K, int ngroups, hipStream_t st) {
-  if (g.weights != nullptr)
-    hipLaunchKernelGGL((hot_rows_kernel<G, true>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
-  else
-    hipLaunchKernelGGL((hot_rows_kernel<G, false>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
+  if (g.weights != nullptr) {
+    hipLaunchKernelGGL((hot_rows_kernel<G, true>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups, 0);
+  } else {
+    // tables with many hot rows go through the dense kernel, the others through the entry-by-entry one
+    hipLaunchKernelGGL((hot_rows_dense_kernel<G>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
+    DLRM_CHECK_LAUNCH();
+    hipLaunchKernelGGL((hot_rows_kernel<G, false>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups,
+                       kDenseFrom);
+  }
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }
