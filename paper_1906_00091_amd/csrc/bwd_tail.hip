@@ -375,12 +375,14 @@ __global__ __launch_bounds__(kThreads) void hot_rows_dense_kernel(GroupArgs a, U
     }
     __syncthreads();
     uint32_t pos[RW], end[RW];   // wave-uniform: next entry / end of the runs this wavefront counts
+    int want[RW];                // wave-uniform: list chunks to request for the next tile
     const uint32_t* rb[RW];
 #pragma unroll
     for (int i = 0; i < RW; ++i) {
       const int rl = w + kNW * i;
       pos[i] = rpos[rl];
       end[i] = rend[rl];
+      want[i] = 1;
       rb[i] = rsrc[rl] ? a.vals[1] : a.vals[0];
     }
     f32x4 acc[2][NBW];   // [run block][column block of this wavefront]
@@ -415,26 +417,35 @@ __global__ __launch_bounds__(kThreads) void hot_rows_dense_kernel(GroupArgs a, U
         }
       }
       // count: wavefront w takes the entries of runs w, w + 4, ... that fall into this tile (a prefix
-      // of what is left of the run); the next 64 entries of all its runs are requested together
+      // of what is left of the run).  All its runs' list chunks are requested together: per run as
+      // many 64-entry chunks as the previous tile used, plus one (a run's share of a tile changes
+      // little from tile to tile), so that a tile usually costs one round trip to memory.
       {
         const uint32_t bound = (uint32_t)(tb0 + nb);
-        uint32_t first[RW];
+        uint32_t ent[RW][kDenseDeep];
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
-          first[i] = 0xFFFFFFFFu;
-          if (pos[i] + (uint32_t)lane < end[i]) first[i] = rb[i][pos[i] + lane];
+#pragma unroll
+          for (int q = 0; q < kDenseDeep; ++q) {
+            ent[i][q] = 0xFFFFFFFFu;
+            const uint32_t e = pos[i] + (uint32_t)(q * DLRM_WAVE + lane);
+            if (q < want[i] && e < end[i]) ent[i][q] = rb[i][e];   // q < want[i]: wave-uniform
+          }
         }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
           const int rl = w + kNW * i;
-          {
-            const bool in = first[i] < bound;
-            if (in) atomicAdd(&cmat[first[i] - (uint32_t)tb0][rl], 1u);
-            const uint32_t n = (uint32_t)__popcll(__ballot(in));
-            pos[i] += n;
-            if (n < (uint32_t)DLRM_WAVE) continue;   // wave-uniform: the run's entries for this tile are done
+          uint32_t n = 0;
+#pragma unroll
+          for (int q = 0; q < kDenseDeep; ++q) {   // ascending bags: those inside the tile are a prefix
+            const bool in = ent[i][q] < bound;
+            if (in) atomicAdd(&cmat[ent[i][q] - (uint32_t)tb0][rl], 1u);
+            n += (uint32_t)__popcll(__ballot(in));
           }
-          while (true) {   // a run with many entries per tile: kDenseDeep x 64 entries in flight per round
+          pos[i] += n;
+          uint32_t used = n;
+          while (n == (uint32_t)(want[i] * DLRM_WAVE)) {   // wave-uniform: every requested entry was inside
+            want[i] = kDenseDeep;
             uint32_t bag[kDenseDeep];
 #pragma unroll
             for (int q = 0; q < kDenseDeep; ++q) {
@@ -442,16 +453,18 @@ __global__ __launch_bounds__(kThreads) void hot_rows_dense_kernel(GroupArgs a, U
               bag[q] = 0xFFFFFFFFu;
               if (e < end[i]) bag[q] = rb[i][e];
             }
-            uint32_t n = 0;
+            n = 0;
 #pragma unroll
-            for (int q = 0; q < kDenseDeep; ++q) {   // ascending bags: those inside the tile are a prefix
+            for (int q = 0; q < kDenseDeep; ++q) {
               const bool in = bag[q] < bound;
               if (in) atomicAdd(&cmat[bag[q] - (uint32_t)tb0][rl], 1u);
               n += (uint32_t)__popcll(__ballot(in));
             }
             pos[i] += n;
-            if (n < (uint32_t)(kDenseDeep * DLRM_WAVE)) break;
+            used += n;
           }
+          const int w1 = (int)(used / DLRM_WAVE) + 1;
+          want[i] = w1 < kDenseDeep ? w1 : kDenseDeep;
         }
       }
       __syncthreads();
