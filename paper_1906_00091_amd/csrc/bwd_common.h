@@ -25,6 +25,8 @@
 //                       with per-row counters in LDS, then reduced window by window.
 //   5. hot_rows       : workgroup (bag group, table) streams the gradient rows of its bags
 //                       through LDS once and adds them into every hot row that names them;
+//      hot_rows_dense : the same for tables with many hot rows, as a dense contraction on the
+//                       matrix cores (multiplicity matrix [bag][hot row] times gradient tile);
 //      hot_finish     : adds a hot row's partial sums in bag-group order and updates the row.
 // Steps 1-3 read indices and offsets only; dlrm_emb_bag_bwd_prepare enqueues just them.
 // ATOMIC path (fp32 tables): a lane group per bag adds -lr*dS[b,k,:] to every row of the bag

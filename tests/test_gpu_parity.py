@@ -273,6 +273,10 @@ BWD_CASES = [
     # rarely taken routes of the sort path
     # 40 rows x ~4096 lookups each: more hot rows per table than one pass of the hot-row kernel holds
     ("many-hot-rows", 2, 4096, 32, gen.F32, 40, ("fixed", 40), ("uniform",)),
+    # 20 hot rows per table, rows of 64 and 256 floats: the dense hot-row kernel with one and four
+    # 16-column blocks per wavefront, a last bag group that is not full, a last tile that is not full
+    ("dense-hot-rows-d64", 2, 2500, 64, gen.F32, 20, ("fixed", 40), ("uniform",)),
+    ("dense-hot-rows-d256-f16", 1, 1100, 256, gen.F16, 12, ("fixed", 70), ("uniform",)),
     # every bucket too large for the LDS sort, nothing dominant, few unsorted bits: segment kernels
     ("segments-no-dominant-row", 1, 32768, 8, gen.F32, 1 << 22, ("fixed", 96), ("uniform",)),
     # dominant rows split off AND a remainder that is still too large
@@ -362,12 +366,14 @@ def test_emb_bag_bwd_sgd_matches_oracle(case, algo):
             assert np.max(np.abs(step_got - lr * grad[k])) <= bound
         else:
             # low-precision tables: fp32 arithmetic + one rounding lands within one unit in the
-            # last place of the fp64-then-rounded reference
+            # last place of the fp64-then-rounded reference, give or take the fp32 error of the value
+            # that was rounded (1e-5 of its magnitude scale: it matters where thousands of gradient rows
+            # are summed and the result cancels against the row)
             a, r = widen_host(g_rows, dtype), widen_host(r_rows, dtype)
             mant = 10 if dtype == gen.F16 else 7
             emin = -14 if dtype == gen.F16 else -126
             expo = np.maximum(np.floor(np.log2(np.maximum(np.abs(r), 2.0 ** emin))), emin)
-            assert np.all(np.abs(a - r) <= 2.0 ** (expo - mant))
+            assert np.all(np.abs(a - r) <= 2.0 ** (expo - mant) + 1e-5 * scale[k][uniq[k]])
     if algo == "sort":
         # bitwise reproducible: same inputs, same bits
         tables2 = [t.clone() for t in before]
@@ -469,7 +475,7 @@ def test_oversized_count_and_the_reduce_launch_alone(case):
 
 ADAGRAD_CASES = [c for c in BWD_CASES if c[0] in (
     "tiny-shape", "multi-tile-ragged", "hot-rows", "d48-nonpow2", "f16-d128-fixed32", "bf16-d64",
-    "many-hot-rows", "dominant-rows-large-rest")]
+    "many-hot-rows", "dominant-rows-large-rest", "dense-hot-rows-d64")]
 
 
 @pytest.mark.parametrize("fresh", [False, True], ids=["warm-state", "fresh-state"])
