@@ -248,7 +248,7 @@ int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* batch, void* workspace
  * grouping cuts a table into: heavy-hitter rows, or tables much smaller than the batch).
  * n_oversized: one uint32 the device can write, e.g. pinned host memory, which the caller
  * reads once the stream has passed this call.
- * Zero means the update needs none of its segment / hot-row launches (four launches that
+ * Zero means the update needs none of its segment / hot-row launches (launches that
  * would find nothing to do): DLRM_BWD_SORT_PREPARED_FLAT then enqueues the reduce kernel
  * alone and gives the same bits as DLRM_BWD_SORT_PREPARED.  With oversized groups FLAT is
  * still correct, but each is handled by a single workgroup (slow for heavy hitters) and long
