@@ -203,6 +203,7 @@ def main():
             ev_record(prep_done2[p], side)
     flat_steps = [0]
     t_poll = [0.0]
+    poll_wait = [0.0, 0]
 
     if args.copy_calib:  # 2^22 x 64 fp32 = 1 GiB read + 1 GiB written by a plain copy kernel
         src = torch.empty((1 << 22, 64), dtype=torch.float32, device=dev).normal_()
@@ -259,6 +260,9 @@ def main():
                     raise RuntimeError("the oversized count of step %d never arrived" % i)
                 if spins == 1:
                     t_poll[0] = time.perf_counter()
+            if spins:
+                poll_wait[0] += time.perf_counter() - t_poll[0]
+                poll_wait[1] += 1
             code = hot.BWD_SORT_PREPARED
             if n_over_np[p] == 0:
                 code = hot.BWD_SORT_PREPARED_FLAT
@@ -477,6 +481,7 @@ def main():
                         "algorithmic_GBps": round(emb_bytes / (emb_ms * 1e-3) / 1e9, 1),
                         "frac_of_hbm_peak": round(emb_bytes / (emb_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "stage_ms": {k: round(v, 5) for k, v in stage_ms.items()},
+        "host_poll_wait": {"ms_total": round(poll_wait[0] * 1e3, 3), "steps_that_waited": poll_wait[1]},
         "emb_interact_fwd_ms": None if fused_ms is None else round(fused_ms, 5),
         "emb_bag_bwd_prepared_ms": None if prepared_ms is None else round(prepared_ms, 5),
         "emb_fwd_bwd_prepared": None if prepared_ms is None else {
