@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--no-flat", action="store_true",
                     help="always enqueue the segment / hot-row launches of the backward, instead of reading the "
                          "prepared batch's count of oversized row groups on the host and leaving them out at zero")
+    ap.add_argument("--no-stamp", action="store_true",
+                    help="order the two streams with events only, not with the forward call's start stamp")
     ap.add_argument("--no-overlap", action="store_true",
                     help="group the (row, bag) pairs inside the backward call instead of on a second "
                          "stream beside the forward pass")
@@ -192,15 +194,42 @@ def main():
     prep_done_r, upd_done_r = hip_event(EV_ORDER), hip_event(EV_ORDER)
     main = torch.cuda.current_stream()
 
-    def prepare_ahead(i):
-        """Grouping of step i's batch on the side stream, in workspace i % 2, with its oversized count."""
+    # Stream order without events where the forward is one call: its first kernel stamps a pinned word
+    # as it starts, which tells the polling host that the previous step's update is over (an event
+    # recorded on the first stream costs the step 6.5 us; the stamp rides in a kernel that runs anyway).
+    use_stamp = use_flat and not args.split_fwd and not args.no_stamp
+    stamp = torch.zeros(1, dtype=torch.int32).pin_memory()
+    stamp_np = stamp.numpy()
+    seq = [0]
+
+    def host_wait(cond, what):
+        """Spin on pinned memory the device writes (no driver call, no sleep); the time goes to poll_wait."""
+        spins = 0
+        while not cond():
+            spins += 1
+            if spins == 1:
+                t_poll[0] = time.perf_counter()
+            if spins % (1 << 20) == 0 and time.perf_counter() - t_poll[0] > 20.0:
+                raise RuntimeError(what + " never arrived")
+        if spins:
+            poll_wait[0] += time.perf_counter() - t_poll[0]
+            poll_wait[1] += 1
+
+    def prepare_ahead(i, after_seq=0):
+        """Grouping of step i's batch on the side stream, in workspace i % 2, with its oversized count.
+        The workspace was last used by step i - 2: with stamps the host waits until the forward pass of
+        step i - 1 has begun, else the side stream waits for the event recorded behind that update."""
         p = i % 2
-        ev_wait(side, upd_done2[p])   # step i - 2 is done with this workspace
+        if use_stamp:
+            host_wait(lambda: stamp_np[0] >= after_seq, "the start stamp of the forward pass")
+        else:
+            ev_wait(side, upd_done2[p])
         n_over_np[p] = -1
         with torch.cuda.stream(side):
             hot.dlrm_emb_bag_bwd_prepare(dev_batches[i % nb][0], ws2[p])
             hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[i % nb][0], ws2[p], n_over, index=p)
-            ev_record(prep_done2[p], side)
+            if not use_stamp:
+                ev_record(prep_done2[p], side)
     flat_steps = [0]
     t_poll = [0.0]
     poll_wait = [0.0, 0]
@@ -233,7 +262,12 @@ def main():
             ev[0].record()
         if not args.split_fwd and ev is None:
             # one call; one launch for short bags, else two (the dense vectors ride in the pooling launch)
-            hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT)
+            if ahead and use_stamp:
+                seq[0] += 1
+                hot.dlrm_emb_interact_fwd_stamped(sb, x, T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT,
+                                                  stamp, seq[0])
+            else:
+                hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT)
         else:
             hot.dlrm_place_dense(x, T)
             if ev is not None:
@@ -253,24 +287,21 @@ def main():
             hot.dlrm_profile_reduce_kernel(None, None)
         if ahead:
             p = i % 2
-            spins = 0
-            while n_over_np[p] < 0:   # pinned memory the device wrote a step ago: no driver call, no sleep
-                spins += 1
-                if spins % (1 << 20) == 0 and time.perf_counter() - t_poll[0] > 20.0:
-                    raise RuntimeError("the oversized count of step %d never arrived" % i)
-                if spins == 1:
-                    t_poll[0] = time.perf_counter()
-            if spins:
-                poll_wait[0] += time.perf_counter() - t_poll[0]
-                poll_wait[1] += 1
+            # the count arrives behind the grouping on the side stream: once the host has it, the
+            # grouping is done and the first stream need not wait for it
+            host_wait(lambda: n_over_np[p] >= 0, "the oversized count of step %d" % i)
             code = hot.BWD_SORT_PREPARED
             if n_over_np[p] == 0:
                 code = hot.BWD_SORT_PREPARED_FLAT
                 flat_steps[0] += 1
-            ev_wait(main, prep_done2[p])
-            backward(sb, code, ws2[p])
-            ev_record(upd_done2[p], main)
-            prepare_ahead(i + 1)
+            if use_stamp:
+                backward(sb, code, ws2[p])
+                prepare_ahead(i + 1, seq[0])
+            else:
+                ev_wait(main, prep_done2[p])
+                backward(sb, code, ws2[p])
+                ev_record(upd_done2[p], main)
+                prepare_ahead(i + 1)
         elif overlap:
             if capturing:
                 torch.cuda.current_stream().wait_event(prep_done)

@@ -170,6 +170,19 @@ int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* batch, const float* x, fl
                               int32_t algo, void* stream);
 
 /*
+ * The same call with a start stamp.  stamp: one uint32 the device can write (e.g. pinned host
+ * memory), or NULL for none.  The first kernel of the call stores stamp_value there as it
+ * begins to execute (a system-scope store: it does not wait for the end of the kernel).
+ * By stream order everything enqueued on `stream` before this call has completed by then, so
+ * a host that polls the word learns it without an event on the stream -- e.g. that the
+ * previous step's update is done with its backward workspace, which may now be prepared
+ * for another batch on a second stream.  (An event record costs the stream about 6 us on
+ * MI355X; the stamp rides in a kernel that runs anyway.)
+ */
+int32_t dlrm_emb_interact_fwd_stamped(const dlrm_sparse_batch* batch, const float* x, float* T, float* R,
+                                      int32_t algo, uint32_t* stamp, uint32_t stamp_value, void* stream);
+
+/*
  * Backward of the above by the chain rule (the paper prints none).  With
  * g_ij = dR[b, d + i(i-1)/2 + j]:
  *   dT[b,i,:] = sum_{j<i} g_ij T[b,j,:] + sum_{j>i} g_ji T[b,j,:]  (+ dR[b,0:d] for i = 0)

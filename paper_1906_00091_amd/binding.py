@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.dlrm_interact_dot_fwd.argtypes = [vp, i32, i32, i32, vp, vp]
         L.dlrm_emb_interact_fwd.restype = i32
         L.dlrm_emb_interact_fwd.argtypes = [sb, vp, vp, vp, i32, vp]
+        L.dlrm_emb_interact_fwd_stamped.restype = i32
+        L.dlrm_emb_interact_fwd_stamped.argtypes = [sb, vp, vp, vp, i32, vp, C.c_uint32, vp]
         L.dlrm_interact_dot_bwd.restype = i32
         L.dlrm_interact_dot_bwd.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.dlrm_emb_bag_bwd_workspace_bytes.restype = sz
@@ -180,6 +182,16 @@ def dlrm_emb_interact_fwd(batch: SparseBatch, x: torch.Tensor, T: torch.Tensor, 
                           algo: int = FWD_AUTO):
     _check("dlrm_emb_interact_fwd",
            lib().dlrm_emb_interact_fwd(batch.ref(), _ptr(x), _ptr(T), _ptr(R), algo, _stream()))
+
+
+def dlrm_emb_interact_fwd_stamped(batch: SparseBatch, x: torch.Tensor, T: torch.Tensor, R: torch.Tensor,
+                                  algo: int, stamp: torch.Tensor, stamp_value: int, index: int = 0):
+    """stamp: int32 tensor the device can write (device memory, or host memory allocated pinned);
+    element `index` receives stamp_value when the call's first kernel starts."""
+    assert stamp.dtype == torch.int32 and (stamp.is_cuda or stamp.is_pinned()) and 0 <= index < stamp.numel()
+    _check("dlrm_emb_interact_fwd_stamped",
+           lib().dlrm_emb_interact_fwd_stamped(batch.ref(), _ptr(x), _ptr(T), _ptr(R), algo,
+                                               _ptr(stamp) + 4 * index, stamp_value & 0xFFFFFFFF, _stream()))
 
 
 def dlrm_interact_dot_bwd(T: torch.Tensor, dR: torch.Tensor, dT: torch.Tensor):

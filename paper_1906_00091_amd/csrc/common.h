@@ -146,6 +146,14 @@ __device__ inline void store8_stream(void* p, u32x2 v) {
 }
 __device__ inline void storef4(float* p, f32x4 v) { *reinterpret_cast<f32x4*>(p) = v; }
 
+// The first thread of a launch tells a polling host that the launch has begun (and so, by stream
+// order, that everything enqueued before it on its stream is done): a system-scope store that
+// leaves the device at once instead of waiting in a cache for the end of the kernel.
+__device__ inline void stamp_start(uint32_t* stamp, uint32_t value) {
+  if (stamp != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    __hip_atomic_store(stamp, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __device__ inline int lane_id() { return threadIdx.x & (DLRM_WAVE - 1); }
 __device__ inline int wave_id() { return threadIdx.x >> 6; }
 

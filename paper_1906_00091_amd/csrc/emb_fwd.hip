@@ -34,6 +34,8 @@ struct FwdArgs {
   const float* dense;
   float* dense_out;
   uint32_t bag_blocks;
+  uint32_t* stamp;       // optional: see stamp_start
+  uint32_t stamp_value;
 };
 
 // true for the rider workgroups, after they have done their copy
@@ -59,6 +61,7 @@ __device__ inline void write_pooled(float* o, const float* acc) {
 // ---------------------------------------------------------------------------
 template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
+  stamp_start(a.stamp, a.stamp_value);
   if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -121,6 +124,7 @@ __global__ __launch_bounds__(256) void emb_fwd_group_kernel(FwdArgs a) {
 // NB consecutive bags and walks their chains side by side.
 template <int DT, int G, int NB, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
+  stamp_start(a.stamp, a.stamp_value);
   if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -188,6 +192,7 @@ __global__ __launch_bounds__(256) void emb_fwd_short_kernel(FwdArgs a) {
 // ---------------------------------------------------------------------------
 template <int DT, int G, int U, bool WT, typename IT>
 __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
+  stamp_start(a.stamp, a.stamp_value);
   if (dense_rider(a)) return;  // workgroup-uniform
   constexpr int E = Tab<DT>::ELEMS;
   constexpr int S = DLRM_WAVE / G;
@@ -318,7 +323,7 @@ namespace dlrm {
 // The pooled lookup; with x != NULL the same launch also copies x[B,d] to out - d + b*stride_b
 // (the dense vector into row 0 of an interaction input whose rows 1..K are `out`).
 int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, int64_t stride_k, const float* x,
-                    void* stream) {
+                    uint32_t* stamp, uint32_t stamp_value, void* stream) {
   int st = check_batch(s);
   if (st != DLRM_OK) return st;
   if (!out) return DLRM_ERR_NULL;
@@ -340,6 +345,8 @@ int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, in
   a.dense = x;
   a.dense_out = x ? out - s->d : nullptr;
   a.bag_blocks = 0;
+  a.stamp = stamp;
+  a.stamp_value = stamp_value;
   const int G = pow2_ceil(a.chunks);
   const int S = DLRM_WAVE / G;
   // a wavefront per bag pays off once a bag keeps all S lane groups busy for a few rounds
@@ -359,5 +366,5 @@ int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, in
 
 extern "C" int32_t dlrm_emb_bag_fwd(const dlrm_sparse_batch* s, float* out, int64_t stride_b,
                                     int64_t stride_k, void* stream) {
-  return dlrm::emb_fwd_enqueue(s, out, stride_b, stride_k, nullptr, stream);
+  return dlrm::emb_fwd_enqueue(s, out, stride_b, stride_k, nullptr, nullptr, 0u, stream);
 }

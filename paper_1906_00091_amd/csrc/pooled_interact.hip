@@ -26,6 +26,8 @@ struct PiArgs {
   float* T;
   float* R;
   int32_t K, B, d, pstride;
+  uint32_t* stamp;       // optional: see stamp_start
+  uint32_t stamp_value;
 };
 
 // table elements col .. col+3 of the row at `row`, widened to fp32 (col a multiple of 4)
@@ -58,6 +60,7 @@ __global__ __launch_bounds__(kPiThreads, NB <= 2 ? 4 : 2) void pooled_interact_f
   constexpr int NTILE = NB * (NB + 1) / 2;
   constexpr int EB = Tab<DT>::EB;
   extern __shared__ float lds[];
+  stamp_start(a.stamp, a.stamp_value);
   const int lane = lane_id();
   const int b = blockIdx.x * kPiWaves + wave_id();
   if (b >= a.B) return;  // wavefronts are independent: no barriers below
@@ -214,12 +217,18 @@ static int dispatch_it(const PiArgs& a, bool idx32, hipStream_t st) {
 
 int check_batch(const dlrm_sparse_batch* s);  // util.hip
 int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, int64_t stride_k, const float* x,
-                    void* stream);            // emb_fwd.hip
+                    uint32_t* stamp, uint32_t stamp_value, void* stream);   // emb_fwd.hip
 
 }  // namespace dlrm
 
 extern "C" int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* s, const float* x, float* T, float* R,
                                          int32_t algo, void* stream) {
+  return dlrm_emb_interact_fwd_stamped(s, x, T, R, algo, nullptr, 0u, stream);
+}
+
+extern "C" int32_t dlrm_emb_interact_fwd_stamped(const dlrm_sparse_batch* s, const float* x, float* T, float* R,
+                                                 int32_t algo, uint32_t* stamp, uint32_t stamp_value,
+                                                 void* stream) {
   using namespace dlrm;
   int st = check_batch(s);
   if (st != DLRM_OK) return st;
@@ -236,7 +245,7 @@ extern "C" int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* s, const float
   }
   if (algo == DLRM_FWD_SPLIT) {
     // the dense vectors ride along in the pooling launch
-    st = emb_fwd_enqueue(s, T + s->d, (int64_t)F * s->d, s->d, x, stream);
+    st = emb_fwd_enqueue(s, T + s->d, (int64_t)F * s->d, s->d, x, stamp, stamp_value, stream);
     if (st != DLRM_OK) return st;
     return dlrm_interact_dot_fwd(T, s->B, F, s->d, R, stream);
   }
@@ -251,6 +260,8 @@ extern "C" int32_t dlrm_emb_interact_fwd(const dlrm_sparse_batch* s, const float
   a.K = s->K;
   a.B = s->B;
   a.d = s->d;
+  a.stamp = stamp;
+  a.stamp_value = stamp_value;
   const int P = F * (F - 1) / 2;
   a.pstride = P < 4 ? 4 : ((P + 3) & ~3);
   hipStream_t hs = static_cast<hipStream_t>(stream);

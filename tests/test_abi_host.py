@@ -66,6 +66,9 @@ def test_one_call_forward_rejects_bad_arguments_on_the_host():
     assert call(_batch(), algo=3) == -5
     assert call(_batch(K=65), algo=1) == -5           # the one-launch kernel takes up to 64 tables
     assert call(_batch(weights=0x1000), algo=1) == -5  # and no pooling weights
+    st = lambda b, x=p, stamp=None: L.dlrm_emb_interact_fwd_stamped(C.byref(b), x, p, p, 0, stamp, 5, None)
+    assert st(_batch(tables=None)) == -1                # the stamped call checks the same things first
+    assert st(_batch(), x=None, stamp=C.c_void_p(0x1000)) == -1
 
 
 def test_unknown_index_dtype_is_rejected():

@@ -218,6 +218,28 @@ def scaleT_pad(scaleT, x):
     return np.concatenate([np.abs(x)[:, None, :].astype(np.float64), scaleT], axis=1).astype(np.float32)
 
 
+@pytest.mark.parametrize("algo", ["fused", "split"])
+def test_emb_interact_fwd_start_stamp_arrives_and_changes_nothing(algo):
+    _say("emb_interact_fwd stamped " + algo)
+    code = hot.FWD_FUSED if algo == "fused" else hot.FWD_SPLIT
+    w = gen.custom_workload("st", K=5, B=300, d=32, rows=400, bag=("uniform", 0, 3), seed=9)
+    b = gen.make_batch(w)
+    tables = upload_tables(_host_tables(b), gen.F32)
+    sb = make_sparse_batch(b, tables)
+    F, P = 6, 15
+    x = torch.from_numpy(np.random.default_rng(1).standard_normal((300, 32)).astype(np.float32)).to(DEV)
+    T0, R0 = torch.empty((300, F, 32), device=DEV), torch.empty((300, 32 + P), device=DEV)
+    hot.dlrm_emb_interact_fwd(sb, x, T0, R0, code)
+    for stamp in (torch.full((3,), -1, dtype=torch.int32).pin_memory(),
+                  torch.full((3,), -1, dtype=torch.int32, device=DEV)):
+        T1, R1 = torch.full_like(T0, 7.0), torch.full_like(R0, 7.0)
+        hot.dlrm_emb_interact_fwd_stamped(sb, x, T1, R1, code, stamp, 123456, index=1)
+        torch.cuda.synchronize()
+        assert stamp.cpu().tolist() == [-1, 123456, -1]
+        assert torch.equal(T1.view(torch.int32), T0.view(torch.int32))
+        assert torch.equal(R1.view(torch.int32), R0.view(torch.int32))
+
+
 def test_emb_interact_fwd_fused_refuses_what_it_cannot_do_and_auto_takes_the_separate_calls():
     _say("emb_interact_fwd refusals")
     for K, weighted in ((65, False), (4, True)):
