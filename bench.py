@@ -225,11 +225,10 @@ def main():
         else:
             ev_wait(side, upd_done2[p])
         n_over_np[p] = -1
-        with torch.cuda.stream(side):
-            hot.dlrm_emb_bag_bwd_prepare(dev_batches[i % nb][0], ws2[p])
-            hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[i % nb][0], ws2[p], n_over, index=p)
-            if not use_stamp:
-                ev_record(prep_done2[p], side)
+        hot.dlrm_emb_bag_bwd_prepare(dev_batches[i % nb][0], ws2[p], stream=side)
+        hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[i % nb][0], ws2[p], n_over, index=p, stream=side)
+        if not use_stamp:
+            ev_record(prep_done2[p], side)
     flat_steps = [0]
     t_poll = [0.0]
     poll_wait = [0.0, 0]

@@ -232,22 +232,25 @@ def state_pointers(state: Sequence[torch.Tensor]) -> torch.Tensor:
     return torch.tensor([h.data_ptr() for h in state], dtype=torch.int64, device=state[0].device)
 
 
-def dlrm_emb_bag_bwd_prepare(batch: SparseBatch, workspace: torch.Tensor):
-    """Enqueued on torch's current stream, like every other call."""
+def dlrm_emb_bag_bwd_prepare(batch: SparseBatch, workspace: torch.Tensor,
+                             stream: Optional[torch.cuda.Stream] = None):
+    """Enqueued on `stream`, or like every other call on torch's current stream."""
     ws_bytes = workspace.numel() * workspace.element_size()
     _check("dlrm_emb_bag_bwd_prepare",
-           lib().dlrm_emb_bag_bwd_prepare(batch.ref(), _ptr(workspace), ws_bytes, _stream()))
+           lib().dlrm_emb_bag_bwd_prepare(batch.ref(), _ptr(workspace), ws_bytes,
+                                          _stream() if stream is None else int(stream.cuda_stream)))
 
 
 def dlrm_emb_bag_bwd_prepared_oversized(batch: SparseBatch, workspace: torch.Tensor, out: torch.Tensor,
-                                        index: int = 0):
+                                        index: int = 0, stream: Optional[torch.cuda.Stream] = None):
     """out: int32 tensor the device can write (device memory, or host memory allocated pinned);
     element `index` receives the count once the stream has passed this call."""
     assert out.dtype == torch.int32 and (out.is_cuda or out.is_pinned()) and 0 <= index < out.numel()
     ws_bytes = workspace.numel() * workspace.element_size()
     _check("dlrm_emb_bag_bwd_prepared_oversized",
            lib().dlrm_emb_bag_bwd_prepared_oversized(batch.ref(), _ptr(workspace), ws_bytes,
-                                                     _ptr(out) + 4 * index, _stream()))
+                                                     _ptr(out) + 4 * index,
+                                                     _stream() if stream is None else int(stream.cuda_stream)))
 
 
 def dlrm_emb_bag_bwd_export_groups(batch: SparseBatch, workspace: torch.Tensor,
