@@ -25,6 +25,31 @@ __device__ inline Entry entry_of(const GroupArgs& a, int64_t tbl, uint32_t val) 
   return e;
 }
 
+// A weighted bucket sorted in LDS has its entries resolved once, by all threads at the same time,
+// before any run is summed: the bag replaces the position in the sorted values and the weight goes to
+// LDS beside it, in two pieces (the sort's per-wavefront counters, dead once the sort is done, and
+// an extension for the rest), which keeps four workgroups per compute unit.  Without this every
+// gradient row load waits for two dependent gathers of its own.
+constexpr int kResolvedLo = kNW * kSortBuckets;
+struct ResolvedW {
+  float* lo;  // entries [0, kResolvedLo)
+  float* hi;  // entries [kResolvedLo, kBktCap)
+  __device__ float& at(uint32_t i) const { return i < (uint32_t)kResolvedLo ? lo[i] : hi[i - kResolvedLo]; }
+};
+// RES: vals[i] is the bag and rw.at(i) the weight; otherwise the entry is looked up by vals[i].
+template <bool WT, bool RES>
+__device__ inline Entry entry_at(const GroupArgs& a, int64_t tbl, const uint32_t* vals, uint32_t i,
+                                 const ResolvedW& rw) {
+  if constexpr (WT && RES) {
+    Entry e;
+    e.bag = vals[i];
+    e.w = rw.at(i);
+    return e;
+  } else {
+    return entry_of<WT>(a, tbl, vals[i]);
+  }
+}
+
 // Runs longer than this are summed by the whole workgroup.  With many lane groups per workgroup
 // (narrow rows) a medium run left to one lane group is the critical path of the bucket sooner.
 template <int G>
@@ -35,16 +60,16 @@ __device__ constexpr uint32_t long_run() {
 // Sum (weight times) dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from
 // i0 + first; U loads in flight, ascending order.  vals: LDS or global.  tbl: start of the table
 // in the batch's index array.
-template <int U, bool WT>
+template <int U, bool WT, bool RES>
 __device__ inline f32x4 sum_entries(const GroupArgs& a, int64_t tbl, const float* g, int64_t stride_b,
-                                    const uint32_t* vals, uint32_t i0, uint32_t i1, uint32_t first,
-                                    uint32_t stride) {
+                                    const uint32_t* vals, const ResolvedW& rw, uint32_t i0, uint32_t i1,
+                                    uint32_t first, uint32_t stride) {
   f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
   for (uint32_t i = i0 + first; i < i1; i += U * stride) {
     Entry e[U];
     f32x4 v[U];
 #pragma unroll
-    for (int t = 0; t < U; ++t) e[t] = entry_of<WT>(a, tbl, vals[i + t * stride < i1 ? i + t * stride : i]);
+    for (int t = 0; t < U; ++t) e[t] = entry_at<WT, RES>(a, tbl, vals, i + t * stride < i1 ? i + t * stride : i, rw);
 #pragma unroll
     for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)e[t].bag * stride_b);
 #pragma unroll
@@ -66,11 +91,11 @@ __device__ inline f32x4 sum_entries(const GroupArgs& a, int64_t tbl, const float
 
 // keys/bags: the bucket's sorted pairs (n of them; LDS or global), heads: LDS list of run starts
 // with heads[nruns] = n.  gpos0: global position of the bucket's first pair.
-template <int DT, int G, int OPT, bool WT>
+template <int DT, int G, int OPT, bool WT, bool RES = false>
 __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                    const uint32_t* keys, const uint32_t* bags, const uint32_t* heads,
                                    uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
-                                   int src, float* part) {
+                                   int src, float* part, const ResolvedW& rw = ResolvedW{nullptr, nullptr}) {
   constexpr int NG = kThreads / G;
   // gradient rows a lane group keeps in flight while the workgroup sums a long run: few lane groups
   // (wide rows) need more each to keep the same number of bytes in flight
@@ -99,7 +124,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     }
     Entry e0[RU];
 #pragma unroll
-    for (int t = 0; t < RU; ++t) e0[t] = entry_of<WT>(a, tbl, bags[i0[t]]);
+    for (int t = 0; t < RU; ++t) e0[t] = entry_at<WT, RES>(a, tbl, bags, i0[t], rw);
 #pragma unroll
     for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)e0[t].bag * u.stride_b);
 #pragma unroll
@@ -112,7 +137,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     for (int t = 0; t < RU; ++t) {
       const uint32_t len = i1[t] - i0[t];
       if (r0 + t >= nruns || len > long_run<G>()) continue;
-      if (len > 1) acc[t] += sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
+      if (len > 1) acc[t] += sum_entries<4, WT, RES>(a, tbl, g, u.stride_b, bags, rw, i0[t] + 1, i1[t], 0, 1);
       if (col_ok) row_update_store<DT, OPT>(wp[t], wv[t], acc[t], u);
     }
   }
@@ -140,7 +165,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     RowRef wr = row_ref<DT, OPT>(W, H, u.d, keys[i0], cchunk);
     RowVal wv{};
     if (upd) wv = row_load<DT, OPT>(wr);
-    const f32x4 acc = sum_entries<kLongU, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
+    const f32x4 acc = sum_entries<kLongU, WT, RES>(a, tbl, g, u.stride_b, bags, rw, i0, i1, (uint32_t)grp, (uint32_t)NG);
     __syncthreads();
     if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
     __syncthreads();
@@ -491,6 +516,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
   __shared__ SortLds s;
   __shared__ SplitLds sp;
   __shared__ float part[kThreads * 4];
+  __shared__ float wext[WT ? kBktCap - kResolvedLo : 1];
   uint32_t bid;
   bool listed;
   if (!bucket_id_of_block(a, &bid, &listed)) return;
@@ -499,9 +525,34 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
   char* W = static_cast<char*>(u.tables[b.k]);
   if (b.n <= (uint32_t)kBktCap) {
     sort_bucket_lds(a, b, s);
+    // weighted: the gathers that resolve every sorted entry are in flight while the runs are found
+    uint32_t ebag[WT ? kBktItems : 1];
+    float ew[WT ? kBktItems : 1];
+    if constexpr (WT) {
+      const int64_t tbl = a.tbl_off[b.k];
+#pragma unroll
+      for (int j = 0; j < kBktItems; ++j) {
+        const uint32_t li = threadIdx.x + j * kThreads;
+        const uint32_t pos = li < b.n ? s.sval[li] : s.sval[0];
+        ebag[j] = a.pos_bag[tbl + pos];
+        ew[j] = a.weights[tbl + pos];
+      }
+    }
     const uint32_t nruns = compact_heads_lds(s, (int)b.n);
     const uint32_t nlong = collect_long_runs(s, nruns, long_run<G>());
-    reduce_runs<DT, G, OPT, WT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part);
+    const ResolvedW rw{reinterpret_cast<float*>(&s.wcnt[0][0]), wext};
+    if constexpr (WT) {
+#pragma unroll
+      for (int j = 0; j < kBktItems; ++j) {  // a thread rewrites only the slots it read
+        const uint32_t li = threadIdx.x + j * kThreads;
+        if (li < b.n) {
+          s.sval[li] = ebag[j];
+          rw.at(li) = ew[j];
+        }
+      }
+      __syncthreads();
+    }
+    reduce_runs<DT, G, OPT, WT, WT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part, rw);
     return;
   }
   if (b.low_bits == 0) {  // the bucket holds one row: a single run, already in position order
