@@ -241,7 +241,8 @@ int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* batch, void* const* st
 /*
  * The index-only half of DLRM_BWD_SORT (Sec. 4.1: the indices of a batch are known
  * before its forward pass): partitions the batch's (row, bag) pairs by row inside
- * `workspace`.  It reads indices, offsets, tbl_off and rows only -- no table, no
+ * `workspace`.  It reads indices, offsets, tbl_off, rows and, if the batch has them, the
+ * weights (copied beside the bag of every lookup) -- no table, no
  * gradient -- so a caller may enqueue it on a second stream while the forward pass
  * and the interaction run, then call dlrm_emb_bag_bwd_sgd with
  * algo = DLRM_BWD_SORT_PREPARED, the same batch and the same workspace once both

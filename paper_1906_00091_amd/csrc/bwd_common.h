@@ -11,9 +11,9 @@
 //   3. bucket_scatter : derives the bag of every position from the offsets, then moves the
 //                       (row, bag) pairs to their bucket, stably, staged through LDS.
 //                       Weighted batches (Eq. (2) with its weights) move (row, position) pairs
-//                       instead and keep the bags in a side array in the original order: nothing
-//                       downstream looks inside the second member until a gradient row is
-//                       fetched, where bag and weight are looked up by position.
+//                       instead and keep (bag, weight) records in a side array in the original
+//                       order: nothing downstream looks inside the second member until a gradient
+//                       row is fetched, where bag and weight are looked up by position.
 //   4. bucket_reduce  : one workgroup per (table, top digit): stable LSD radix sort of the
 //                       bucket on the remaining low bits (in LDS when it fits), run heads,
 //                       then a lane group per run sums its dS rows in ascending position
@@ -81,8 +81,8 @@ struct WsLayout {
   size_t hist;               // uint32[kMaxBuckets * nt_max]: per-tile digit counts / offsets
   size_t bucket_start;       // uint32[K * kMaxBuckets + 1]
   size_t tile_heads;         // uint32[nt_max + 1]   (export only)
-  size_t seg_start;          // uint32[nnz + 1]      (export only)
-  size_t seg_tbl;            // uint32[nnz]          (export only)
+  size_t seg_start;          // uint32[nnz + 1]      (export only; a weighted update keeps its nnz
+  size_t seg_tbl;            // uint32[nnz]           8-byte PosEntry records across these two)
   size_t n_seg;              // uint32[4]            (export only)
   size_t huge_ctr;           // uint32[4]: [2] = listed (heavy) buckets, [3] = oversized buckets among them
   size_t hot_cnt;            // uint32[K]: queued hot runs per table
@@ -94,6 +94,13 @@ struct WsLayout {
   size_t total;
   int64_t nt_max;            // upper bound on the number of tiles
   int64_t max_huge;          // upper bound on the number of queued runs
+};
+
+// Weighted batches: what one lookup contributes besides its row, found by its position with one
+// 8-byte load.
+struct alignas(8) PosEntry {
+  uint32_t bag;
+  float w;  // the weight a of Eq. (2)
 };
 
 struct SegInfo {
@@ -150,7 +157,7 @@ struct GroupArgs {            // everything the grouping kernels need
   const int64_t* rows;
   int32_t idx32;
   const float* weights;       // NULL, or the weight of every lookup (parallel to indices)
-  uint32_t* pos_bag;          // weighted batches: bag of every position, in the original order
+  PosEntry* pos_entry;        // weighted batches: bag and weight of every position, in the original order
   int32_t K, B;
   int32_t nt_max;
   int32_t top_bits;           // bits of the partition digit (0..kMaxTopBits)
@@ -503,7 +510,8 @@ inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.bucket_start = reinterpret_cast<uint32_t*>(base + L.bucket_start);
   g.tile_heads = reinterpret_cast<uint32_t*>(base + L.tile_heads);
   g.seg_start = reinterpret_cast<uint32_t*>(base + L.seg_start);
-  g.pos_bag = g.seg_start;  // the export arrays are idle during an update
+  // the two export arrays, idle during an update and adjacent in the layout, hold the nnz records
+  g.pos_entry = reinterpret_cast<PosEntry*>(base + L.seg_start);
   g.seg_tbl = reinterpret_cast<uint32_t*>(base + L.seg_tbl);
   g.n_seg = reinterpret_cast<uint32_t*>(base + L.n_seg);
   g.hot_cnt = reinterpret_cast<uint32_t*>(base + L.hot_cnt);

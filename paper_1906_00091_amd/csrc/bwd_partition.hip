@@ -211,7 +211,10 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
     const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
     val[j] = ok[j] ? sval[li] : 0u;
     if (a.weights != nullptr && ok[j]) {  // uniform branch: weighted batch
-      a.pos_bag[ti.start + li] = val[j];
+      PosEntry pe;
+      pe.bag = val[j];
+      pe.w = a.weights[ti.start + li];
+      a.pos_entry[ti.start + li] = pe;
       val[j] = (uint32_t)(P0 + li);       // position inside the table
     }
   }

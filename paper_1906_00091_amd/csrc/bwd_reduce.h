@@ -16,8 +16,9 @@ template <bool WT>
 __device__ inline Entry entry_of(const GroupArgs& a, int64_t tbl, uint32_t val) {
   Entry e;
   if constexpr (WT) {
-    e.bag = a.pos_bag[tbl + val];
-    e.w = a.weights[tbl + val];
+    const PosEntry pe = a.pos_entry[tbl + val];
+    e.bag = pe.bag;
+    e.w = pe.w;
   } else {
     e.bag = val;
     e.w = 1.0f;
@@ -534,8 +535,9 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
       for (int j = 0; j < kBktItems; ++j) {
         const uint32_t li = threadIdx.x + j * kThreads;
         const uint32_t pos = li < b.n ? s.sval[li] : s.sval[0];
-        ebag[j] = a.pos_bag[tbl + pos];
-        ew[j] = a.weights[tbl + pos];
+        const PosEntry pe = a.pos_entry[tbl + pos];
+        ebag[j] = pe.bag;
+        ew[j] = pe.w;
       }
     }
     const uint32_t nruns = compact_heads_lds(s, (int)b.n);

@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
         uint32_t lo = 0, hi = hr.len;
         while (lo < hi) {
           const uint32_t mid = (lo + hi) >> 1;
-          const uint32_t bm = WT ? a.pos_bag[tbl + bags[mid]] : bags[mid];
+          const uint32_t bm = WT ? a.pos_entry[tbl + bags[mid]].bag : bags[mid];
           if (bm < bound) lo = mid + 1; else hi = mid;
         }
         c = hr.start + lo;
@@ -230,8 +230,9 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
             uint32_t moff = (uint32_t)kHotTileFloats;  // entries past the end: the row of zeros, weight 0
             float mw = 0.0f;
             if ((uint32_t)lane < cnt) {
-              moff = (a.pos_bag[tbl + cur] - (uint32_t)tb0) * (uint32_t)u.d;
-              mw = a.weights[tbl + cur];
+              const PosEntry pe = a.pos_entry[tbl + cur];
+              moff = (pe.bag - (uint32_t)tb0) * (uint32_t)u.d;
+              mw = pe.w;
             }
             for (uint32_t e = 0; e < cnt; e += HU * S) {
               f32x4 v[HU];
