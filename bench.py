@@ -22,7 +22,8 @@ METRIC = "emb-bag fwd+bwd lookups/s & HBM GB/s (% of peak); samples/s at batch 2
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by the same counters on the 1 GiB --copy-calib kernel;
-# the summaries are under profiles/.  Keyed by (workload, kernel).
+# the summaries are under profiles/.  Keyed by (workload, kernel); measured with sum pooling and SGD
+# (the Adagrad and weighted variants report null).
 MEASURED_TRAFFIC = {(3, "bucket_reduce_kernel"): 806.7e6, (3, "emb_fwd_kernel"): 440.6e6,
                     (5, "bucket_reduce_kernel"): 8.28e9, (5, "emb_fwd_kernel"): 2.29e9}
 
@@ -476,7 +477,7 @@ def main():
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((args.config, dom)) if not adagrad else None,
+                "traffic": MEASURED_TRAFFIC.get((args.config, dom)) if not (adagrad or args.weighted) else None,
                 "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_ms": round(dom_ms, 5),
                 "launch_timing": ("HIP event pair recorded by the library on the launch stream around every %d-th "
                                   "launch of the timed region (each pair costs the step about 10 us)"
