@@ -136,3 +136,35 @@ def test_random_shape_forward_and_update_match_oracle(c):
             assert rel_err(got_h[u], ref_h[k][u], h0[k][u] + S * S) <= 1e-5
             assert rel_err(gw, rw, w0 + lr * S / (np.sqrt(h0[k][u].astype(np.float64)) + eps),
                            SCALE_FLOOR[dtype]) <= TOL[dtype]
+
+
+def _draw_interaction(i):
+    rng = np.random.default_rng(9000 + i)
+    F = int(rng.integers(1, 129))
+    d = 4 * int(rng.integers(1, 65))
+    B = int(np.exp(rng.uniform(0.0, np.log(max(2.0, 2.0e7 / (F * d))))))
+    return B, F, d
+
+
+INTERACTIONS = [_draw_interaction(i) for i in range(24)]
+
+
+@pytest.mark.parametrize("B,F,d", INTERACTIONS)
+def test_random_shape_interaction_matches_oracle(B, F, d):
+    """Sec. 2.2: dots of all distinct pairs of the F vectors, the dense vector copied in front; and the
+    transpose of that map applied to an upstream gradient."""
+    print("[case] random interaction B=%d F=%d d=%d" % (B, F, d), flush=True)
+    rng = np.random.default_rng(B * 1000 + F)
+    P = F * (F - 1) // 2
+    T = rng.standard_normal((B, F, d)).astype(np.float32)
+    dR = rng.standard_normal((B, d + P)).astype(np.float32)
+    Td = torch.from_numpy(T).to(DEV)
+    R = torch.full((B, d + P), -5.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_interact_dot_fwd(Td, R)
+    got = R.cpu().numpy()
+    assert np.array_equal(got[:, :d].view(np.uint32), T[:, 0, :].view(np.uint32))
+    assert rel_err(got, oracle.interact_dot_fwd(T), oracle.interact_dot_fwd(np.abs(T))) <= 1e-5
+    dT = torch.full((B, F, d), -5.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_interact_dot_bwd(Td, torch.from_numpy(dR).to(DEV), dT)
+    assert rel_err(dT.cpu().numpy(), oracle.interact_dot_bwd(T, dR),
+                   oracle.interact_dot_bwd(np.abs(T), np.abs(dR))) <= 1e-5
