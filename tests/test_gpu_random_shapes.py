@@ -96,11 +96,29 @@ def test_random_shape_forward_and_update_match_oracle(c):
         assert np.array_equal(t1[:, 0, :].view(np.uint32), x.view(np.uint32))
         assert rel_err(R1.cpu().numpy(), oracle.interact_dot_fwd(t1), oracle.interact_dot_fwd(np.abs(t1))) <= 1e-5
 
+    # ---- the grouping of the lookups by row (index work: bit-exact)
+    ws = hot.alloc_workspace(sb)
+    n = max(b.nnz, 1)
+    uniq = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    seg = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    sbag = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+    nu = torch.full((K,), -1, dtype=torch.int64, device=DEV)
+    hot.dlrm_emb_bag_bwd_export_groups(sb, ws, uniq, seg, sbag, nu)
+    torch.cuda.synchronize()
+    uniq, seg, sbag, nu = uniq.cpu().numpy(), seg.cpu().numpy(), sbag.cpu().numpy(), nu.cpu().numpy()
+    groups = oracle.group_rows(b.indices, b.offsets, b.tbl_off)
+    for k in range(K):
+        a0, a1 = int(b.tbl_off[k]), int(b.tbl_off[k + 1])
+        wu, wseg, wpos, wbag = groups[k]
+        assert int(nu[k]) == len(wu)
+        assert np.array_equal(uniq[a0:a0 + len(wu)], wu)
+        assert np.array_equal(seg[a0:a0 + len(wu)], wseg)
+        assert np.array_equal(sbag[a0:a1], wbag)
+
     # ---- backward fused with the row update (Sec. 5.1: SGD or Adagrad)
     dS = b.dS()
     dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
     dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
-    ws = hot.alloc_workspace(sb)
     lr, eps = float(np.float32(0.05)), float(np.float32(1e-8))
     ref_w = [t.copy() for t in host]
     sg = [np.zeros((int(r), d), dtype=np.float32) for r in b.rows]  # sum of the terms' magnitudes per row
