@@ -49,7 +49,23 @@ def _draw_case(i):
                 opt=opt)
 
 
-CASES = [_draw_case(i) for i in range(N_CASES)]
+def _draw_large_case(i):
+    """Millions of lookups on narrow rows: many partition tiles, the separate scan, buckets past the LDS
+    sort, with whatever the draw makes of hot rows."""
+    rng = np.random.default_rng(8000 + i)
+    K = int(rng.integers(1, 4))
+    d = 4 * int(rng.integers(1, 5))
+    dtype = gen.F32 if d % 8 else [gen.F32, gen.F16, gen.BF16][int(rng.integers(0, 3))]
+    rows = int(np.exp(rng.uniform(np.log(1000.0), np.log(4.0e6))))
+    n = int(rng.integers(24, 100))
+    bag = ("fixed", n) if rng.random() < 0.5 else ("uniform", 0, 2 * n)
+    dist = ("uniform",) if rng.random() < 0.5 else ("zipf", float(rng.uniform(1.05, 1.3)))
+    B = int(rng.uniform(1.0e6, 3.5e6) / (K * n))
+    return dict(K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, weighted=bool(rng.random() < 0.5),
+                index32=bool(rng.random() < 0.5), opt="adagrad" if rng.random() < 0.5 else "sgd")
+
+
+CASES = [_draw_case(i) for i in range(N_CASES)] + [_draw_large_case(i) for i in range(6)]
 
 
 def _id(c):
