@@ -64,7 +64,50 @@ def parse_args():
     ap.add_argument("--copy-calib", action="store_true",
                     help="run a 1 GiB plain copy (place_dense with F=1) before the timed region, as the "
                          "known-size reference for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of a workload, time the library's plain memory kernels (stream copy and "
+                         "read, random whole-row gather and read-modify-write) and print what this board "
+                         "sustains for each pattern, one JSON line")
     return ap.parse_args()
+
+
+def measure_ceilings(torch, hot, reps=20):
+    """GB/s of the measurement kernels: 4 GiB streamed; 1.5 GB of distinct random rows out of a 2 GiB
+    table for the row patterns (HIP events around `reps` back-to-back launches on the current stream)."""
+    dev = "cuda:0"
+    sink = hot.ceiling_sink()
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps   # ms
+
+    out = {}
+    n = 1 << 30                                   # fp32 elements: 4 GiB
+    src = torch.ones(n, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    out["stream_copy"] = round(2 * 4 * n / timed(lambda: hot.dlrm_ceiling_copy(src, dst)) / 1e6, 1)
+    out["stream_read"] = round(4 * n / timed(lambda: hot.dlrm_ceiling_read(src, sink)) / 1e6, 1)
+    del dst
+    table = src[: n // 2]                          # 2 GiB
+    g = torch.Generator(device=dev).manual_seed(1)
+    for row_bytes in (64, 256, 512):
+        nrows = table.numel() * 4 // row_bytes
+        take = int(1.5e9) // row_bytes
+        rows = torch.randperm(nrows, generator=g, device=dev)[:take].to(torch.int32)
+        ms = timed(lambda: hot.dlrm_ceiling_gather(table, rows, row_bytes, sink))
+        out["row_gather_%dB" % row_bytes] = round(take * row_bytes / ms / 1e6, 1)
+        if row_bytes != 64:
+            ms = timed(lambda: hot.dlrm_ceiling_rmw(table, rows, row_bytes))
+            out["row_rmw_%dB" % row_bytes] = round(2 * take * row_bytes / ms / 1e6, 1)
+        del rows
+    return out
 
 
 def algorithmic_bytes(w, batch, elem_bytes, index_bytes=8, weighted=False):
@@ -100,6 +143,12 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.ceilings:
+        print(json.dumps({"board_ceilings": measure_ceilings(torch, hot), "unit": "GB/s",
+                          "what": "bytes read + bytes written per second by the library's measurement "
+                                  "kernels: 4 GiB streamed; 1.5 GB of distinct random rows of a 2 GiB table, "
+                                  "four rows in flight per lane group", "nominal_hbm_peak": HBM_PEAK_GBPS}))
+        return
     w = gen.WORKLOADS[args.config]
     eb = gen.ELEM_BYTES[w.dtype]
     algo = {"auto": hot.BWD_AUTO, "sort": hot.BWD_SORT, "atomic": hot.BWD_ATOMIC}[args.algo]
@@ -530,6 +579,16 @@ def main():
             "interact_dot_bwd": round(mean("int_bwd") / (stage_ms["interact_dot_bwd"] * 1e-3) / 1e9, 1)},
         "roofline": roofline,
     }
+
+    # ---- what this board sustains for the dominant kernel's access pattern (a few seconds, 8 GiB)
+    if not args.no_cpu_baseline:
+        ceil = measure_ceilings(torch, hot)
+        row_bytes = 512 if d * eb > 256 else 256   # the row patterns are measured at 64, 256 and 512 bytes
+        pattern = ("row_rmw_%dB" if dom == "bucket_reduce_kernel" else "row_gather_%dB") % row_bytes
+        out["board_ceilings"] = dict(ceil, unit="GB/s", note="the library's plain memory kernels on this board: "
+                                     "4 GiB streamed; 1.5 GB of distinct random rows of a 2 GiB table")
+        roofline["board_ceiling"] = {"pattern": pattern, "GBps": ceil[pattern],
+                                     "frac": round(achieved / ceil[pattern], 4)}
 
     # ---- CPU baseline: the oracle as it stands, on this machine's host cores, same workload
     if not args.no_cpu_baseline and not args.weighted:

@@ -85,6 +85,16 @@ def lib() -> C.CDLL:
         L.dlrm_profile_reduce_kernel.argtypes = [vp, vp]
         L.dlrm_table_init_hash.restype = i32
         L.dlrm_table_init_hash.argtypes = [vp, i64, i32, i32, C.c_uint64, f32, vp]
+        L.dlrm_ceiling_sink_floats.restype = i32
+        L.dlrm_ceiling_sink_floats.argtypes = []
+        L.dlrm_ceiling_copy.restype = i32
+        L.dlrm_ceiling_copy.argtypes = [vp, vp, sz, vp]
+        L.dlrm_ceiling_read.restype = i32
+        L.dlrm_ceiling_read.argtypes = [vp, sz, vp, vp]
+        L.dlrm_ceiling_gather.restype = i32
+        L.dlrm_ceiling_gather.argtypes = [vp, vp, i64, i32, vp, vp]
+        L.dlrm_ceiling_rmw.restype = i32
+        L.dlrm_ceiling_rmw.argtypes = [vp, vp, i64, i32, vp]
         _lib = L
     return _lib
 
@@ -273,6 +283,46 @@ def dlrm_table_init_hash(table: torch.Tensor, table_dtype: int, key: int, scale:
 def dlrm_profile_reduce_kernel(ev_start: Optional[int], ev_stop: Optional[int]):
     """ev_start / ev_stop: raw hipEvent_t handles (ints) or None, None to clear."""
     _check("dlrm_profile_reduce_kernel", lib().dlrm_profile_reduce_kernel(ev_start, ev_stop))
+
+
+def _nbytes(t: torch.Tensor) -> int:
+    assert t.is_contiguous()
+    return t.numel() * t.element_size()
+
+
+def ceiling_sink() -> torch.Tensor:
+    """Scratch output of the read-only measurement kernels."""
+    return torch.empty(int(lib().dlrm_ceiling_sink_floats()), dtype=torch.float32, device="cuda")
+
+
+def dlrm_ceiling_copy(src: torch.Tensor, dst: torch.Tensor):
+    assert _nbytes(src) == _nbytes(dst)
+    _check("dlrm_ceiling_copy", lib().dlrm_ceiling_copy(_ptr(src), _ptr(dst), _nbytes(src), _stream()))
+
+
+def dlrm_ceiling_read(src: torch.Tensor, sink: torch.Tensor):
+    assert sink.dtype == torch.float32 and sink.numel() >= int(lib().dlrm_ceiling_sink_floats())
+    _check("dlrm_ceiling_read", lib().dlrm_ceiling_read(_ptr(src), _nbytes(src), _ptr(sink), _stream()))
+
+
+def _rows_arg(table: torch.Tensor, rows: torch.Tensor, row_bytes: int) -> int:
+    # row numbers as uint32 bit patterns in an int32 tensor; the caller keeps them below the row count
+    assert rows.dtype == torch.int32 and rows.is_contiguous() and rows.numel() >= 1
+    assert _nbytes(table) % row_bytes == 0
+    return rows.numel()
+
+
+def dlrm_ceiling_gather(table: torch.Tensor, rows: torch.Tensor, row_bytes: int, sink: torch.Tensor):
+    assert sink.dtype == torch.float32 and sink.numel() >= int(lib().dlrm_ceiling_sink_floats())
+    n = _rows_arg(table, rows, row_bytes)
+    _check("dlrm_ceiling_gather",
+           lib().dlrm_ceiling_gather(_ptr(table), _ptr(rows), n, row_bytes, _ptr(sink), _stream()))
+
+
+def dlrm_ceiling_rmw(table: torch.Tensor, rows: torch.Tensor, row_bytes: int):
+    """Scales the fp32 elements of the listed (distinct) rows by 1 + 2^-10 in place."""
+    n = _rows_arg(table, rows, row_bytes)
+    _check("dlrm_ceiling_rmw", lib().dlrm_ceiling_rmw(_ptr(table), _ptr(rows), n, row_bytes, _stream()))
 
 
 def alloc_workspace(batch: SparseBatch) -> torch.Tensor:

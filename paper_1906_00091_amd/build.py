@@ -13,7 +13,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libdlrm_hot.so")
 SOURCES = ["bwd_reduce_sgd.hip", "bwd_reduce_adagrad.hip", "bwd_reduce_sgd_weighted.hip",
            "bwd_reduce_adagrad_weighted.hip", "bwd_tail.hip", "bwd_partition.hip", "bwd_export.hip",
-           "emb_bwd.hip", "emb_fwd.hip", "interact.hip","pooled_interact.hip", "util.hip"]
+           "emb_bwd.hip", "emb_fwd.hip", "interact.hip", "pooled_interact.hip", "util.hip", "ceilings.hip"]
 
 # -packed-fp32-ops: keep hipcc from forming packed fp32 VALU instructions.
 HIPCC_FLAGS = [

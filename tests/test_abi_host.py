@@ -124,6 +124,23 @@ def test_interaction_and_helpers_reject_bad_arguments_on_the_host():
     assert L.dlrm_table_init_hash(p, 10, 6, 0, C.c_uint64(1), C.c_float(1.0), None) == -2
 
 
+def test_measurement_kernels_reject_bad_arguments_on_the_host():
+    L = hot.lib()
+    p = C.c_void_p(0x1000)
+    assert L.dlrm_ceiling_sink_floats() >= 4096
+    assert L.dlrm_ceiling_copy(None, p, 64, None) == -1
+    assert L.dlrm_ceiling_copy(p, p, 0, None) == -2
+    assert L.dlrm_ceiling_copy(p, p, 24, None) == -2
+    assert L.dlrm_ceiling_copy(C.c_void_p(0x1004), p, 64, None) == -2
+    assert L.dlrm_ceiling_read(p, 64, None, None) == -1
+    assert L.dlrm_ceiling_read(p, 8, p, None) == -2
+    assert L.dlrm_ceiling_gather(p, None, 4, 256, p, None) == -1
+    assert L.dlrm_ceiling_gather(p, p, 0, 256, p, None) == -2
+    assert L.dlrm_ceiling_gather(p, p, 4, 100, p, None) == -2
+    assert L.dlrm_ceiling_rmw(None, p, 4, 256, None) == -1
+    assert L.dlrm_ceiling_rmw(p, p, 4, 1024, None) == -2
+
+
 def test_binding_raises_instead_of_falling_back():
     with pytest.raises(hot.DlrmError):
         binding._check("dlrm_emb_bag_fwd", -2)

@@ -865,3 +865,28 @@ def test_empty_batch_is_a_no_op():
     hot.dlrm_emb_bag_bwd_sgd(sb, out, 8, 4, 0.1, ws, algo=hot.BWD_ATOMIC)
     for k in range(2):
         assert np.array_equal(tables[k].cpu().numpy(), host[k])
+
+
+# ------------------------------------------------------------------ measurement kernels
+@pytest.mark.parametrize("row_bytes", [64, 128, 256, 512])
+def test_measurement_kernels_move_the_bytes_they_claim(row_bytes):
+    """The kernels a benchmark times for the board's ceilings: the copy copies, the row update touches
+    exactly the listed rows (one fp32 multiply by 1 + 2^-10 each), the read-only ones change nothing."""
+    _say("ceiling kernels, rows of %d bytes" % row_bytes)
+    g = torch.Generator(device="cpu").manual_seed(row_bytes)
+    nrows, w = 5003, row_bytes // 4
+    table = torch.randn((nrows, w), generator=g).to(DEV)
+    before = table.clone()
+    rows = torch.randperm(nrows, generator=g)[:3001].to(torch.int32).to(DEV)   # distinct, ragged count
+    sink = hot.ceiling_sink()
+    hot.dlrm_ceiling_gather(table, rows, row_bytes, sink)
+    hot.dlrm_ceiling_read(table, sink)
+    assert torch.equal(table, before)
+    hot.dlrm_ceiling_rmw(table, rows, row_bytes)
+    want = before.clone()
+    sel = rows.long()
+    want[sel] = before[sel] * torch.tensor(1.0 + 2.0 ** -10, dtype=torch.float32, device=DEV)
+    assert torch.equal(table, want)
+    dst = torch.zeros_like(table)
+    hot.dlrm_ceiling_copy(table, dst)
+    assert torch.equal(dst, table)
