@@ -176,6 +176,8 @@ PI_CASES = [
     ("k1-b1-d4", 1, 1, 4, gen.F32, 3, ("fixed", 2), ("uniform",), False),
     ("mostly-empty", 5, 66, 32, gen.F32, 30, ("uniform", 0, 1), ("uniform",), False),
     ("long-bags-forced", 3, 20, 64, gen.F32, 400, ("uniform", 0, 40), ("uniform",), False),
+    # four-row bags of 104 floats: the three-call path pools them with a wavefront per bag
+    ("fixed4-d104", 17, 48, 104, gen.F32, 146, ("fixed", 4), ("zipf", 1.1), False),
 ]
 
 
@@ -207,7 +209,12 @@ def test_emb_interact_fwd_fused_matches_oracle_and_the_separate_calls(case):
         # the pairs are products of the fp32 T this path wrote
         assert rel_err(R, oracle.interact_dot_fwd(T), scale_interact_fwd(T)) <= 1e-5
         assert rel_err(R, wantR, scale_interact_fwd(scaleT_pad(scaleT, x))) <= 1e-5
-    if bag[-1] <= 4:   # short bags: both paths add a bag's rows one by one in position order
+    # short bags: both paths add a bag's rows one by one in position order, unless the three-call path
+    # gives every bag a whole wavefront (mean bag >= twice the lane groups a wavefront holds), where
+    # the lane groups' partial sums meet in a butterfly
+    groups = 64 // min(64, 1 << int(np.ceil(np.log2(d * gen.ELEM_BYTES[dtype] / 16.0))))
+    wavefront_per_bag = groups > 1 and b.nnz / float(K * B) >= 2 * groups
+    if bag[-1] <= 4 and not wavefront_per_bag:
         assert np.array_equal(got[hot.FWD_FUSED][0].view(np.uint32), got[hot.FWD_SPLIT][0].view(np.uint32))
     for k, bb in np.argwhere(b.lengths == 0):
         assert np.all(got[hot.FWD_FUSED][0][bb, k + 1].view(np.uint32) == 0)     # +0.0 exactly
