@@ -65,7 +65,15 @@ def _draw_large_case(i):
                 index32=bool(rng.random() < 0.5), opt="adagrad" if rng.random() < 0.5 else "sgd")
 
 
-CASES = [_draw_case(i) for i in range(N_CASES)] + [_draw_large_case(i) for i in range(6)]
+# hundreds of tables with enough lookups for the separate scan (one workgroup per table there)
+MANY_TABLES = [
+    dict(K=600, B=1000, d=8, dtype=gen.F32, rows=3000, bag=("fixed", 8), dist=("zipf", 1.2), weighted=False,
+         index32=False, opt="sgd"),
+    dict(K=700, B=900, d=16, dtype=gen.F16, rows=50, bag=("uniform", 0, 20), dist=("uniform",), weighted=True,
+         index32=True, opt="adagrad"),
+]
+
+CASES = [_draw_case(i) for i in range(N_CASES)] + [_draw_large_case(i) for i in range(6)] + MANY_TABLES
 
 
 def _id(c):
