@@ -214,6 +214,9 @@ size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t
  * stride_k = d); 16-byte aligned rows.
  * workspace: device memory, 256-byte aligned, at least
  * dlrm_emb_bag_bwd_workspace_bytes(...) bytes; contents are scratch.
+ * d <= 256 (a gradient row of d fp32 values is at most one wavefront of 16-byte pieces): fp16/bf16
+ * tables with 256 < d <= 512 can be pooled but not updated (DLRM_ERR_BAD_SHAPE, here and in
+ * dlrm_emb_bag_bwd_adagrad and dlrm_emb_bag_bwd_prepare).
  */
 int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
                              int64_t stride_k, float lr, void* workspace, size_t workspace_bytes,

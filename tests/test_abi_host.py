@@ -104,6 +104,12 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert ada(_batch(), C.c_void_p(0x1000), 0.0, hot.BWD_SORT) == -2   # eps must be positive
     assert ada(_batch(), C.c_void_p(0x1000), 1e-8, hot.BWD_ATOMIC) == -5
     assert call(_batch(table_dtype=1), C.c_void_p(0x1000), need, hot.BWD_ATOMIC) == -3
+    # a gradient row is d fp32 values and one wavefront wide at most: fp16 rows of 512 elements can be
+    # pooled but not updated
+    wide = lambda: _batch(d=512, table_dtype=1)
+    assert L.dlrm_emb_bag_bwd_sgd(C.byref(wide()), ds, 3 * 512, 512, C.c_float(0.01), C.c_void_p(0x1000),
+                                  1 << 30, hot.BWD_SORT, None) == -2
+    assert prep(wide(), C.c_void_p(0x1000), 1 << 30) == -2
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(0, 4, 16, 8, 100, 0) == 0
     assert hot.dlrm_emb_bag_bwd_workspace_bytes(2, 4, 16, 8, 100, 5) == 0
     # workspace grows with the number of lookups

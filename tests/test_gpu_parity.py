@@ -84,6 +84,9 @@ FWD_CASES = [
     ("d256-fullwave", 2, 19, 256, gen.F32, 100, ("uniform", 0, 9), ("uniform",)),
     ("f16-d128-fixed32", 4, 200, 128, gen.F16, 20000, ("fixed", 32), ("zipf", 1.2)),
     ("f16-d8", 2, 50, 8, gen.F16, 64, ("uniform", 0, 6), ("uniform",)),
+    # the widest low-precision rows (1024 bytes): short and long bags
+    ("f16-d512", 3, 70, 512, gen.F16, 500, ("uniform", 0, 12), ("uniform",)),
+    ("bf16-d384-long-bags", 2, 9, 384, gen.BF16, 500, ("uniform", 0, 300), ("uniform",)),
     ("bf16-d64", 3, 90, 64, gen.BF16, 700, ("uniform", 0, 70), ("uniform",)),
     ("one-row-table", 2, 20, 16, gen.F32, 1, ("uniform", 0, 5), ("uniform",)),
     ("300-tables", 300, 40, 8, gen.F32, 60, ("uniform", 0, 6), ("zipf", 1.1)),
@@ -178,6 +181,7 @@ PI_CASES = [
     ("long-bags-forced", 3, 20, 64, gen.F32, 400, ("uniform", 0, 40), ("uniform",), False),
     # four-row bags of 104 floats: the three-call path pools them with a wavefront per bag
     ("fixed4-d104", 17, 48, 104, gen.F32, 146, ("fixed", 4), ("zipf", 1.1), False),
+    ("f16-d512", 5, 40, 512, gen.F16, 300, ("uniform", 0, 3), ("uniform",), False),
 ]
 
 
