@@ -158,6 +158,17 @@ def test_config5_hotrow_stress():
     _check_config(5)
 
 
+def test_tables_with_the_largest_row_count():
+    """m_k = 2^31 - 1 rows (the documented maximum; 2 x 34 GB of fp32 rows of 4): row numbers that use
+    every bit of the sort keys, byte offsets far past 2^32."""
+    gen.WORKLOADS[99] = gen.custom_workload("max-rows", K=2, B=4096, d=4, rows=2 ** 31 - 1, bag=("uniform", 0, 6),
+                                            dist=("uniform",), seed=3)
+    try:
+        _check_config(99)
+    finally:
+        del gen.WORKLOADS[99]
+
+
 def _check_adagrad_config(cfg_id, h_init=0.1, steps=2):
     """The Adagrad backward at a workload's full size, in the launch configuration the benchmark
     uses (grouping prepared on a second stream for >= 200K lookups): two steps with the same
