@@ -66,6 +66,7 @@ extern "C" {
 #define DLRM_MAX_ROWS 2147483647LL      /* m_k < 2^31 */
 #define DLRM_MAX_NNZ 2147483647LL       /* total lookups per batch < 2^31 */
 #define DLRM_MAX_INTERACT_F 128         /* F <= 128 */
+/* also: K * (B + 1) <= DLRM_MAX_NNZ (bags are numbered in 32 bits); the backward needs d <= 256 */
 
 /*
  * One mini-batch of sparse lookups for all K tables (Sec. 2.1.1, Eq. (2);

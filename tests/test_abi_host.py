@@ -71,6 +71,13 @@ def test_one_call_forward_rejects_bad_arguments_on_the_host():
     assert st(_batch(), x=None, stamp=C.c_void_p(0x1000)) == -1
 
 
+def test_more_bags_than_32_bits_number_is_rejected():
+    L = hot.lib()
+    p = C.c_void_p(0x1000)
+    assert L.dlrm_emb_bag_fwd(C.byref(_batch(K=64, B=(1 << 25))), p, 64 * 16, 16, None) == -2
+    assert L.dlrm_emb_bag_fwd(C.byref(_batch(K=1 << 20, B=1 << 12)), p, 64 * 16, 16, None) == -2
+
+
 def test_unknown_index_dtype_is_rejected():
     L = hot.lib()
     # (no output pointer: a known index type gets as far as that check, nothing is launched)
