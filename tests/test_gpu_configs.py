@@ -236,3 +236,56 @@ def test_config3_multihot_bandwidth_adagrad():
 
 def test_config2_clicklog_onehot_adagrad():
     _check_adagrad_config(2)
+
+
+def test_the_largest_lookup_count():
+    """nnz = 2^31 - 1 lookups (the documented maximum) in one table: 2^20 bags of 2047 rows and one of a
+    million, rows drawn uniformly from 2^23.  The oracle would take hours; with tables and gradients of
+    zeros, ones and a parity bit every sum is a count, exact in fp32 in any order, and torch's integer ops
+    on the device give the expected counts.  About 110 GB of device memory."""
+    _say("largest lookup count")
+    B, m, d = 1 << 20, 1 << 23, 4
+    nnz = (1 << 31) - 1
+    lengths = torch.full((1, B), 2047, dtype=torch.int32, device=DEV)
+    lengths[0, B - 1] += nnz - 2047 * B
+    offsets = torch.empty((1, B + 1), dtype=torch.int64, device=DEV)
+    tbl_off = torch.empty(2, dtype=torch.int64, device=DEV)
+    hot.dlrm_lengths_to_offsets(lengths, offsets, tbl_off)
+    torch.cuda.synchronize()
+    assert int(tbl_off[1]) == nnz and int(offsets[0, B]) == nnz
+    g = torch.Generator(device=DEV).manual_seed(7)
+    idx = torch.randint(0, m, (nnz,), generator=g, device=DEV, dtype=torch.int64)
+    parity = (torch.arange(m, device=DEV) & 1)
+    W = torch.ones((m, d), dtype=torch.float32, device=DEV)
+    W[:, 1] = parity.float()
+    sb = hot.SparseBatch([W], hot.F32, idx, offsets, tbl_off, nnz)
+    n_bad = torch.zeros(1, dtype=torch.int64, device=DEV)
+    hot.dlrm_validate_csr(sb, n_bad)
+    assert int(n_bad.item()) == 0
+    _say("forward")
+    S = torch.empty((B, 1, d), dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_bag_fwd(sb, S, d, d)
+    torch.cuda.synchronize()
+    want_len = lengths[0].float()                      # every bag length is below 2^24
+    assert torch.equal(S[:, 0, 0], want_len) and torch.equal(S[:, 0, 2], want_len)
+    odd = torch.cumsum(idx & 1, 0)
+    ends = odd[offsets[0, 1:] - 1]
+    cnt_odd = ends - torch.cat([torch.zeros(1, dtype=torch.int64, device=DEV), ends[:-1]])
+    assert torch.equal(S[:, 0, 1], cnt_odd.float())
+    del odd, ends, cnt_odd, S
+    _say("backward")
+    lr = 2.0 ** -22                                    # count * lr and 1 - count * lr are exact in fp32
+    dS = torch.zeros((B, 1, d), dtype=torch.float32, device=DEV)
+    dS[:, 0, 0] = 1.0
+    dS[B - 1, 0, 1] = 1.0
+    ws = hot.alloc_workspace(sb)
+    hot.dlrm_emb_bag_bwd_sgd(sb, dS, d, d, lr, ws)
+    torch.cuda.synchronize()
+    del ws
+    count = torch.bincount(idx, minlength=m)
+    assert int(count.sum()) == nnz
+    assert torch.equal(W[:, 0], (1.0 - count.double() * lr).float())
+    last = torch.bincount(idx[int(offsets[0, B - 1]):], minlength=m)
+    assert torch.equal(W[:, 1], (parity.double() - last.double() * lr).float())
+    assert bool(torch.all(W[:, 2] == 1.0)) and bool(torch.all(W[:, 3] == 1.0))
+    _say("ok")
