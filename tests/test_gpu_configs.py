@@ -161,6 +161,7 @@ def test_config5_hotrow_stress():
 def test_tables_with_the_largest_row_count():
     """m_k = 2^31 - 1 rows (the documented maximum; 2 x 34 GB of fp32 rows of 4): row numbers that use
     every bit of the sort keys, byte offsets far past 2^32."""
+    torch.cuda.empty_cache()
     gen.WORKLOADS[99] = gen.custom_workload("max-rows", K=2, B=4096, d=4, rows=2 ** 31 - 1, bag=("uniform", 0, 6),
                                             dist=("uniform",), seed=3)
     try:
@@ -244,6 +245,7 @@ def test_the_largest_lookup_count():
     zeros, ones and a parity bit every sum is a count, exact in fp32 in any order, and torch's integer ops
     on the device give the expected counts.  About 110 GB of device memory."""
     _say("largest lookup count")
+    torch.cuda.empty_cache()   # blocks cached from the earlier tests go back to the device first
     B, m, d = 1 << 20, 1 << 23, 4
     nnz = (1 << 31) - 1
     lengths = torch.full((1, B), 2047, dtype=torch.int32, device=DEV)
