@@ -277,6 +277,22 @@ int32_t dlrm_emb_bag_bwd_prepared_oversized(const dlrm_sparse_batch* batch, void
                                             size_t workspace_bytes, uint32_t* n_oversized, void* stream);
 
 /*
+ * Diagnostic (for tests of the update's rarely taken routes; not part of the method).  After a
+ * DLRM_BWD_SORT* update (dlrm_emb_bag_bwd_sgd or _adagrad) of `batch` with `workspace`, same stream
+ * or ordered after it: copies to counts[0..9] (device, uint32) how the update handled the row
+ * groups of this batch (transpose of Eq. (2): every lookup of a row must reach that row's sum once):
+ *   [0] heavy row ranges handed to the first workgroups   [1] of them too large for one LDS sort
+ *   [2] lists sorted by many workgroups ("segments")      [3] their 2048-pair tiles
+ *   [4] oversized ranges that split off dominant rows     [5] lists one workgroup sorted through memory
+ *   [6] oversized ranges holding a single row             [7] runs > 2048 summed by one workgroup
+ *   [8] hot rows (runs > 2048) summed by the bag-group kernels, all tables
+ *   [9] tables whose hot rows took the dense (matrix core) kernel
+ * DLRM_ERR_BAD_SHAPE for an empty batch (nothing ran).
+ */
+int32_t dlrm_emb_bag_bwd_route_counts(const dlrm_sparse_batch* batch, void* workspace,
+                                      size_t workspace_bytes, uint32_t* counts, void* stream);
+
+/*
  * Runs only the grouping stage of DLRM_BWD_SORT and exports it in canonical
  * form, for checking index handling bit for bit.  Per table k, in that table's
  * slice [tbl_off[k], tbl_off[k+1]) of each output array:

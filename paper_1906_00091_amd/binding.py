@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_prepare.argtypes = [sb, vp, sz, vp]
         L.dlrm_emb_bag_bwd_prepared_oversized.restype = i32
         L.dlrm_emb_bag_bwd_prepared_oversized.argtypes = [sb, vp, sz, vp, vp]
+        L.dlrm_emb_bag_bwd_route_counts.restype = i32
+        L.dlrm_emb_bag_bwd_route_counts.argtypes = [sb, vp, sz, vp, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
         L.dlrm_emb_bag_bwd_export_groups.argtypes = [sb, vp, sz, vp, vp, vp, vp, vp]
         L.dlrm_profile_reduce_kernel.restype = i32
@@ -261,6 +263,18 @@ def dlrm_emb_bag_bwd_prepared_oversized(batch: SparseBatch, workspace: torch.Ten
            lib().dlrm_emb_bag_bwd_prepared_oversized(batch.ref(), _ptr(workspace), ws_bytes,
                                                      _ptr(out) + 4 * index,
                                                      _stream() if stream is None else int(stream.cuda_stream)))
+
+
+ROUTE_NAMES = ("heavy_ranges", "oversized_ranges", "segments", "segment_tiles", "dominant_row_splits",
+               "global_sorts", "one_row_ranges", "huge_runs_in_place", "hot_rows", "dense_hot_tables")
+
+
+def dlrm_emb_bag_bwd_route_counts(batch: SparseBatch, workspace: torch.Tensor, counts: torch.Tensor):
+    """counts: int32 device tensor of >= 10 elements (see ROUTE_NAMES)."""
+    assert counts.dtype == torch.int32 and counts.is_cuda and counts.numel() >= 10
+    ws_bytes = workspace.numel() * workspace.element_size()
+    _check("dlrm_emb_bag_bwd_route_counts",
+           lib().dlrm_emb_bag_bwd_route_counts(batch.ref(), _ptr(workspace), ws_bytes, _ptr(counts), _stream()))
 
 
 def dlrm_emb_bag_bwd_export_groups(batch: SparseBatch, workspace: torch.Tensor,

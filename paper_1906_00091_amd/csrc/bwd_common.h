@@ -73,6 +73,14 @@ constexpr int kSmallBatch = 65536;              // up to this many lookups the f
 constexpr int kCandMin = 128;                   // a row with this many of an oversized bucket's first
                                                 // kBktCap pairs is split off before any sorting
 constexpr int kCand = kBktCap / kCandMin;       // at most this many such rows
+constexpr int kDenseFrom = 8;                   // tables with at least this many hot rows (unweighted batch)
+                                                // have them summed as a dense contraction on the matrix cores
+// Route counters of an update, kept behind the two segment counters in seg_meta (zeroed by the
+// partition, read back by dlrm_emb_bag_bwd_route_counts): how often each rarely taken route ran.
+constexpr int kRouteSplit = 4;                  // oversized buckets that split off dominant rows
+constexpr int kRouteGlobalSort = 5;             // lists sorted by one workgroup through global memory
+constexpr int kRouteOneRow = 6;                 // oversized buckets holding a single row
+constexpr int kRouteHugeInPlace = 7;            // runs above kHugeRun summed by one workgroup (no tail launches)
 
 // ---------------------------------------------------------------------------
 // Workspace layout (all offsets 256-byte aligned)
@@ -88,7 +96,7 @@ struct WsLayout {
   size_t hot_cnt;            // uint32[K]: queued hot runs per table
   size_t over_list;          // uint32[nnz / kBigMin + 1]: heavy buckets, handed to the first workgroups
   size_t segs;               // SegInfo[nnz / kBktCap + 2]: those of them sorted by many workgroups
-  size_t seg_meta;           // uint32[8]: segment tiles, segments
+  size_t seg_meta;           // uint32[8]: segment tiles, segments, -, -, route counters (kRoute*)
   size_t huge_runs;          // HugeRun[nnz / kHugeRun + K]: table k's list starts at sum_{j<k}(nnz_j/kHugeRun + 1)
   size_t huge_part;          // float[max_runs * bag groups * d]
   size_t total;

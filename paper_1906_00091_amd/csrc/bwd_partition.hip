@@ -24,9 +24,7 @@ __global__ __launch_bounds__(kThreads) void bucket_hist_kernel(GroupArgs a) {
     *a.over_cnt = 0u;
     *a.list_cnt = 0u;
     for (int k = 0; k < a.K; ++k) a.hot_cnt[k] = 0u;
-    a.seg_meta[0] = 0u;
-    a.seg_meta[1] = 0u;
-    a.seg_meta[2] = 0u;
+    for (int i = 0; i < 8; ++i) a.seg_meta[i] = 0u;
   }
 }
 

@@ -148,6 +148,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     const uint32_t r = longs[q];
     const uint32_t i0 = heads[r] - h0, i1 = heads[r + 1] - h0;
     const uint32_t len = i1 - i0;
+    if (len > (uint32_t)kHugeRun && a.no_tail && threadIdx.x == 0) atomicAdd(&a.seg_meta[kRouteHugeInPlace], 1u);
     if (len > (uint32_t)kHugeRun && !a.no_tail) {  // queue for the multi-workgroup pass
       if (threadIdx.x == 0) {
         HugeRun hr;
@@ -324,6 +325,7 @@ __device__ inline void sort_reduce_large(const GroupArgs& a, const UpdArgs& u, c
     }
     return;
   }
+  if (threadIdx.x == 0) atomicAdd(&a.seg_meta[kRouteGlobalSort], 1u);
   const int res = sort_bucket_global(a, bk, s, src);
   __syncthreads();
   const uint32_t* keys = a.keys[res] + bk.start;
@@ -365,6 +367,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
     sort_reduce_large<DT, G, OPT, WT>(a, u, b, W, 1, s, part);
     return;
   }
+  if (tid == 0) atomicAdd(&a.seg_meta[kRouteSplit], 1u);
   uint32_t cd[kCand];
 #pragma unroll
   for (int c = 0; c < kCand; ++c) cd[c] = sp.cand[c];
@@ -561,6 +564,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
     if (threadIdx.x == 0) {
       s.heads[0] = 0;
       s.heads[1] = b.n;
+      atomicAdd(&a.seg_meta[kRouteOneRow], 1u);
     }
     __syncthreads();
     const uint32_t nlong = collect_long_runs(s, 1, long_run<G>());

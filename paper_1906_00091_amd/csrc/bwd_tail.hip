@@ -318,7 +318,6 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
 //   16x16x4 layout: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16] and holds
 //   D[m = 4*(l/16) + v][n = l%16] in element v of its accumulator.
 constexpr int kDenseRuns = 32;     // hot rows per pass of a workgroup
-constexpr int kDenseFrom = 8;      // tables with at least this many hot rows take this kernel
 constexpr int kDenseStage = 8;     // float4 registers per thread holding the next tile
 constexpr int kDenseTileFloats = 8192;
 constexpr int kDenseDeep = 4;      // 64-entry chunks of one run's list in flight while counting

@@ -54,6 +54,26 @@ __global__ __launch_bounds__(256) void atomic_update_kernel(AtomArgs a) {
 // reduce launches with the row update OPT.
 __global__ void copy_u32_kernel(const uint32_t* src, uint32_t* dst) { *dst = src ? *src : 0u; }
 
+// One thread copies the counters an update left in the workspace (dlrm_emb_bag_bwd_route_counts).
+__global__ void route_counts_kernel(GroupArgs a, uint32_t* out) {
+  uint32_t hot = 0, dense = 0;
+  for (int k = 0; k < a.K; ++k) {
+    const uint32_t c = a.hot_cnt[k];
+    hot += c;
+    dense += (a.weights == nullptr && c >= (uint32_t)kDenseFrom) ? 1u : 0u;
+  }
+  out[0] = *a.list_cnt;
+  out[1] = *a.over_cnt;
+  out[2] = a.seg_meta[1];
+  out[3] = a.seg_meta[0];
+  out[4] = a.seg_meta[kRouteSplit];
+  out[5] = a.seg_meta[kRouteGlobalSort];
+  out[6] = a.seg_meta[kRouteOneRow];
+  out[7] = a.seg_meta[kRouteHugeInPlace];
+  out[8] = hot;
+  out[9] = dense;
+}
+
 template <int OPT>
 static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* workspace, size_t workspace_bytes,
                          int algo, hipStream_t hs) {
@@ -204,6 +224,23 @@ extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* wo
   GroupArgs g;
   fill_group_args(g, s, L, workspace);
   return enqueue_partition(s, g, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_route_counts(const dlrm_sparse_batch* s, void* workspace,
+                                                 size_t workspace_bytes, uint32_t* counts, void* stream) {
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  if (!counts) return DLRM_ERR_NULL;
+  if ((s->d & 3) || pow2_ceil(s->d / 4) > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
+  WsLayout L;
+  st = check_ws(s, workspace, workspace_bytes, &L);
+  if (st != DLRM_OK) return st;
+  if (s->nnz_total == 0) return DLRM_ERR_BAD_SHAPE;  // an empty batch never wrote the counters
+  GroupArgs g;
+  fill_group_args(g, s, L, workspace);
+  hipLaunchKernelGGL(route_counts_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), g, counts);
+  DLRM_CHECK_LAUNCH();
+  return DLRM_OK;
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_prepared_oversized(const dlrm_sparse_batch* s, void* workspace,
