@@ -224,6 +224,26 @@ int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, in
                              int32_t algo, void* stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): dlrm_emb_bag_bwd_sgd with algo = DLRM_BWD_SORT, its
+ * workspace being an array of DLRM_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it
+ * runs on from the moment it is loaded until the process ends.  Allocates nothing, frees nothing.
+ * Same arguments, same launches, same bits as dlrm_emb_bag_bwd_sgd on a caller-owned workspace.
+ * DLRM_ERR_WORKSPACE if dlrm_emb_bag_bwd_workspace_bytes(...) of this batch exceeds
+ * DLRM_NOALLOC_SCRATCH_BYTES (about 24 bytes per lookup plus 4 KB per 4096 lookups and per table:
+ * batches up to ~2.5 M lookups fit); nothing is launched then.
+ * All calls on one GPU share that GPU's array: two calls that overlap in time (different streams,
+ * or different host threads without stream order between them) race on it -- the caller orders
+ * them.  The array keeps the previous call's contents; the first kernel of every call resets the
+ * counters the later ones read, nothing else needs to start at zero.
+ * The per-GPU address of the array is looked up on the first call on that GPU and kept (the one piece
+ * of state the library holds).
+ */
+#define DLRM_NOALLOC_SCRATCH_BYTES (64u << 20)
+int32_t dlrm_emb_bag_bwd_sgd_noalloc(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
+                                     int64_t stride_k, float lr, void* stream);
+
+/*
  * The same backward with sparse Adagrad in place of the SGD step (Sec. 5.1 trains with "SGD
  * and Adagrad"; the paper prints no formula: this is the standard element-wise rule applied
  * to the rows a batch touches, duplicates summed first as for SGD).  For every distinct row r

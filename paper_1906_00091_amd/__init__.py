@@ -3,7 +3,7 @@ their backward and the fused sparse SGD update, as hand-written HIP kernels
 behind a C ABI (include/dlrm_hot.h).  This package is the thin binding."""
 from .binding import (  # noqa: F401
     BF16, BWD_ATOMIC, BWD_AUTO, BWD_SORT, BWD_SORT_PREPARED, BWD_SORT_PREPARED_FLAT, F16, F32, FWD_AUTO, FWD_FUSED, FWD_SPLIT, DlrmError, SparseBatch, alloc_workspace,
-    dlrm_emb_bag_bwd_adagrad, dlrm_emb_bag_bwd_export_groups, dlrm_emb_bag_bwd_route_counts, ROUTE_NAMES, dlrm_emb_bag_bwd_prepare, dlrm_emb_bag_bwd_prepared_oversized, dlrm_emb_bag_bwd_sgd,
+    dlrm_emb_bag_bwd_adagrad, dlrm_emb_bag_bwd_export_groups, dlrm_emb_bag_bwd_route_counts, ROUTE_NAMES, dlrm_emb_bag_bwd_prepare, dlrm_emb_bag_bwd_prepared_oversized, dlrm_emb_bag_bwd_sgd, dlrm_emb_bag_bwd_sgd_noalloc, NOALLOC_SCRATCH_BYTES,
     state_pointers, dlrm_emb_bag_bwd_workspace_bytes,
     dlrm_emb_bag_fwd, dlrm_emb_interact_fwd, dlrm_emb_interact_fwd_stamped, dlrm_interact_dot_bwd, dlrm_interact_dot_fwd, dlrm_lengths_to_offsets,
     ceiling_sink, dlrm_ceiling_copy, dlrm_ceiling_gather, dlrm_ceiling_read, dlrm_ceiling_rmw,

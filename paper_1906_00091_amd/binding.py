@@ -73,6 +73,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_workspace_bytes.argtypes = [i32, i32, i32, i64, i64, i32]
         L.dlrm_emb_bag_bwd_sgd.restype = i32
         L.dlrm_emb_bag_bwd_sgd.argtypes = [sb, vp, i64, i64, f32, vp, sz, i32, vp]
+        L.dlrm_emb_bag_bwd_sgd_noalloc.restype = i32
+        L.dlrm_emb_bag_bwd_sgd_noalloc.argtypes = [sb, vp, i64, i64, f32, vp]
         L.dlrm_emb_bag_bwd_adagrad.restype = i32
         L.dlrm_emb_bag_bwd_adagrad.argtypes = [sb, vp, vp, i64, i64, f32, f32, vp, sz, i32, vp]
         L.dlrm_emb_bag_bwd_prepare.restype = i32
@@ -224,6 +226,17 @@ def dlrm_emb_bag_bwd_sgd(batch: SparseBatch, dS: torch.Tensor, stride_b: int, st
     _check("dlrm_emb_bag_bwd_sgd",
            lib().dlrm_emb_bag_bwd_sgd(batch.ref(), _ptr(dS) + 4 * dS_offset, stride_b, stride_k,
                                       C.c_float(lr), _ptr(workspace), ws_bytes, algo, _stream()))
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def dlrm_emb_bag_bwd_sgd_noalloc(batch: SparseBatch, dS: torch.Tensor, stride_b: int, stride_k: int, lr: float,
+                                 dS_offset: int = 0):
+    """The update on the library's own per-GPU scratch array (no workspace argument, no allocation)."""
+    _check("dlrm_emb_bag_bwd_sgd_noalloc",
+           lib().dlrm_emb_bag_bwd_sgd_noalloc(batch.ref(), _ptr(dS) + 4 * dS_offset, stride_b, stride_k,
+                                              C.c_float(lr), _stream()))
 
 
 def dlrm_emb_bag_bwd_adagrad(batch: SparseBatch, state_ptrs: torch.Tensor, dS: torch.Tensor, stride_b: int,

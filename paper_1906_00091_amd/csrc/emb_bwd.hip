@@ -5,7 +5,32 @@
 // 8 x 1M x 64 multi-hot workload, so AUTO always takes SORT.
 #include "bwd_common.h"
 
+#include <mutex>
+
 namespace dlrm {
+
+// Backward workspace of dlrm_emb_bag_bwd_sgd_noalloc: one array per GPU, held until the process
+// ends.  The name below is a host-side stand-in; host code only ever uses the per-device address
+// that hipGetSymbolAddress returns (scratch_base).
+static __device__ __align__(256) unsigned char scratch[DLRM_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mu;
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+static int scratch_base(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DLRM_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return DLRM_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DLRM_OK;
+}
 
 hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
@@ -183,6 +208,20 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   u.eps = 0.0f;
   u.d = s->d;
   return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo, hs);
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_sgd_noalloc(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
+                                                int64_t stride_k, float lr, void* stream) {
+  int st = check_batch(s);
+  if (st != DLRM_OK) return st;
+  // the size is checked before the address is looked up: a batch that does not fit touches nothing
+  if (ws_layout(s->K, s->B, s->d, s->nnz_total).total > (size_t)DLRM_NOALLOC_SCRATCH_BYTES) return DLRM_ERR_WORKSPACE;
+  void* ws = nullptr;
+  st = scratch_base(&ws);
+  if (st != DLRM_OK) return st;
+  // every counter the update reads is zeroed by the first kernel of the grouping: nothing to clear here
+  return dlrm_emb_bag_bwd_sgd(s, dS, stride_b, stride_k, lr, ws, (size_t)DLRM_NOALLOC_SCRATCH_BYTES, DLRM_BWD_SORT,
+                              stream);
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* const* state, const float* dS,
