@@ -3,8 +3,8 @@
  *
  * C ABI.  Every pointer is a DEVICE pointer owned by the caller unless a
  * comment says "host".  The library allocates nothing, keeps no state between
- * calls (the optional profiling hook at the end of this file aside), and only enqueues work on the HIP stream passed as `stream`
- * (a hipStream_t cast to void*; NULL = the default stream).  No call
+ * calls (one exception, stated at dlrm_emb_bag_bwd_sgd_noalloc), and only enqueues work on the
+ * HIP stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream).  No call
  * synchronises with the host.
  *
  * Every function returns a status: DLRM_OK, or a negative DLRM_ERR_* value.
@@ -43,8 +43,8 @@ extern "C" {
 #define DLRM_F16 1
 #define DLRM_BF16 2
 
-/* element type of a batch's index array (Sec. 5.1: the framework operators take int64
- * or int32 indices) */
+/* element type of a batch's index array (Sec. 5, opening paragraph: the framework operators take
+ * int64 or int32 indices) */
 #define DLRM_I64 0 /* int64 (what the five workloads use) */
 #define DLRM_I32 1 /* int32: 4 bytes less traffic per lookup */
 
@@ -66,6 +66,7 @@ extern "C" {
 #define DLRM_MAX_ROWS 2147483647LL      /* m_k < 2^31 */
 #define DLRM_MAX_NNZ 2147483647LL       /* total lookups per batch < 2^31 */
 #define DLRM_MAX_INTERACT_F 128         /* F <= 128 */
+#define DLRM_MAX_BWD_TABLES 65535        /* the backward takes K <= 65535 (tables are a grid dimension) */
 /* also: K * (B + 1) <= DLRM_MAX_NNZ (bags are numbered in 32 bits); the backward needs d <= 256 */
 
 /*
@@ -217,7 +218,8 @@ size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t
  * dlrm_emb_bag_bwd_workspace_bytes(...) bytes; contents are scratch.
  * d <= 256 (a gradient row of d fp32 values is at most one wavefront of 16-byte pieces): fp16/bf16
  * tables with 256 < d <= 512 can be pooled but not updated (DLRM_ERR_BAD_SHAPE, here and in
- * dlrm_emb_bag_bwd_adagrad and dlrm_emb_bag_bwd_prepare).
+ * dlrm_emb_bag_bwd_adagrad and dlrm_emb_bag_bwd_prepare).  K <= DLRM_MAX_BWD_TABLES (else
+ * DLRM_ERR_BAD_SHAPE, before anything is launched).
  */
 int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
                              int64_t stride_k, float lr, void* workspace, size_t workspace_bytes,
@@ -339,38 +341,24 @@ int32_t dlrm_table_init_hash(void* table, int64_t rows, int32_t d, int32_t table
                              uint64_t key, float scale, void* stream);
 
 /*
- * Profiling aid (not part of the method; the only process-wide state in the library).
- * While a pair of caller-owned hipEvent_t is set, every DLRM_BWD_SORT call records
- * ev_start immediately before and ev_stop immediately after the launch of its dominant
- * kernel (the bucket sort + row reduce + SGD update), on the stream of that call, so a
- * benchmark can time that one kernel with HIP events.  Pass NULL, NULL to clear.  Both or
- * neither must be NULL (else DLRM_ERR_NULL).  Not thread-safe.
+ * Timing aid (not part of the method): dlrm_emb_bag_bwd_sgd / dlrm_emb_bag_bwd_adagrad with a pair of
+ * caller-owned HIP events for THIS call.  On the sort path ev_start is recorded on `stream`
+ * immediately before and ev_stop immediately after the launch of the call's dominant kernel (the
+ * bucket sort + row reduce + row update), so a benchmark can time that one kernel with HIP events
+ * on the stream it runs on.  timing == NULL, or both events NULL: exactly the plain call.  One event
+ * NULL and the other not: DLRM_ERR_NULL.  With DLRM_BWD_ATOMIC the events bracket its one launch.
  */
-int32_t dlrm_profile_reduce_kernel(void* ev_start, void* ev_stop);
-
-/*
- * Measurement aid (not part of the method): memory-bound kernels of known traffic in the access
- * patterns of the path, for a benchmark to time, so that a kernel of the path can be held against
- * what the board sustains for its pattern as well as against the nominal HBM peak.  Each call
- * enqueues one launch on `stream`; all pointers are device pointers, 16-byte aligned.
- *   copy   : dst[0:bytes] = src[0:bytes]; bytes a multiple of 16.  Traffic: bytes read + bytes written.
- *   read   : reads src[0:bytes]; `sink` receives dlrm_ceiling_sink_floats() meaningless floats.
- *   gather : reads the n listed rows (row r = table[r*row_bytes : (r+1)*row_bytes], row_bytes one of
- *            64, 128, 256, 512; `rows` uint32 [n]) whole, four rows in flight per lane group, like the
- *            pooled lookup of Eq. (2) with nothing to add them to.  Traffic: n*row_bytes read.
- *   rmw    : multiplies every fp32 element of the n listed rows by 1 + 2^-10 in place: each row is
- *            read once and written once, like the row update of Sec. 5.1 without its gradient.  The
- *            listed rows must be distinct (else the result depends on the order).  Traffic:
- *            n*row_bytes read + n*row_bytes written.
- * Out-of-range row numbers are undefined behaviour.  Errors: DLRM_ERR_NULL, DLRM_ERR_BAD_SHAPE
- * (size 0, misaligned, unsupported row_bytes).
- */
-int32_t dlrm_ceiling_sink_floats(void);
-int32_t dlrm_ceiling_copy(const void* src, void* dst, size_t bytes, void* stream);
-int32_t dlrm_ceiling_read(const void* src, size_t bytes, float* sink, void* stream);
-int32_t dlrm_ceiling_gather(const void* table, const uint32_t* rows, int64_t n, int32_t row_bytes, float* sink,
-                            void* stream);
-int32_t dlrm_ceiling_rmw(void* table, const uint32_t* rows, int64_t n, int32_t row_bytes, void* stream);
+typedef struct dlrm_bwd_timing {
+  void* ev_start; /* hipEvent_t */
+  void* ev_stop;  /* hipEvent_t */
+} dlrm_bwd_timing;
+int32_t dlrm_emb_bag_bwd_sgd_timed(const dlrm_sparse_batch* batch, const float* dS, int64_t stride_b,
+                                   int64_t stride_k, float lr, void* workspace, size_t workspace_bytes,
+                                   int32_t algo, const dlrm_bwd_timing* timing, void* stream);
+int32_t dlrm_emb_bag_bwd_adagrad_timed(const dlrm_sparse_batch* batch, void* const* state, const float* dS,
+                                       int64_t stride_b, int64_t stride_k, float lr, float eps,
+                                       void* workspace, size_t workspace_bytes, int32_t algo,
+                                       const dlrm_bwd_timing* timing, void* stream);
 
 #ifdef __cplusplus
 }

@@ -6,6 +6,5 @@ from .binding import (  # noqa: F401
     dlrm_emb_bag_bwd_adagrad, dlrm_emb_bag_bwd_export_groups, dlrm_emb_bag_bwd_route_counts, ROUTE_NAMES, dlrm_emb_bag_bwd_prepare, dlrm_emb_bag_bwd_prepared_oversized, dlrm_emb_bag_bwd_sgd, dlrm_emb_bag_bwd_sgd_noalloc, NOALLOC_SCRATCH_BYTES,
     state_pointers, dlrm_emb_bag_bwd_workspace_bytes,
     dlrm_emb_bag_fwd, dlrm_emb_interact_fwd, dlrm_emb_interact_fwd_stamped, dlrm_interact_dot_bwd, dlrm_interact_dot_fwd, dlrm_lengths_to_offsets,
-    ceiling_sink, dlrm_ceiling_copy, dlrm_ceiling_gather, dlrm_ceiling_read, dlrm_ceiling_rmw,
-    dlrm_place_dense, dlrm_profile_reduce_kernel, dlrm_table_init_hash, dlrm_validate_csr, lib, status_string, version,
+    dlrm_place_dense, dlrm_emb_bag_bwd_sgd_timed, dlrm_emb_bag_bwd_adagrad_timed, dlrm_table_init_hash, dlrm_validate_csr, lib, status_string, version,
 )

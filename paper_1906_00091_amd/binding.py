@@ -26,6 +26,10 @@ class DlrmError(RuntimeError):
         super().__init__("%s failed: status %d (%s)" % (fn, status, status_string(status)))
 
 
+class _BwdTimingC(C.Structure):
+    _fields_ = [("ev_start", C.c_void_p), ("ev_stop", C.c_void_p)]
+
+
 class _SparseBatchC(C.Structure):
     _fields_ = [
         ("K", C.c_int32), ("B", C.c_int32), ("d", C.c_int32), ("table_dtype", C.c_int32),
@@ -85,20 +89,13 @@ def lib() -> C.CDLL:
         L.dlrm_emb_bag_bwd_route_counts.argtypes = [sb, vp, sz, vp, vp]
         L.dlrm_emb_bag_bwd_export_groups.restype = i32
         L.dlrm_emb_bag_bwd_export_groups.argtypes = [sb, vp, sz, vp, vp, vp, vp, vp]
-        L.dlrm_profile_reduce_kernel.restype = i32
-        L.dlrm_profile_reduce_kernel.argtypes = [vp, vp]
         L.dlrm_table_init_hash.restype = i32
         L.dlrm_table_init_hash.argtypes = [vp, i64, i32, i32, C.c_uint64, f32, vp]
-        L.dlrm_ceiling_sink_floats.restype = i32
-        L.dlrm_ceiling_sink_floats.argtypes = []
-        L.dlrm_ceiling_copy.restype = i32
-        L.dlrm_ceiling_copy.argtypes = [vp, vp, sz, vp]
-        L.dlrm_ceiling_read.restype = i32
-        L.dlrm_ceiling_read.argtypes = [vp, sz, vp, vp]
-        L.dlrm_ceiling_gather.restype = i32
-        L.dlrm_ceiling_gather.argtypes = [vp, vp, i64, i32, vp, vp]
-        L.dlrm_ceiling_rmw.restype = i32
-        L.dlrm_ceiling_rmw.argtypes = [vp, vp, i64, i32, vp]
+        tm = C.POINTER(_BwdTimingC)
+        L.dlrm_emb_bag_bwd_sgd_timed.restype = i32
+        L.dlrm_emb_bag_bwd_sgd_timed.argtypes = [sb, vp, i64, i64, f32, vp, sz, i32, tm, vp]
+        L.dlrm_emb_bag_bwd_adagrad_timed.restype = i32
+        L.dlrm_emb_bag_bwd_adagrad_timed.argtypes = [sb, vp, vp, i64, i64, f32, f32, vp, sz, i32, tm, vp]
         _lib = L
     return _lib
 
@@ -228,6 +225,33 @@ def dlrm_emb_bag_bwd_sgd(batch: SparseBatch, dS: torch.Tensor, stride_b: int, st
                                       C.c_float(lr), _ptr(workspace), ws_bytes, algo, _stream()))
 
 
+def _timing(ev_start, ev_stop):
+    """ev_start / ev_stop: raw hipEvent_t handles (ints or c_void_p)."""
+    val = lambda e: e.value if isinstance(e, C.c_void_p) else e
+    return _BwdTimingC(val(ev_start), val(ev_stop))
+
+
+def dlrm_emb_bag_bwd_sgd_timed(batch: SparseBatch, dS: torch.Tensor, stride_b: int, stride_k: int,
+                               lr: float, workspace: Optional[torch.Tensor], ev_start, ev_stop,
+                               algo: int = BWD_AUTO, dS_offset: int = 0):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tm = _timing(ev_start, ev_stop)
+    _check("dlrm_emb_bag_bwd_sgd_timed",
+           lib().dlrm_emb_bag_bwd_sgd_timed(batch.ref(), _ptr(dS) + 4 * dS_offset, stride_b, stride_k,
+                                            C.c_float(lr), _ptr(workspace), ws_bytes, algo, C.byref(tm), _stream()))
+
+
+def dlrm_emb_bag_bwd_adagrad_timed(batch: SparseBatch, state_ptrs: torch.Tensor, dS: torch.Tensor, stride_b: int,
+                                   stride_k: int, lr: float, eps: float, workspace: Optional[torch.Tensor],
+                                   ev_start, ev_stop, algo: int = BWD_AUTO, dS_offset: int = 0):
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    tm = _timing(ev_start, ev_stop)
+    _check("dlrm_emb_bag_bwd_adagrad_timed",
+           lib().dlrm_emb_bag_bwd_adagrad_timed(batch.ref(), _ptr(state_ptrs), _ptr(dS) + 4 * dS_offset, stride_b,
+                                                stride_k, C.c_float(lr), C.c_float(eps), _ptr(workspace), ws_bytes,
+                                                algo, C.byref(tm), _stream()))
+
+
 NOALLOC_SCRATCH_BYTES = 64 << 20
 
 
@@ -305,51 +329,6 @@ def dlrm_table_init_hash(table: torch.Tensor, table_dtype: int, key: int, scale:
     _check("dlrm_table_init_hash",
            lib().dlrm_table_init_hash(_ptr(table), rows, d, table_dtype, C.c_uint64(key),
                                       C.c_float(scale), _stream()))
-
-
-def dlrm_profile_reduce_kernel(ev_start: Optional[int], ev_stop: Optional[int]):
-    """ev_start / ev_stop: raw hipEvent_t handles (ints) or None, None to clear."""
-    _check("dlrm_profile_reduce_kernel", lib().dlrm_profile_reduce_kernel(ev_start, ev_stop))
-
-
-def _nbytes(t: torch.Tensor) -> int:
-    assert t.is_contiguous()
-    return t.numel() * t.element_size()
-
-
-def ceiling_sink() -> torch.Tensor:
-    """Scratch output of the read-only measurement kernels."""
-    return torch.empty(int(lib().dlrm_ceiling_sink_floats()), dtype=torch.float32, device="cuda")
-
-
-def dlrm_ceiling_copy(src: torch.Tensor, dst: torch.Tensor):
-    assert _nbytes(src) == _nbytes(dst)
-    _check("dlrm_ceiling_copy", lib().dlrm_ceiling_copy(_ptr(src), _ptr(dst), _nbytes(src), _stream()))
-
-
-def dlrm_ceiling_read(src: torch.Tensor, sink: torch.Tensor):
-    assert sink.dtype == torch.float32 and sink.numel() >= int(lib().dlrm_ceiling_sink_floats())
-    _check("dlrm_ceiling_read", lib().dlrm_ceiling_read(_ptr(src), _nbytes(src), _ptr(sink), _stream()))
-
-
-def _rows_arg(table: torch.Tensor, rows: torch.Tensor, row_bytes: int) -> int:
-    # row numbers as uint32 bit patterns in an int32 tensor; the caller keeps them below the row count
-    assert rows.dtype == torch.int32 and rows.is_contiguous() and rows.numel() >= 1
-    assert _nbytes(table) % row_bytes == 0
-    return rows.numel()
-
-
-def dlrm_ceiling_gather(table: torch.Tensor, rows: torch.Tensor, row_bytes: int, sink: torch.Tensor):
-    assert sink.dtype == torch.float32 and sink.numel() >= int(lib().dlrm_ceiling_sink_floats())
-    n = _rows_arg(table, rows, row_bytes)
-    _check("dlrm_ceiling_gather",
-           lib().dlrm_ceiling_gather(_ptr(table), _ptr(rows), n, row_bytes, _ptr(sink), _stream()))
-
-
-def dlrm_ceiling_rmw(table: torch.Tensor, rows: torch.Tensor, row_bytes: int):
-    """Scales the fp32 elements of the listed (distinct) rows by 1 + 2^-10 in place."""
-    n = _rows_arg(table, rows, row_bytes)
-    _check("dlrm_ceiling_rmw", lib().dlrm_ceiling_rmw(_ptr(table), _ptr(rows), n, row_bytes, _stream()))
 
 
 def alloc_workspace(batch: SparseBatch) -> torch.Tensor:

@@ -1,4 +1,5 @@
-"""Builds libdlrm_hot.so (HIP, gfx950 only) in-tree with hipcc."""
+"""Builds libdlrm_hot.so (the method) and libdlrm_ceilings.so (measurement kernels a benchmark times;
+a library of its own) in-tree with hipcc, for gfx950 only."""
 from __future__ import annotations
 
 import os
@@ -13,7 +14,9 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libdlrm_hot.so")
 SOURCES = ["bwd_reduce_sgd.hip", "bwd_reduce_adagrad.hip", "bwd_reduce_sgd_weighted.hip",
            "bwd_reduce_adagrad_weighted.hip", "bwd_tail.hip", "bwd_partition.hip", "bwd_export.hip",
-           "emb_bwd.hip", "emb_fwd.hip", "interact.hip", "pooled_interact.hip", "util.hip", "ceilings.hip"]
+           "emb_bwd.hip", "emb_fwd.hip", "interact.hip", "pooled_interact.hip", "util.hip"]
+CEIL_LIB = os.path.join(PKG, "libdlrm_ceilings.so")
+CEIL_SOURCES = ["ceilings.hip"]
 
 # -packed-fp32-ops: keep hipcc from forming packed fp32 VALU instructions.
 HIPCC_FLAGS = [
@@ -31,10 +34,10 @@ def _hipcc() -> str:
 
 
 def _stale() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(CEIL_LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(INCLUDE, "dlrm_hot.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE)]
     return any(os.path.getmtime(p) > t for p in deps)
 
 
@@ -57,12 +60,13 @@ def build(force: bool = True, verbose: bool = False) -> str:
         # the host pass warns that it does not know -packed-fp32-ops: harmless, not shown
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(compile_one, SOURCES + CEIL_SOURCES))
+    for lib, lib_objs in ((LIB, objs[:len(SOURCES)]), (CEIL_LIB, objs[len(SOURCES):])):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + lib_objs
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
     return LIB
 
 

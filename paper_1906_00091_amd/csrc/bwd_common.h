@@ -548,6 +548,7 @@ inline int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout
   *L = ws_layout(s->K, s->B, s->d, s->nnz_total);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || bytes < L->total) return DLRM_ERR_WORKSPACE;
   if (L->nt_max > 0x7FFFFFFF || ((int64_t)s->K << kMaxTopBits) > 0x7FFFFFFF) return DLRM_ERR_BAD_SHAPE;
+  if (s->K > DLRM_MAX_BWD_TABLES) return DLRM_ERR_BAD_SHAPE;  // the hot-row launches put the table in grid.y
   return DLRM_OK;
 }
 
@@ -556,14 +557,17 @@ inline int check_ws(const dlrm_sparse_batch* s, void* ws, size_t bytes, WsLayout
 int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_t st);
 // step 4 onwards with the SGD / Adagrad row update (bwd_reduce_sgd.hip, bwd_reduce_adagrad.hip)
 // (one translation unit per optimizer and per weighted / unweighted pooling)
-int run_reduce_sgd(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
-int run_reduce_adagrad(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
-int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
-int run_reduce_adagrad_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st);
+// tm: NULL, or the caller's event pair recorded around the bucket_reduce launch of this call
+int run_reduce_sgd(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, const dlrm_bwd_timing* tm,
+                   hipStream_t st);
+int run_reduce_adagrad(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, const dlrm_bwd_timing* tm,
+                       hipStream_t st);
+int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, const dlrm_bwd_timing* tm,
+                            hipStream_t st);
+int run_reduce_adagrad_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K,
+                                const dlrm_bwd_timing* tm, hipStream_t st);
 // bwd_tail.hip
 int launch_segment_sort(const GroupArgs& g, hipStream_t st);
 int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, hipStream_t st);
-// optional pair of caller-owned HIP events recorded around the bucket_reduce launch (emb_bwd.hip)
-extern hipEvent_t g_ev_start, g_ev_stop;
 
 }  // namespace dlrm

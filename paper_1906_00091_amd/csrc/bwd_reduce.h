@@ -625,12 +625,12 @@ __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdAr
 
 
 template <int DT, int G, int OPT, bool WT>
-static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_t st) {
+static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, const dlrm_bwd_timing* tm, hipStream_t st) {
   const unsigned blocks = ((unsigned)K << g.top_bits) + (unsigned)g.max_over;
-  if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return DLRM_ERR_HIP;
+  if (tm && tm->ev_start && hipEventRecord(static_cast<hipEvent_t>(tm->ev_start), st) != hipSuccess) return DLRM_ERR_HIP;
   hipLaunchKernelGGL((bucket_reduce_kernel<DT, G, OPT, WT>), dim3(blocks), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
-  if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return DLRM_ERR_HIP;
+  if (tm && tm->ev_stop && hipEventRecord(static_cast<hipEvent_t>(tm->ev_stop), st) != hipSuccess) return DLRM_ERR_HIP;
   if (g.no_tail) return DLRM_OK;
   const unsigned seg_tiles = (unsigned)(g.seg_tiles_max);
   int rc = launch_segment_sort(g, st);
@@ -646,26 +646,26 @@ static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, hipStream_
 }
 
 template <int DT, int OPT, bool WT>
-static int dispatch_reduce(const GroupArgs& g, const UpdArgs& u, int G, int K, hipStream_t st) {
+static int dispatch_reduce(const GroupArgs& g, const UpdArgs& u, int G, int K, const dlrm_bwd_timing* tm, hipStream_t st) {
   switch (G) {
-    case 1: return launch_reduce<DT, 1, OPT, WT>(g, u, K, st);
-    case 2: return launch_reduce<DT, 2, OPT, WT>(g, u, K, st);
-    case 4: return launch_reduce<DT, 4, OPT, WT>(g, u, K, st);
-    case 8: return launch_reduce<DT, 8, OPT, WT>(g, u, K, st);
-    case 16: return launch_reduce<DT, 16, OPT, WT>(g, u, K, st);
-    case 32: return launch_reduce<DT, 32, OPT, WT>(g, u, K, st);
-    case 64: return launch_reduce<DT, 64, OPT, WT>(g, u, K, st);
+    case 1: return launch_reduce<DT, 1, OPT, WT>(g, u, K, tm, st);
+    case 2: return launch_reduce<DT, 2, OPT, WT>(g, u, K, tm, st);
+    case 4: return launch_reduce<DT, 4, OPT, WT>(g, u, K, tm, st);
+    case 8: return launch_reduce<DT, 8, OPT, WT>(g, u, K, tm, st);
+    case 16: return launch_reduce<DT, 16, OPT, WT>(g, u, K, tm, st);
+    case 32: return launch_reduce<DT, 32, OPT, WT>(g, u, K, tm, st);
+    case 64: return launch_reduce<DT, 64, OPT, WT>(g, u, K, tm, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
 
 
 template <int OPT, bool WT>
-inline int run_reduce(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st) {
+inline int run_reduce(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, const dlrm_bwd_timing* tm, hipStream_t st) {
   switch (dtype) {
-    case DLRM_F32: return dispatch_reduce<DLRM_F32, OPT, WT>(g, u, G, K, st);
-    case DLRM_F16: return dispatch_reduce<DLRM_F16, OPT, WT>(g, u, G, K, st);
-    case DLRM_BF16: return dispatch_reduce<DLRM_BF16, OPT, WT>(g, u, G, K, st);
+    case DLRM_F32: return dispatch_reduce<DLRM_F32, OPT, WT>(g, u, G, K, tm, st);
+    case DLRM_F16: return dispatch_reduce<DLRM_F16, OPT, WT>(g, u, G, K, tm, st);
+    case DLRM_BF16: return dispatch_reduce<DLRM_BF16, OPT, WT>(g, u, G, K, tm, st);
   }
   return DLRM_ERR_BAD_DTYPE;
 }

@@ -2,7 +2,8 @@
 #include "bwd_reduce.h"
 
 namespace dlrm {
-int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K, hipStream_t st) {
-  return run_reduce<kSgd, true>(g, u, dtype, G, K, st);
+int run_reduce_sgd_weighted(const GroupArgs& g, const UpdArgs& u, int dtype, int G, int K,
+    const dlrm_bwd_timing* tm, hipStream_t st) {
+  return run_reduce<kSgd, true>(g, u, dtype, G, K, tm, st);
 }
 }  // namespace dlrm

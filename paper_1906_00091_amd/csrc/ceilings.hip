@@ -3,6 +3,7 @@
 // them to learn what the board in front of it sustains for each pattern, which is what a kernel of
 // the path can be held against besides the nominal HBM peak.
 #include "common.h"
+#include "dlrm_ceilings.h"
 
 namespace dlrm {
 

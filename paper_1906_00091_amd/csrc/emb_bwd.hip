@@ -32,8 +32,6 @@ static int scratch_base(void** out) {
   return DLRM_OK;
 }
 
-hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
-
 // --- ATOMIC path --------------------------------------------------------------------
 struct AtomArgs {
   void* const* tables;
@@ -101,7 +99,7 @@ __global__ void route_counts_kernel(GroupArgs a, uint32_t* out) {
 
 template <int OPT>
 static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* workspace, size_t workspace_bytes,
-                         int algo, hipStream_t hs) {
+                         int algo, const dlrm_bwd_timing* tm, hipStream_t hs) {
   const bool prepared = algo == DLRM_BWD_SORT_PREPARED || algo == DLRM_BWD_SORT_PREPARED_FLAT;
   const int G = pow2_ceil(s->d / 4);  // lanes per fp32 gradient row
   if (G > DLRM_WAVE) return DLRM_ERR_BAD_SHAPE;
@@ -117,32 +115,29 @@ static int run_sort_path(const dlrm_sparse_batch* s, const UpdArgs& u, void* wor
   }
   if (algo == DLRM_BWD_SORT_PREPARED_FLAT) g.no_tail = 1;  // the grouping itself does not depend on it
   if (g.weights != nullptr)
-    return OPT == kAdagrad ? run_reduce_adagrad_weighted(g, u, s->table_dtype, G, s->K, hs)
-                           : run_reduce_sgd_weighted(g, u, s->table_dtype, G, s->K, hs);
-  return OPT == kAdagrad ? run_reduce_adagrad(g, u, s->table_dtype, G, s->K, hs)
-                         : run_reduce_sgd(g, u, s->table_dtype, G, s->K, hs);
+    return OPT == kAdagrad ? run_reduce_adagrad_weighted(g, u, s->table_dtype, G, s->K, tm, hs)
+                           : run_reduce_sgd_weighted(g, u, s->table_dtype, G, s->K, tm, hs);
+  return OPT == kAdagrad ? run_reduce_adagrad(g, u, s->table_dtype, G, s->K, tm, hs)
+                         : run_reduce_sgd(g, u, s->table_dtype, G, s->K, tm, hs);
 }
 
 template <int G>
-static int launch_atomic(const AtomArgs& a, hipStream_t st) {
+static int launch_atomic(const AtomArgs& a, const dlrm_bwd_timing* tm, hipStream_t st) {
   constexpr int S = DLRM_WAVE / G;
+  if (tm && tm->ev_start && hipEventRecord(static_cast<hipEvent_t>(tm->ev_start), st) != hipSuccess) return DLRM_ERR_HIP;
   hipLaunchKernelGGL((atomic_update_kernel<G>), dim3(div_up((int64_t)a.K * a.B, 4 * S)), dim3(256), 0,
                      st, a);
   DLRM_CHECK_LAUNCH();
+  if (tm && tm->ev_stop && hipEventRecord(static_cast<hipEvent_t>(tm->ev_stop), st) != hipSuccess) return DLRM_ERR_HIP;
   return DLRM_OK;
 }
+
+static bool timing_ok(const dlrm_bwd_timing* tm) { return !tm || ((tm->ev_start == nullptr) == (tm->ev_stop == nullptr)); }
 
 
 }  // namespace dlrm
 
 using namespace dlrm;
-
-extern "C" int32_t dlrm_profile_reduce_kernel(void* ev_start, void* ev_stop) {
-  if ((ev_start == nullptr) != (ev_stop == nullptr)) return DLRM_ERR_NULL;
-  g_ev_start = static_cast<hipEvent_t>(ev_start);
-  g_ev_stop = static_cast<hipEvent_t>(ev_stop);
-  return DLRM_OK;
-}
 
 extern "C" size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t d, int64_t nnz_total,
                                                    int64_t max_rows, int32_t table_dtype) {
@@ -155,9 +150,17 @@ extern "C" size_t dlrm_emb_bag_bwd_workspace_bytes(int32_t K, int32_t B, int32_t
 extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
                                         int64_t stride_k, float lr, void* workspace,
                                         size_t workspace_bytes, int32_t algo, void* stream) {
+  return dlrm_emb_bag_bwd_sgd_timed(s, dS, stride_b, stride_k, lr, workspace, workspace_bytes, algo, nullptr, stream);
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_sgd_timed(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
+                                              int64_t stride_k, float lr, void* workspace,
+                                              size_t workspace_bytes, int32_t algo, const dlrm_bwd_timing* tm,
+                                              void* stream) {
   int st = check_batch(s);
   if (st != DLRM_OK) return st;
-  if (!dS) return DLRM_ERR_NULL;
+  if (!dS || !timing_ok(tm)) return DLRM_ERR_NULL;
+  if (s->K > DLRM_MAX_BWD_TABLES) return DLRM_ERR_BAD_SHAPE;
   if ((s->d & 3) || stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0)
     return DLRM_ERR_BAD_SHAPE;
   if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
@@ -187,13 +190,13 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
     a.B = s->B;
     a.d = s->d;
     switch (G) {
-      case 1: return launch_atomic<1>(a, hs);
-      case 2: return launch_atomic<2>(a, hs);
-      case 4: return launch_atomic<4>(a, hs);
-      case 8: return launch_atomic<8>(a, hs);
-      case 16: return launch_atomic<16>(a, hs);
-      case 32: return launch_atomic<32>(a, hs);
-      case 64: return launch_atomic<64>(a, hs);
+      case 1: return launch_atomic<1>(a, tm, hs);
+      case 2: return launch_atomic<2>(a, tm, hs);
+      case 4: return launch_atomic<4>(a, tm, hs);
+      case 8: return launch_atomic<8>(a, tm, hs);
+      case 16: return launch_atomic<16>(a, tm, hs);
+      case 32: return launch_atomic<32>(a, tm, hs);
+      case 64: return launch_atomic<64>(a, tm, hs);
     }
     return DLRM_ERR_BAD_SHAPE;
   }
@@ -207,7 +210,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_sgd(const dlrm_sparse_batch* s, const float*
   u.lr = lr;
   u.eps = 0.0f;
   u.d = s->d;
-  return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo, hs);
+  return run_sort_path<kSgd>(s, u, workspace, workspace_bytes, algo, tm, hs);
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_sgd_noalloc(const dlrm_sparse_batch* s, const float* dS, int64_t stride_b,
@@ -228,9 +231,17 @@ extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* co
                                             int64_t stride_b, int64_t stride_k, float lr, float eps,
                                             void* workspace, size_t workspace_bytes, int32_t algo,
                                             void* stream) {
+  return dlrm_emb_bag_bwd_adagrad_timed(s, state, dS, stride_b, stride_k, lr, eps, workspace, workspace_bytes, algo,
+                                        nullptr, stream);
+}
+
+extern "C" int32_t dlrm_emb_bag_bwd_adagrad_timed(const dlrm_sparse_batch* s, void* const* state, const float* dS,
+                                                  int64_t stride_b, int64_t stride_k, float lr, float eps,
+                                                  void* workspace, size_t workspace_bytes, int32_t algo,
+                                                  const dlrm_bwd_timing* tm, void* stream) {
   int st = check_batch(s);
   if (st != DLRM_OK) return st;
-  if (!dS || !state) return DLRM_ERR_NULL;
+  if (!dS || !state || !timing_ok(tm)) return DLRM_ERR_NULL;
   if ((s->d & 3) || stride_k < s->d || (stride_k & 3) || (stride_b & 3) || stride_b < 0)
     return DLRM_ERR_BAD_SHAPE;
   if (reinterpret_cast<uintptr_t>(dS) & 15) return DLRM_ERR_BAD_SHAPE;
@@ -248,7 +259,7 @@ extern "C" int32_t dlrm_emb_bag_bwd_adagrad(const dlrm_sparse_batch* s, void* co
   u.lr = lr;
   u.eps = eps;
   u.d = s->d;
-  return run_sort_path<kAdagrad>(s, u, workspace, workspace_bytes, algo, static_cast<hipStream_t>(stream));
+  return run_sort_path<kAdagrad>(s, u, workspace, workspace_bytes, algo, tm, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int32_t dlrm_emb_bag_bwd_prepare(const dlrm_sparse_batch* s, void* workspace,

@@ -7,25 +7,37 @@ import re
 import pytest
 
 import paper_1906_00091_amd as hot
-from paper_1906_00091_amd import binding
+from paper_1906_00091_amd import binding, ceilings
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "dlrm_hot.h")).read()
+def _declared(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(dlrm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared()
-    assert len(names) >= 11
+    names = _declared("dlrm_hot.h")
+    assert len(names) >= 20
     L = hot.lib()
     for n in names:
         assert hasattr(L, n), n
     assert hot.version() >= 100
     assert hot.status_string(0) == "ok" and "NULL" in hot.status_string(-1)
+
+
+def test_measurement_library_is_separate_and_exports_its_header():
+    """The plain memory kernels a benchmark times live in a library of their own: the method's
+    header declares none of them and the method's library exports none."""
+    names = _declared("dlrm_ceilings.h")
+    assert len(names) == 5
+    L = ceilings.lib()
+    for n in names:
+        assert hasattr(L, n), n
+        assert not hasattr(hot.lib(), n), n
+    assert not [n for n in _declared("dlrm_hot.h") if "ceiling" in n or "profile" in n]
 
 
 def _batch(**kw):
@@ -97,6 +109,15 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert call(_batch(), C.c_void_p(0x1010), need, hot.BWD_SORT) == -4      # misaligned
     assert call(_batch(), C.c_void_p(0x1000), need, 9) == -5
     assert call(_batch(), None, 0, hot.BWD_SORT_PREPARED) == -4
+    assert call(_batch(K=65536, B=1), C.c_void_p(0x1000), 1 << 40, hot.BWD_SORT) == -2   # K is a grid dimension
+    assert call(_batch(K=65536, B=1), C.c_void_p(0x1000), 1 << 40, hot.BWD_ATOMIC) == -2
+    # the timed call: both events or none
+    tm = binding._BwdTimingC(0x10, None)
+    assert L.dlrm_emb_bag_bwd_sgd_timed(C.byref(_batch()), ds, 64, 16, C.c_float(0.01), C.c_void_p(0x1000), need,
+                                        hot.BWD_SORT, C.byref(tm), None) == -1
+    assert L.dlrm_emb_bag_bwd_adagrad_timed(C.byref(_batch()), C.c_void_p(0x1000), ds, 64, 16, C.c_float(0.01),
+                                            C.c_float(1e-8), C.c_void_p(0x1000), need, hot.BWD_SORT, C.byref(tm),
+                                            None) == -1
     prep = lambda b, ws, n: L.dlrm_emb_bag_bwd_prepare(C.byref(b), ws, n, None)
     over = lambda b, ws, n, o: L.dlrm_emb_bag_bwd_prepared_oversized(C.byref(b), ws, n, o, None)
     assert over(_batch(), C.c_void_p(0x1000), 1 << 30, None) == -1
@@ -138,7 +159,7 @@ def test_interaction_and_helpers_reject_bad_arguments_on_the_host():
 
 
 def test_measurement_kernels_reject_bad_arguments_on_the_host():
-    L = hot.lib()
+    L = ceilings.lib()
     p = C.c_void_p(0x1000)
     assert L.dlrm_ceiling_sink_floats() >= 4096
     assert L.dlrm_ceiling_copy(None, p, 64, None) == -1

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import paper_1906_00091_amd as hot
+from paper_1906_00091_amd import ceilings
 from oracle import oracle
 from workloads import gen
 
@@ -889,15 +890,15 @@ def test_measurement_kernels_move_the_bytes_they_claim(row_bytes):
     table = torch.randn((nrows, w), generator=g).to(DEV)
     before = table.clone()
     rows = torch.randperm(nrows, generator=g)[:3001].to(torch.int32).to(DEV)   # distinct, ragged count
-    sink = hot.ceiling_sink()
-    hot.dlrm_ceiling_gather(table, rows, row_bytes, sink)
-    hot.dlrm_ceiling_read(table, sink)
+    sink = ceilings.ceiling_sink()
+    ceilings.dlrm_ceiling_gather(table, rows, row_bytes, sink)
+    ceilings.dlrm_ceiling_read(table, sink)
     assert torch.equal(table, before)
-    hot.dlrm_ceiling_rmw(table, rows, row_bytes)
+    ceilings.dlrm_ceiling_rmw(table, rows, row_bytes)
     want = before.clone()
     sel = rows.long()
     want[sel] = before[sel] * torch.tensor(1.0 + 2.0 ** -10, dtype=torch.float32, device=DEV)
     assert torch.equal(table, want)
     dst = torch.zeros_like(table)
-    hot.dlrm_ceiling_copy(table, dst)
+    ceilings.dlrm_ceiling_copy(table, dst)
     assert torch.equal(dst, table)
