@@ -253,18 +253,21 @@ __device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti, uin
 }
 
 // --- shared by steps 3 and 4: stable ranking of a tile by a digit ---------------------
-// Wave w of the workgroup owns the contiguous positions [w*64*ITEMS, (w+1)*64*ITEMS) of
-// the tile, item j of lane l being position w*64*ITEMS + j*64 + l.  Ranks inside a wave
-// come from ballot matching; per-wave digit counters in LDS give the order across waves.
+// Wave w of the workgroup owns the contiguous positions [w*64*items, (w+1)*64*items) of
+// the tile, item j < items of lane l being position w*64*items + j*64 + l (items <= ITEMS is
+// workgroup-uniform: a tile that is not full is dealt evenly to the wavefronts, and nobody ranks
+// items that do not exist).  Ranks inside a wave come from ballot matching; per-wave digit counters
+// in LDS give the order across waves.
 // On return rnk[j] is the item's rank among the items of its wave with the same digit that
 // precede it, and wcnt[w][digit] the wave's count.  wcnt must be zero on entry.
 template <int ITEMS, int NBK>
 __device__ inline void rank_items(const uint32_t* dg, const bool* ok, int bits,
-                                  uint32_t (*wcnt)[NBK], uint32_t* rnk) {
+                                  uint32_t (*wcnt)[NBK], uint32_t* rnk, int items = ITEMS) {
   const int lane = lane_id(), w = wave_id();
   const unsigned long long lt = (1ull << lane) - 1ull;
 #pragma unroll
   for (int j = 0; j < ITEMS; ++j) {
+    if (j >= items) break;  // uniform
     unsigned long long m = __ballot(ok[j]);
     for (int bit = 0; bit < bits; ++bit) {
       const bool one = (dg[j] >> bit) & 1u;

@@ -57,26 +57,30 @@ struct SortLds {
 __device__ inline int pass_bits(int left, int passes_left) { return (left + passes_left - 1) / passes_left; }
 
 // Buckets of at most kBktCap pairs (read from pair buffer src): stable LSD passes entirely in
-// LDS.  The pairs end up in s.skey / s.sval in (row, position) order.
+// LDS.  The pairs end up in s.skey / s.sval in (row, position) order.  The bucket is dealt evenly to
+// the wavefronts, `per` = ceil(n / 256) items a lane (see rank_items).
 __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, SortLds& s, int src = 1) {
   const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
   const uint32_t* kin = a.keys[src] + b.start;
   const uint32_t* vin = a.vals[src] + b.start;
   const int n = (int)b.n;
+  const int per = (n + kThreads - 1) / kThreads;   // 1..kBktItems, uniform
   uint32_t key[kBktItems], val[kBktItems], dg[kBktItems], rnk[kBktItems];
   bool ok[kBktItems];
 #pragma unroll
   for (int j = 0; j < kBktItems; ++j) {
-    const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
-    ok[j] = li < n;
+    const int li = w * (DLRM_WAVE * per) + j * DLRM_WAVE + lane;
+    ok[j] = j < per && li < n;
     key[j] = ok[j] ? kin[li] : 0xFFFFFFFFu;
     val[j] = ok[j] ? vin[li] : 0u;
+    dg[j] = 0;
+    rnk[j] = 0;
   }
   const int passes = (b.low_bits + kSortBits - 1) / kSortBits;
   if (passes == 0) {  // a single row per bucket: already in position order
 #pragma unroll
     for (int j = 0; j < kBktItems; ++j) {
-      const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+      const int li = w * (DLRM_WAVE * per) + j * DLRM_WAVE + lane;
       if (ok[j]) {
         s.skey[li] = key[j];
         s.sval[li] = val[j];
@@ -94,7 +98,7 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kBktItems; ++j) dg[j] = (key[j] >> shift) & mask;
-    rank_items<kBktItems, kSortBuckets>(dg, ok, bits, s.wcnt, rnk);
+    rank_items<kBktItems, kSortBuckets>(dg, ok, bits, s.wcnt, rnk, per);
     __syncthreads();
     uint32_t lofs, tot;
     digit_offsets<kSortBuckets>(nb, s.wcnt, s.smem, &lofs, &tot);
@@ -112,7 +116,7 @@ __device__ inline void sort_bucket_lds(const GroupArgs& a, const Bucket& b, Sort
     if (p + 1 < passes) {
 #pragma unroll
       for (int j = 0; j < kBktItems; ++j) {
-        const int li = w * (DLRM_WAVE * kBktItems) + j * DLRM_WAVE + lane;
+        const int li = w * (DLRM_WAVE * per) + j * DLRM_WAVE + lane;
         if (ok[j]) {
           key[j] = s.skey[li];
           val[j] = s.sval[li];

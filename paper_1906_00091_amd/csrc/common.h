@@ -122,6 +122,13 @@ struct Tab<DLRM_BF16> {
 };
 
 __device__ inline u32x4 load16(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+// 16 bytes from a device address held as an integer (e.g. a table base that travelled through a
+// cross-lane read): the pointer is built in the global address space, so the load is a global one.  A
+// pointer made from an integer is otherwise a flat pointer, and flat loads also count as LDS-type
+// operations, so that every wait for a cross-lane permute would wait for the rows in flight too.
+__device__ inline u32x4 load16_global(uint64_t addr) {
+  return *(const __attribute__((address_space(1))) u32x4*)addr;
+}
 __device__ inline void store16(void* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
 __device__ inline f32x4 loadf4(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
 // Element i of a batch's index array, whose element type is a run-time property of the batch

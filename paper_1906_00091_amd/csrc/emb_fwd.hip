@@ -51,6 +51,82 @@ __device__ inline bool dense_rider(const FwdArgs& a) {
   return true;
 }
 
+// acc += w * widen(v): the 16 bytes of a row held by this lane.  fp16 rows: fma(x, 1, acc) is the
+// same single rounding as acc + x and lets the conversion fold into a mixed-precision multiply-add
+// (one instruction per element instead of two; the pooling of fp16 tables is bound by the vector ALUs).
+template <int DT, bool WT>
+__device__ inline void add_row(float* acc, u32x4 v, float w) {
+  constexpr int E = Tab<DT>::ELEMS;
+  if constexpr (DT == DLRM_F16) {
+    // v_fma_mix_f32: fp32 result of a * b + c where a is the low or high fp16 half of a register, widened
+    // exactly; b = w (fp32), c = acc (fp32): one rounding, the same value as acc + w * (float)a computed
+    // with a fused multiply-add.  (The compiler turns fma(x, 1, acc) back into convert + add.)
+    const uint32_t q[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[1,0,0]" : "+v"(acc[2 * i]) : "v"(q[i]), "v"(w));
+      asm("v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(acc[2 * i + 1]) : "v"(q[i]), "v"(w));
+    }
+  } else {
+    float f[E];
+    Tab<DT>::widen(v, f);
+    if constexpr (WT) {
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] = fmaf(w, f[i], acc[i]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] += f[i];
+    }
+  }
+}
+
+// Rows [0, n) of an index chunk held one per lane in `rows` (weights in `wts`): lane group `slot` adds the
+// rows at positions slot, slot + S, ... in ascending order, U row loads in flight.  Wbase: address of this
+// lane's 16 bytes of row 0.  Rounds that lie entirely inside the chunk carry no per-lane bounds logic.
+template <int DT, int G, int U, bool WT>
+__device__ inline void gather_chunk(float* acc, uint64_t Wbase, uint32_t row_bytes, uint32_t rows, float wts, int n,
+                                    int slot) {
+  constexpr int S = DLRM_WAVE / G;
+  const int iters = (n + S - 1) / S;
+  const int full = n / S;  // rounds in which every lane group has a row
+  int q = 0;
+  for (; q + U <= full; q += U) {
+    u32x4 v[U];
+    float wt[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int e = (q + u) * S + slot;
+      const uint32_t r = (uint32_t)__shfl((int)rows, e, DLRM_WAVE);
+      wt[u] = 1.0f;
+      if constexpr (WT) wt[u] = __shfl(wts, e, DLRM_WAVE);
+      v[u] = load16_global(Wbase + (uint64_t)r * row_bytes);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) add_row<DT, WT>(acc, v[u], wt[u]);
+  }
+  for (; q < iters; q += U) {   // the tail: branch-free, positions past the end re-read n - 1 and add the identity
+    u32x4 v[U];
+    float wt[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int e = (q + u) * S + slot;
+      const uint32_t r = (uint32_t)__shfl((int)rows, e < n ? e : n - 1, DLRM_WAVE);
+      wt[u] = 1.0f;
+      if constexpr (WT) wt[u] = __shfl(wts, e < n ? e : n - 1, DLRM_WAVE);
+      v[u] = load16_global(Wbase + (uint64_t)r * row_bytes);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const bool past = (q + u) * S + slot >= n;
+      if (past) {
+        v[u] = Tab<DT>::ident();
+        wt[u] = 1.0f;   // 1 * (-0) leaves the sum alone
+      }
+      add_row<DT, WT>(acc, v[u], wt[u]);
+    }
+  }
+}
+
 template <int DT>
 __device__ inline void write_pooled(float* o, const float* acc) {
   constexpr int E = Tab<DT>::ELEMS;
@@ -221,33 +297,7 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
     const uint32_t my_row = (uint32_t)idx[base + (lane < n ? lane : n - 1)];
     float my_wt = 1.0f;
     if constexpr (WT) my_wt = a.weights[pos0 + base + (lane < n ? lane : n - 1)];
-    const int iters = (n + S - 1) / S;
-    for (int j = 0; j < iters; j += U) {
-      u32x4 v[U];
-      float wt[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int e = (j + u) * S + slot;
-        const uint32_t r = __shfl(my_row, e < n ? e : n - 1, DLRM_WAVE);
-        if constexpr (WT) wt[u] = __shfl(my_wt, e < n ? e : n - 1, DLRM_WAVE);
-        v[u] = load16(W + (int64_t)r * row_bytes);   // branch-free: the tail re-reads position n-1
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const bool past = (j + u) * S + slot >= n;
-        if (past) v[u] = Tab<DT>::ident();
-        float f[E];
-        Tab<DT>::widen(v[u], f);
-        if constexpr (WT) {
-          const float w1 = past ? 1.0f : wt[u];
-#pragma unroll
-          for (int i = 0; i < E; ++i) acc[i] = fmaf(w1, f[i], acc[i]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < E; ++i) acc[i] += f[i];
-        }
-      }
-    }
+    gather_chunk<DT, G, U, WT>(acc, reinterpret_cast<uint64_t>(W), (uint32_t)row_bytes, my_row, my_wt, n, slot);
   }
   // combine the S lane groups: xor butterfly, identical result in every group
 #pragma unroll
@@ -264,7 +314,101 @@ __global__ __launch_bounds__(256) void emb_fwd_wave_kernel(FwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// A wavefront per bag as above, but the wavefront walks NBW consecutive bags and keeps the index
+// chunk of the NEXT bag (or of the next 64 positions of a long bag) in flight while it gathers the
+// rows of the current one.  With one bag per wavefront a bag of a few dozen rows is a chain of
+// dependent round trips (offsets -> indices -> rows) with little to overlap; here the offsets and
+// table bases of all NBW bags are fetched up front by the lanes (lane j holds bag j), and per bag
+// only the row gathers remain on the critical path.  Same additions in the same order as
+// emb_fwd_wave_kernel: the results are identical bit for bit.
+template <int DT, int G, int U, bool WT, typename IT>
+__global__ __launch_bounds__(256) void emb_fwd_wave_seq_kernel(FwdArgs a, int nbw) {
+  stamp_start(a.stamp, a.stamp_value);
+  if (dense_rider(a)) return;  // workgroup-uniform
+  constexpr int E = Tab<DT>::ELEMS;
+  constexpr int S = DLRM_WAVE / G;
+  const int lane = lane_id();
+  const int slot = lane / G, chunk = lane % G;
+  const uint32_t nbags = (uint32_t)a.K * (uint32_t)a.B;
+  const uint32_t bag0 = (blockIdx.x * (blockDim.x >> 6) + wave_id()) * (uint32_t)nbw;
+  if (bag0 >= nbags) return;  // wave-uniform
+  const int nb = (int)(nbags - bag0 < (uint32_t)nbw ? nbags - bag0 : (uint32_t)nbw);
+  const bool col_ok = chunk < a.chunks;
+  const int64_t row_bytes = (int64_t)a.chunks * 16;
+  // lane j describes bag bag0 + j: table, sample, first position (global), length, table base
+  const uint32_t my_bag = bag0 + (uint32_t)(lane < nb ? lane : nb - 1);
+  const int my_k = (int)(my_bag / (uint32_t)a.B), my_b = (int)(my_bag - (uint32_t)my_k * (uint32_t)a.B);
+  const int64_t* off = a.offsets + (int64_t)my_k * (a.B + 1);
+  const int64_t my_p0 = off[my_b], my_p1 = off[my_b + 1];
+  const uint64_t my_pos = (uint64_t)(a.tbl_off[my_k] + my_p0);
+  const uint32_t my_len = (uint32_t)(my_p1 - my_p0);
+  const uint64_t my_W = reinterpret_cast<uint64_t>(a.tables[my_k]);
+  auto bcast64 = [](uint64_t v, int j) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, j);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), j);
+    return ((uint64_t)hi << 32) | lo;
+  };
+  // the index chunk [base, base + 64) of bag j: one coalesced fetch; rows are < 2^31
+  auto fetch = [&](int j, uint32_t base, uint32_t& row, float& wt) {
+    const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, j);
+    if (base >= len) return;  // wave-uniform (an empty bag)
+    const uint32_t n = len - base < (uint32_t)DLRM_WAVE ? len - base : (uint32_t)DLRM_WAVE;
+    const uint64_t pos = bcast64(my_pos, j) + base + ((uint32_t)lane < n ? (uint32_t)lane : n - 1);
+    row = (uint32_t)static_cast<const IT*>(a.indices)[pos];
+    if constexpr (WT) wt = a.weights[pos];
+  };
+  uint32_t cur_row = 0, nxt_row = 0;
+  float cur_wt = 1.0f, nxt_wt = 1.0f;
+  fetch(0, 0u, cur_row, cur_wt);
+  float acc[E];
+  int j = 0;
+  uint32_t base = 0;
+  while (j < nb) {  // wave-uniform
+    const uint32_t len = (uint32_t)__builtin_amdgcn_readlane((int)my_len, j);
+    int nj = j;
+    uint32_t nbase = base + DLRM_WAVE;
+    if (nbase >= len) {
+      nj = j + 1;
+      nbase = 0;
+    }
+    if (nj < nb) fetch(nj, nbase, nxt_row, nxt_wt);   // in flight while this chunk's rows are gathered
+    if (base == 0) {
+#pragma unroll
+      for (int i = 0; i < E; ++i) acc[i] = -0.0f;
+    }
+    if (base < len) {
+      const int n = (int)(len - base < (uint32_t)DLRM_WAVE ? len - base : (uint32_t)DLRM_WAVE);
+      const uint64_t W = bcast64(my_W, j) + (uint64_t)((col_ok ? chunk : 0) * 16);
+      gather_chunk<DT, G, U, WT>(acc, W, (uint32_t)row_bytes, cur_row, cur_wt, n, slot);
+    }
+    if (nbase == 0) {  // the bag is complete: combine the S lane groups (xor butterfly) and store
+      float tot[E];
+#pragma unroll
+      for (int i = 0; i < E; ++i) tot[i] = acc[i];
+#pragma unroll
+      for (int o = G; o < DLRM_WAVE; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) tot[i] += __shfl_xor(tot[i], o, DLRM_WAVE);
+      }
+      if (len == 0) {
+#pragma unroll
+        for (int i = 0; i < E; ++i) tot[i] = 0.0f;
+      }
+      const uint32_t bag = bag0 + (uint32_t)j;
+      const int k = (int)(bag / (uint32_t)a.B), b = (int)(bag - (uint32_t)k * (uint32_t)a.B);
+      if (slot == 0 && col_ok)
+        write_pooled<DT>(a.out + (int64_t)b * a.stride_b + (int64_t)k * a.stride_k + chunk * E, tot);
+    }
+    j = nj;
+    base = nbase;
+    cur_row = nxt_row;
+    cur_wt = nxt_wt;
+  }
+}
+
+// ---------------------------------------------------------------------------
 constexpr int kShortBags = 4;  // bags per lane group of the short-bag kernel
+constexpr int kSeqMaxMeanLen = 64;  // mean bag length below which a wavefront walks several bags
 
 template <int DT, int G, bool WT, typename IT>
 static int launch_fwd(const FwdArgs& a_in, int mode, hipStream_t st) {
@@ -281,6 +425,12 @@ static int launch_fwd(const FwdArgs& a_in, int mode, hipStream_t st) {
     a.bag_blocks = div_up(bags, 4 * S * kShortBags);
     hipLaunchKernelGGL((emb_fwd_short_kernel<DT, G, kShortBags, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0,
                        st, a);
+  } else if (mode == 3) {
+    // several bags per wavefront, as many as leaves every compute unit a few dozen wavefronts
+    int nbw = (int)(bags / 16384);
+    nbw = nbw < 1 ? 1 : nbw > 16 ? 16 : nbw;
+    a.bag_blocks = div_up(bags, 4 * nbw);
+    hipLaunchKernelGGL((emb_fwd_wave_seq_kernel<DT, G, 8, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a, nbw);
   } else if (wave_mode) {
     // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
@@ -351,8 +501,11 @@ int emb_fwd_enqueue(const dlrm_sparse_batch* s, float* out, int64_t stride_b, in
   const int S = DLRM_WAVE / G;
   // a wavefront per bag pays off once a bag keeps all S lane groups busy for a few rounds
   const double mean_len = (double)s->nnz_total / ((double)s->K * s->B);
-  // mode 0: several bags per lane group (mean bag <= 2), 1: a lane group per bag, 2: a wavefront per bag
-  const int wave_mode = mean_len <= 2.0 ? 0 : (S > 1 && mean_len >= 2.0 * S) ? 2 : 1;
+  // mode 0: several bags per lane group (mean bag <= 2), 1: a lane group per bag, 2: a wavefront per bag,
+  // 3: a wavefront per bag walking several bags with the next bag's indices in flight (bags of up to a
+  // few dozen rows, where a bag is a chain of round trips rather than a stream)
+  int wave_mode = mean_len <= 2.0 ? 0 : (S > 1 && mean_len >= 2.0 * S) ? 2 : 1;
+  if (wave_mode == 2 && mean_len < (double)kSeqMaxMeanLen) wave_mode = 3;
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const bool idx32 = s->index_dtype == DLRM_I32;
   switch (s->table_dtype) {
