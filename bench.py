@@ -73,6 +73,10 @@ def parse_args():
     ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adagrad"],
                     help="row update of the fused backward (the metric is quoted on sgd)")
+    ap.add_argument("--locality", type=float, default=0.0, metavar="ALPHA",
+                    help="draw the workload's indices with the stack-distance trace generator of Sec. 4.2 from the "
+                         "profile of a Zipf(ALPHA) trace instead of the workload's own distribution: same shape, "
+                         "more temporal locality the larger ALPHA (a variant; the metric is quoted without)")
     ap.add_argument("--index32", action="store_true", help="int32 index arrays instead of int64")
     ap.add_argument("--weighted", action="store_true",
                     help="per-lookup weights (Eq. (2) in full) instead of sum pooling; the metric is quoted without")
@@ -183,7 +187,7 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     from workloads import gen
 
     dev = "cuda:0"
-    w = gen.WORKLOADS[config]
+    w = gen.locality_workload(config, args.locality) if args.locality > 0 else gen.WORKLOADS[config]
     print("bench.py: workload %d (%s), %d steps" % (config, w.name, steps), file=sys.stderr, flush=True)
     eb = gen.ELEM_BYTES[w.dtype]
     algo = {"auto": hot.BWD_AUTO, "sort": hot.BWD_SORT, "atomic": hot.BWD_ATOMIC}[args.algo]
@@ -684,7 +688,9 @@ def run_workload(args, config, steps, warmup, headline, ceil):
                    "rows_total": int(rows.sum()), "lookups_per_step": int(round(nnz_mean)),
                    "unique_rows_per_step": int(round(mean("U"))), "distinct_batches": nb,
                    "bwd_algo": args.algo, "optimizer": args.optimizer, "pooling": "weighted" if args.weighted else "sum",
-                   "indices": "int32" if args.index32 else "int64", "launch": "hip graph replays" if args.graph else "eager",
+                   "indices": "int32" if args.index32 else "int64",
+                   "index_distribution": ("stack-distance generator (Sec. 4.2) on the profile of a Zipf(%g) trace" % args.locality
+                                          if args.locality > 0 else {"uniform": "uniform", "zipf": "Zipf(%s)" % (w.dist[1:] or ("",))[0]}[w.dist[0]]), "launch": "hip graph replays" if args.graph else "eager",
                    "lr": w.lr, "upstream_gradient": "N(0,1) x 2^-20 (keeps the fed-back tables finite over 10^4 steps and more)",
                    "forward": ("emb_interact_fwd, one launch" if fused_fwd else
                                "place_dense, emb_bag_fwd, interact_dot_fwd" if args.split_fwd else
@@ -809,7 +815,7 @@ def main():
     if ceil is not None:
         out["board_ceilings"] = dict(ceil, unit="GB/s", note="plain memory kernels (libdlrm_ceilings) on this board: "
                                      "4 GiB streamed; 1.5 GB of distinct random rows of a 2 GiB table")
-    if not args.config and not args.no_extra and not args.graph:
+    if not args.config and not args.no_extra and not args.graph and not args.locality > 0:
         keep = ("steps", "warmup", "ms_per_step", "value", "unit", "samples_per_s", "dtype", "ms_per_step_chunks",
                 "ms_per_step_same_batch", "emb_fwd_bwd", "emb_fwd_bwd_prepared", "stage_ms", "stage_ms_median",
                 "emb_interact_fwd_ms", "emb_bag_bwd_prepared_ms", "stage_algorithmic_GBps", "state_after_run", "roofline")

@@ -42,7 +42,7 @@ class Workload:
     dtype: int                   # table storage type
     rows: Tuple                  # ("fixed", m) | ("loguniform", lo, hi, cap_total or None, min_rows)
     bag: Tuple                   # ("fixed", L) | ("uniform", lo, hi)  inclusive
-    dist: Tuple                  # ("uniform",) | ("zipf", alpha)
+    dist: Tuple                  # ("uniform",) | ("zipf", alpha) | ("trace", alpha): Sec. 4.2 generator
     lr: float = 0.01
     seed: int = 0
 
@@ -213,7 +213,24 @@ def _draw_indices(rng, dist: Tuple, m: int, n: int, A: int, C: int) -> np.ndarra
         rank = np.searchsorted(cdf, rng.random(n), side="left").astype(np.int64)  # 0-based rank
         rank = np.minimum(rank, m - 1)
         return (rank * np.int64(A) + np.int64(C)) % np.int64(m)
+    if dist[0] == "trace":
+        # Sec. 4.2: a synthetic trace with the locality of an original one.  The original here is a
+        # bounded-Zipf draw (alpha = dist[1]) four times as long as the batch; Alg. 1 profiles it into its
+        # unique ids u and stack-distance distribution p, Alg. 2 emits n lookups from (u, p) (first-time
+        # accesses at no less than 10 % while unseen ids remain, the section's adjustment).
+        from workloads import trace
+        original = _draw_indices(rng, ("zipf", float(dist[1])), m, 4 * n, A, C)
+        u, p = trace.profile_trace(original, m)
+        return trace.generate_trace(u, p, rng.random(n), min_new=0.1)
     raise ValueError(dist)
+
+
+def locality_workload(base: int, alpha: float) -> "Workload":
+    """Workload `base` with its indices drawn by the stack-distance generator of Sec. 4.2 from the profile
+    of a Zipf(alpha) trace: alpha moves the temporal locality (how soon an id comes back)."""
+    import dataclasses
+    w = WORKLOADS[base]
+    return dataclasses.replace(w, name="%s_trace_a%g" % (w.name, alpha), dist=("trace", float(alpha)))
 
 
 @dataclass
