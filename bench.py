@@ -83,6 +83,10 @@ def parse_args():
     ap.add_argument("--split-fwd", action="store_true",
                     help="forward as three calls (place_dense, emb_bag_fwd, interact_dot_fwd) even where the "
                          "one-launch forward applies (short bags)")
+    ap.add_argument("--keep-t", action="store_true",
+                    help="where the forward is the one launch (short bags), still write T and run the interaction "
+                         "backward on it, instead of the pair that never materialises T "
+                         "(dlrm_emb_interact_fwd with T = NULL, dlrm_emb_interact_bwd)")
     ap.add_argument("--event-every", type=int, default=8,
                     help="an event pair around the dominant kernel is recorded on every N-th timed step")
     ap.add_argument("--self-check", type=int, default=0, metavar="N",
@@ -164,7 +168,11 @@ def algorithmic_bytes(w, batch, elem_bytes, index_bytes=8, weighted=False):
     bwd = pooled + csr + 2 * U * w.d * elem_bytes
     int_fwd = w.B * (w.F * w.d + w.d + w.P) * 4
     int_bwd = w.B * (2 * w.F * w.d + w.d + w.P) * 4
-    return dict(U=U, nnz=nnz, fwd=fwd, bwd=bwd, int_fwd=int_fwd, int_bwd=int_bwd,
+    return dict(U=U, nnz=nnz, fwd=fwd, bwd=bwd, int_fwd=int_fwd, int_bwd=int_bwd, csr=csr,
+                # the one-launch forward that leaves T alone: rows, indices, x in; R out
+                fwd_no_t=U * w.d * elem_bytes + csr + w.B * w.d * 4 + w.B * (w.d + w.P) * 4,
+                # the backward that pools again: rows, indices, x, dR in; dT out
+                bwd_no_t=U * w.d * elem_bytes + csr + w.B * w.d * 4 + w.B * (w.d + w.P) * 4 + w.B * w.F * w.d * 4,
                 fwd_logical=nnz * w.d * elem_bytes + csr + pooled)
 
 
@@ -233,6 +241,10 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     # the library's own rule for dlrm_emb_interact_fwd(DLRM_FWD_AUTO), spelled out so the line says which ran
     fused_fwd = (not args.split_fwd and not args.weighted and K <= 64
                  and sum(b.nnz for b in batches) / (len(batches) * K * B) <= 4.0)
+
+    # short bags and a T of at least 16 MiB: the step never writes or reads T (below that the three kernels are
+    # latency-bound and the pair measured 1-2 us slower per step on the tiny and click-log workloads)
+    no_t = fused_fwd and not args.keep_t and B * F * d * 4 >= (16 << 20)
 
     def backward(sb, algo_code, ws=ws, red=None):
         """red: a pair of raw HIP events recorded around the dominant kernel of THIS call."""
@@ -365,10 +377,10 @@ def run_workload(args, config, steps, warmup, headline, ceil):
             # one call; one launch for short bags, else two (the dense vectors ride in the pooling launch)
             if ahead and use_stamp:
                 seq[0] += 1
-                hot.dlrm_emb_interact_fwd_stamped(sb, x, T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT,
-                                                  stamp, seq[0])
+                hot.dlrm_emb_interact_fwd_stamped(sb, x, None if no_t else T, R,
+                                                  hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT, stamp, seq[0])
             else:
-                hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT)
+                hot.dlrm_emb_interact_fwd(sb, x, None if no_t else T, R, hot.FWD_FUSED if fused_fwd else hot.FWD_SPLIT)
         else:
             hot.dlrm_place_dense(x, T)
             if ev is not None:
@@ -379,7 +391,10 @@ def run_workload(args, config, steps, warmup, headline, ceil):
             hot.dlrm_interact_dot_fwd(T, R)
             if ev is not None:
                 ev[3].record()
-        hot.dlrm_interact_dot_bwd(T, dR, dT)
+        if no_t and ev is None:
+            hot.dlrm_emb_interact_bwd(sb, x, dR, dT)   # pools the bags again instead of reading T
+        else:
+            hot.dlrm_interact_dot_bwd(T, dR, dT)
         if ev is not None:
             ev[4].record()
         if ahead:
@@ -588,10 +603,22 @@ def run_workload(args, config, steps, warmup, headline, ceil):
         for i in range(nbk):
             sb, x, _ = dev_batches[(warmup + i) % nb]
             fe[i][0].record()
-            hot.dlrm_emb_interact_fwd(sb, x, T, R, hot.FWD_FUSED)
+            hot.dlrm_emb_interact_fwd(sb, x, None if no_t else T, R, hot.FWD_FUSED)
             fe[i][1].record()
         torch.cuda.synchronize()
         fused_ms = sum(a.elapsed_time(b_) for a, b_ in fe) / nbk
+
+    not_ms = None
+    if no_t:  # the backward that pools again, by itself, same batches
+        fe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nbk)]
+        for i in range(nbk):
+            sb, x, dR = dev_batches[(warmup + i) % nb]
+            fe[i][0].record()
+            hot.dlrm_emb_interact_bwd(sb, x, dR, dT)
+            fe[i][1].record()
+        torch.cuda.synchronize()
+        not_ms = sum(a.elapsed_time(b_) for a, b_ in fe) / nbk
+        hot.dlrm_emb_interact_fwd(dev_batches[0][0], dev_batches[0][1], T, R, hot.FWD_FUSED)   # (T for the checks below)
 
     # ---- the state the steps left behind is finite (the feedback is bounded, see DR_SCALE)
     bad = [n for n, t in (("T", T), ("R", R), ("dT", dT)) if not bool(torch.isfinite(t).all())]
@@ -627,11 +654,12 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     row_rw = d * eb + (d * 4 if adagrad else 0)
     red_bytes = float(np.mean([abytes[i]["nnz"] * 8 + K * B * d * 4 + 2 * abytes[i]["U"] * row_rw for i in ids]))
     fwd_kernel_ms = fused_ms if fused_fwd else stage_ms["emb_bag_fwd"]
-    fwd_kernel_bytes = mean("fwd") + (mean("int_fwd") if fused_fwd else 0.0)
+    fwd_kernel_bytes = mean("fwd_no_t") if no_t else mean("fwd") + (mean("int_fwd") if fused_fwd else 0.0)
     kernels = {
         ("pooled_interact_fwd_kernel" if fused_fwd else "emb_fwd_kernel"): (fwd_kernel_bytes, fwd_kernel_ms),
         "bucket_reduce_kernel": (red_bytes, red_ms),
-        "interact_bwd_kernel": (mean("int_bwd"), stage_ms["interact_dot_bwd"]),
+        ("pooled_interact_bwd_kernel" if no_t else "interact_bwd_kernel"):
+            (mean("bwd_no_t"), not_ms) if no_t else (mean("int_bwd"), stage_ms["interact_dot_bwd"]),
     }
     dom = max(kernels, key=lambda n: kernels[n][1])
     dom_bytes, dom_ms = kernels[dom]
@@ -668,6 +696,7 @@ def run_workload(args, config, steps, warmup, headline, ceil):
         row_bytes = 512 if d * eb > 256 else 256   # the row patterns are measured at 64, 256 and 512 bytes
         pattern = ("row_rmw_%dB" % row_bytes if dom == "bucket_reduce_kernel" else
                    "stream_copy" if dom == "interact_bwd_kernel" else "row_gather_%dB" % row_bytes)
+        # (the pooled-interaction kernels gather rows and stream the rest: held against the gather)
         roofline["board_ceiling"] = {"pattern": pattern, "GBps": ceil[pattern],
                                      "frac": round(achieved / ceil[pattern], 4)}
 
@@ -692,7 +721,8 @@ def run_workload(args, config, steps, warmup, headline, ceil):
                    "index_distribution": ("stack-distance generator (Sec. 4.2) on the profile of a Zipf(%g) trace" % args.locality
                                           if args.locality > 0 else {"uniform": "uniform", "zipf": "Zipf(%s)" % (w.dist[1:] or ("",))[0]}[w.dist[0]]), "launch": "hip graph replays" if args.graph else "eager",
                    "lr": w.lr, "upstream_gradient": "N(0,1) x 2^-20 (keeps the fed-back tables finite over 10^4 steps and more)",
-                   "forward": ("emb_interact_fwd, one launch" if fused_fwd else
+                   "forward": ("emb_interact_fwd, one launch, T not written; backward dlrm_emb_interact_bwd pools again" if no_t else
+                               "emb_interact_fwd, one launch" if fused_fwd else
                                "place_dense, emb_bag_fwd, interact_dot_fwd" if args.split_fwd else
                                "emb_interact_fwd, two launches (pooling with the dense copy, interaction)"),
                    "grouping": ("second stream, one step ahead (two workspaces)" if mode["ahead"] else
@@ -712,6 +742,7 @@ def run_workload(args, config, steps, warmup, headline, ceil):
         "stage_ms_min": {k: round(float(np.min(v)), 5) for k, v in stage_all.items()},
         "host_poll_wait": {"ms_total": round(poll_wait[0] * 1e3, 3), "steps_that_waited": poll_wait[1]},
         "emb_interact_fwd_ms": None if fused_ms is None else round(fused_ms, 5),
+        "emb_interact_bwd_ms": None if not_ms is None else round(not_ms, 5),
         "emb_bag_bwd_prepared_ms": None if prepared_ms is None else round(prepared_ms, 5),
         "emb_fwd_bwd_prepared": None if prepared_ms is None else dict(
             rate(emb_bytes, stage_ms["emb_bag_fwd"] + prepared_ms),
@@ -818,7 +849,7 @@ def main():
     if not args.config and not args.no_extra and not args.graph and not args.locality > 0:
         keep = ("steps", "warmup", "ms_per_step", "value", "unit", "samples_per_s", "dtype", "ms_per_step_chunks",
                 "ms_per_step_same_batch", "emb_fwd_bwd", "emb_fwd_bwd_prepared", "stage_ms", "stage_ms_median",
-                "emb_interact_fwd_ms", "emb_bag_bwd_prepared_ms", "stage_algorithmic_GBps", "state_after_run", "roofline")
+                "emb_interact_fwd_ms", "emb_interact_bwd_ms", "emb_bag_bwd_prepared_ms", "stage_algorithmic_GBps", "state_after_run", "roofline")
         per = {}
         for cfg, nsteps in ((4, 100), (5, 30)):
             import gc

@@ -163,6 +163,9 @@ int32_t dlrm_interact_dot_fwd(const float* T, int32_t B, int32_t F, int32_t d, f
  * stride_k = d) and dlrm_interact_dot_fwd define; T is written because the backward reads it.
  * x: [B,d] fp32, T: [B,F,d] fp32, R: [B, d + F(F-1)/2] fp32, all device, contiguous, x and T
  * 16-byte aligned.  Requires K + 1 <= DLRM_MAX_INTERACT_F and d a multiple of 4.
+ * T may be NULL where the one-launch path runs (DLRM_FWD_FUSED, or DLRM_FWD_AUTO choosing it): T is
+ * then never written, for a caller whose backward is dlrm_emb_interact_bwd; elsewhere a NULL T is
+ * DLRM_ERR_NULL.
  * algo: DLRM_FWD_FUSED needs a batch without weights and K <= 64 (else DLRM_ERR_BAD_ALGO); it
  * adds a bag's rows one by one in ascending position order (a one-index bag is an exact copy
  * of its row), each lane walking one bag, so it is meant for bags of a few rows;
@@ -193,6 +196,22 @@ int32_t dlrm_emb_interact_fwd_stamped(const dlrm_sparse_batch* batch, const floa
  */
 int32_t dlrm_interact_dot_bwd(const float* T, const float* dR, int32_t B, int32_t F, int32_t d,
                               float* dT, void* stream);
+
+/*
+ * Backward of dlrm_emb_interact_fwd without T (Sec. 2.2 by the chain rule, with the pooled vectors of
+ * Eq. (2) formed again on the way): dT as dlrm_interact_dot_bwd(T, dR, ...) defines it, for the T that
+ * dlrm_emb_interact_fwd(DLRM_FWD_FUSED) defines -- T[b,0,:] = x[b,:], T[b,k+1,:] = the bag's rows added
+ * one by one in ascending position order -- bit for bit, but T is not an argument: a wavefront pools a
+ * sample's K bags from the tables again while it multiplies.  A training step made of
+ * dlrm_emb_interact_fwd(T = NULL), this call and the update never writes or reads T (per sample
+ * 2*F*d floats of traffic less, the bags' rows read a second time instead).
+ * The tables must still hold the values the forward pass read: call it BEFORE the update of the step.
+ * x: [B,d] fp32, dR: [B, d + F(F-1)/2] fp32, dT: [B,F,d] fp32 (row 0: gradient of the dense vector,
+ * rows 1..K: dS), device, contiguous, x and dT 16-byte aligned.  A batch without pooling weights and
+ * K <= 64 (else DLRM_ERR_BAD_ALGO); each lane walks a bag, so it is meant for bags of a few rows.
+ */
+int32_t dlrm_emb_interact_bwd(const dlrm_sparse_batch* batch, const float* x, const float* dR, float* dT,
+                              void* stream);
 
 /*
  * Bytes of workspace dlrm_emb_bag_bwd_sgd / dlrm_emb_bag_bwd_export_groups need

@@ -166,6 +166,15 @@ def emb_interact_fwd(tables: Sequence[np.ndarray], dtype: int, indices, offsets,
     return T, interact_dot_fwd(T)
 
 
+def emb_interact_bwd(tables: Sequence[np.ndarray], dtype: int, indices, offsets, tbl_off, x: np.ndarray,
+                     dR: np.ndarray) -> np.ndarray:
+    """Backward of emb_interact_fwd with respect to its F vectors, composed of the functions above:
+    T as emb_interact_fwd hands it over (pooled vectors of Eq. (2) rounded to fp32, x in row 0), then the
+    chain rule of the interaction (Sec. 2.2).  -> dT float64 [B,F,d]."""
+    T, _ = emb_interact_fwd(tables, dtype, indices, offsets, tbl_off, x)
+    return interact_dot_bwd(T, dR)
+
+
 def interact_dot_bwd(T: np.ndarray, dR: np.ndarray) -> np.ndarray:
     """-> dT float64 [B,F,d]."""
     T = np.ascontiguousarray(T, dtype=np.float32)

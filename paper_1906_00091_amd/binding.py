@@ -71,6 +71,8 @@ def lib() -> C.CDLL:
         L.dlrm_emb_interact_fwd.argtypes = [sb, vp, vp, vp, i32, vp]
         L.dlrm_emb_interact_fwd_stamped.restype = i32
         L.dlrm_emb_interact_fwd_stamped.argtypes = [sb, vp, vp, vp, i32, vp, C.c_uint32, vp]
+        L.dlrm_emb_interact_bwd.restype = i32
+        L.dlrm_emb_interact_bwd.argtypes = [sb, vp, vp, vp, vp]
         L.dlrm_interact_dot_bwd.restype = i32
         L.dlrm_interact_dot_bwd.argtypes = [vp, vp, i32, i32, i32, vp, vp]
         L.dlrm_emb_bag_bwd_workspace_bytes.restype = sz
@@ -203,6 +205,15 @@ def dlrm_emb_interact_fwd_stamped(batch: SparseBatch, x: torch.Tensor, T: torch.
     _check("dlrm_emb_interact_fwd_stamped",
            lib().dlrm_emb_interact_fwd_stamped(batch.ref(), _ptr(x), _ptr(T), _ptr(R), algo,
                                                _ptr(stamp) + 4 * index, stamp_value & 0xFFFFFFFF, _stream()))
+
+
+def dlrm_emb_interact_bwd(batch: SparseBatch, x: torch.Tensor, dR: torch.Tensor, dT: torch.Tensor):
+    """dT of the interaction with the pooled vectors formed again from the tables (no T)."""
+    assert x.dtype == torch.float32 and x.is_contiguous() and x.shape == (batch.B, batch.d)
+    F = batch.K + 1
+    assert dR.dtype == torch.float32 and dR.is_contiguous() and dR.shape == (batch.B, batch.d + F * (F - 1) // 2)
+    assert dT.dtype == torch.float32 and dT.is_contiguous() and dT.shape == (batch.B, F, batch.d)
+    _check("dlrm_emb_interact_bwd", lib().dlrm_emb_interact_bwd(batch.ref(), _ptr(x), _ptr(dR), _ptr(dT), _stream()))
 
 
 def dlrm_interact_dot_bwd(T: torch.Tensor, dR: torch.Tensor, dT: torch.Tensor):

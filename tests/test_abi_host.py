@@ -70,7 +70,8 @@ def test_one_call_forward_rejects_bad_arguments_on_the_host():
     call = lambda b, x=p, T=p, R=p, algo=0: L.dlrm_emb_interact_fwd(C.byref(b), x, T, R, algo, None)
     assert call(_batch(tables=None)) == -1
     assert call(_batch(), x=None) == -1
-    assert call(_batch(), T=None) == -1
+    assert call(_batch(), T=None, algo=2) == -1        # only the one-launch path can do without T
+    assert call(_batch(nnz_total=800), T=None) == -1   # AUTO with long bags takes the separate calls
     assert call(_batch(), R=None) == -1
     assert call(_batch(K=128)) == -2                  # F = 129 vectors
     assert call(_batch(), x=C.c_void_p(0x1004)) == -2
@@ -78,6 +79,11 @@ def test_one_call_forward_rejects_bad_arguments_on_the_host():
     assert call(_batch(), algo=3) == -5
     assert call(_batch(K=65), algo=1) == -5           # the one-launch kernel takes up to 64 tables
     assert call(_batch(weights=0x1000), algo=1) == -5  # and no pooling weights
+    bwd = lambda b, x=p, dR=p, dT=p: L.dlrm_emb_interact_bwd(C.byref(b), x, dR, dT, None)
+    assert bwd(_batch(tables=None)) == -1
+    assert bwd(_batch(), x=None) == -1 and bwd(_batch(), dR=None) == -1 and bwd(_batch(), dT=None) == -1
+    assert bwd(_batch(), dT=C.c_void_p(0x1008)) == -2
+    assert bwd(_batch(K=65)) == -5 and bwd(_batch(weights=0x1000)) == -5
     st = lambda b, x=p, stamp=None: L.dlrm_emb_interact_fwd_stamped(C.byref(b), x, p, p, 0, stamp, 5, None)
     assert st(_batch(tables=None)) == -1                # the stamped call checks the same things first
     assert st(_batch(), x=None, stamp=C.c_void_p(0x1000)) == -1

@@ -225,6 +225,54 @@ def test_emb_interact_fwd_fused_matches_oracle_and_the_separate_calls(case):
         assert np.all(got[hot.FWD_FUSED][0][bb, k + 1].view(np.uint32) == 0)     # +0.0 exactly
 
 
+@pytest.mark.parametrize("case", PI_CASES, ids=[c[0] for c in PI_CASES])
+def test_emb_interact_bwd_without_T_gives_the_bits_of_the_backward_on_T(case):
+    """dlrm_emb_interact_fwd(T = NULL) + dlrm_emb_interact_bwd: the forward leaves T alone and gives the same
+    R; the backward pools the bags again and gives, bit for bit, what dlrm_interact_dot_bwd gives on the T of
+    the one-launch forward -- and matches the oracle's composed backward."""
+    name, K, B, d, dtype, rows, bag, dist, index32 = case
+    _say("emb_interact_bwd " + name)
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=5)
+    b = gen.make_batch(w)
+    host = _host_tables(b)
+    tables = upload_tables(host, dtype)
+    sb = make_sparse_batch(b, tables, index32=index32)
+    F, P = K + 1, (K + 1) * K // 2
+    rng = np.random.default_rng(K * 100 + d)
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    dR = rng.standard_normal((B, d + P)).astype(np.float32)
+    xd, dRd = torch.from_numpy(x).to(DEV), torch.from_numpy(dR).to(DEV)
+    T = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+    R = torch.empty((B, d + P), dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_interact_fwd(sb, xd, T, R, hot.FWD_FUSED)
+    R2 = torch.full((B, d + P), -5.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_interact_fwd(sb, xd, None, R2, hot.FWD_FUSED)
+    dT_ref = torch.empty((B, F, d), dtype=torch.float32, device=DEV)
+    hot.dlrm_interact_dot_bwd(T, dRd, dT_ref)
+    dT = torch.full((B, F, d), 7.0, dtype=torch.float32, device=DEV)
+    hot.dlrm_emb_interact_bwd(sb, xd, dRd, dT)
+    torch.cuda.synchronize()
+    assert torch.equal(R.view(torch.int32), R2.view(torch.int32))
+    assert torch.equal(dT.view(torch.int32), dT_ref.view(torch.int32))
+    want = oracle.emb_interact_bwd(host, dtype, b.indices, b.offsets, b.tbl_off, x, dR)
+    Th = T.cpu().numpy()
+    assert rel_err(dT.cpu().numpy(), oracle.interact_dot_bwd(Th, dR), scale_interact_bwd(Th, dR)) <= 1e-5
+    scaleT = scaleT_pad(scale_emb_fwd(host, dtype, b.indices, b.offsets, b.tbl_off), x)
+    assert rel_err(dT.cpu().numpy(), want, scale_interact_bwd(scaleT, dR)) <= 2e-5
+
+
+def test_emb_interact_fwd_without_T_needs_the_one_launch_path():
+    w = gen.custom_workload("long-bags", K=3, B=20, d=64, dtype=gen.F32, rows=400, bag=("uniform", 0, 40), seed=5)
+    b = gen.make_batch(w)
+    sb = make_sparse_batch(b, upload_tables(_host_tables(b), gen.F32))
+    x = torch.zeros((20, 64), dtype=torch.float32, device=DEV)
+    R = torch.zeros((20, 64 + 6), dtype=torch.float32, device=DEV)
+    for algo in (hot.FWD_SPLIT, hot.FWD_AUTO):      # AUTO takes the separate calls for bags this long
+        with pytest.raises(hot.DlrmError) as e:
+            hot.dlrm_emb_interact_fwd(sb, x, None, R, algo)
+        assert e.value.status == -1
+
+
 def scaleT_pad(scaleT, x):
     """|x| and the pooled magnitude scales laid out like T."""
     return np.concatenate([np.abs(x)[:, None, :].astype(np.float64), scaleT], axis=1).astype(np.float32)

@@ -583,3 +583,41 @@ def test_unit_weights_are_the_unweighted_functions_and_repeats_add_their_weights
     oracle.emb_bag_bwd_weighted(W, gen.F32, bb.indices, bb.offsets, bb.tbl_off, a, dS1, 1.0)
     assert np.array_equal(W[0][3], np.array([6.0 + 1.75, 7.0 + 3.5], dtype=np.float32))
     assert np.array_equal(W[0][1], np.array([2.0 - 1.0, 3.0 - 2.0], dtype=np.float32))
+
+
+def test_emb_interact_bwd_is_the_chain_rule_through_pooling_and_interaction():
+    """The composed backward against central finite differences of L = sum(R * U) with respect to the
+    dense vector and to the pooled vectors (moved through one table row of a one-index bag)."""
+    rng = np.random.default_rng(31)
+    K, B, d, m = 3, 4, 8, 6
+    tables = [rng.standard_normal((m, d)).astype(np.float32) for _ in range(K)]
+    bags = [[[int(rng.integers(0, m))] for _ in range(B)] for _ in range(K)]
+    bags[1][2] = [1, 4, 4]          # one multi-index bag with a repeat
+    b = gen.batch_from_lists([m] * K, bags, d)
+    x = rng.standard_normal((B, d)).astype(np.float32)
+    F = K + 1
+    U = rng.standard_normal((B, d + F * (F - 1) // 2)).astype(np.float32)
+    dT = oracle.emb_interact_bwd(tables, gen.F32, b.indices, b.offsets, b.tbl_off, x, U)
+
+    def loss(tabs, xx):
+        _, R = oracle.emb_interact_fwd(tabs, gen.F32, b.indices, b.offsets, b.tbl_off, xx)
+        return float((R * U).sum())
+    eps = 1e-3
+    for (bb, c) in ((0, 0), (3, 5)):                      # dense vector
+        xp, xm = x.copy(), x.copy()
+        xp[bb, c] += eps
+        xm[bb, c] -= eps
+        fd = (loss(tables, xp) - loss(tables, xm)) / (2 * eps)
+        assert abs(fd - dT[bb, 0, c]) <= 2e-3 * max(1.0, abs(fd))
+    # a table row looked up once, by bag (k=0, b=1) only: dL/dW = dT[b, k+1]
+    k, bb = 0, 1
+    r = bags[k][bb][0]
+    others = sum(1 for q in range(B) for i in bags[k][q] if i == r)
+    if others == 1:
+        for c in (2, 7):
+            tp = [t.copy() for t in tables]
+            tm = [t.copy() for t in tables]
+            tp[k][r, c] += eps
+            tm[k][r, c] -= eps
+            fd = (loss(tp, x) - loss(tm, x)) / (2 * eps)
+            assert abs(fd - dT[bb, k + 1, c]) <= 2e-3 * max(1.0, abs(fd))
