@@ -582,17 +582,24 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     prepared_ms = None
     if overlap:
         pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nbk)]
+        # which update every distinct batch takes is found first (a host read), so that the timed calls
+        # follow one another without the host in between
+        codes = []
         chk = torch.zeros(1, dtype=torch.int32, device=dev)
-        for i in range(nbk):
-            sb = dev_batches[(warmup + i) % nb][0]
-            hot.dlrm_emb_bag_bwd_prepare(sb, ws)
+        for bi in range(nb):
             code = hot.BWD_SORT_PREPARED
             if mode["ahead"]:
-                hot.dlrm_emb_bag_bwd_prepared_oversized(sb, ws, chk)
+                hot.dlrm_emb_bag_bwd_prepare(dev_batches[bi][0], ws)
+                hot.dlrm_emb_bag_bwd_prepared_oversized(dev_batches[bi][0], ws, chk)
                 if int(chk.item()) == 0:
                     code = hot.BWD_SORT_PREPARED_FLAT
+            codes.append(code)
+        for i in range(nbk):
+            bi = (warmup + i) % nb
+            sb = dev_batches[bi][0]
+            hot.dlrm_emb_bag_bwd_prepare(sb, ws)
             pe[i][0].record()
-            backward(sb, code)
+            backward(sb, codes[bi])
             pe[i][1].record()
         torch.cuda.synchronize()
         prepared_ms = sum(a.elapsed_time(b_) for a, b_ in pe) / nbk

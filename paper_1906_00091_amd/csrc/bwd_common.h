@@ -45,8 +45,13 @@ namespace dlrm {
 
 constexpr int kThreads = 256;
 constexpr int kNW = kThreads / DLRM_WAVE;       // wavefronts per workgroup
-constexpr int kItems = 16;                      // positions per thread in a partition tile
-constexpr int kTile = kThreads * kItems;        // 4096 positions per tile
+constexpr int kItems = 16;                      // positions per thread in a (large) partition tile
+constexpr int kTile = kThreads * kItems;        // 4096 positions per tile; batches below kSmallTileNnz lookups
+constexpr int kSmallItems = 4;                  // use tiles of 1024: four times the workgroups, a quarter of the
+constexpr int64_t kSmallTileNnz = 1 << 20;      // dependent steps each (the partition of a small batch is a chain
+                                                // of latencies on a mostly idle machine)
+// log2 of the partition tile for a batch of nnz lookups (host and device agree through GroupArgs::tile_shift)
+inline int tile_shift_for(int64_t nnz) { return nnz < kSmallTileNnz ? 10 : 12; }
 constexpr int kMaxTopBits = 10;                 // partition digit: up to 1024 buckets per table
 constexpr int kMaxBuckets = 1 << kMaxTopBits;
 constexpr int kDPT = kMaxBuckets / kThreads;    // partition digits owned by one thread
@@ -136,7 +141,7 @@ inline WsLayout ws_layout(int32_t K, int32_t B, int32_t d, int64_t nnz) {
   WsLayout L;
   size_t o = 0;
   const size_t n = (size_t)(nnz > 0 ? nnz : 1);
-  L.nt_max = nnz / kTile + K;
+  L.nt_max = (nnz >> tile_shift_for(nnz)) + K;
   L.max_huge = nnz / kHugeRun + K;
   for (int i = 0; i < 2; ++i) { L.keys[i] = o; o = align256(o + n * 4); }
   for (int i = 0; i < 2; ++i) { L.vals[i] = o; o = align256(o + n * 4); }
@@ -168,6 +173,7 @@ struct GroupArgs {            // everything the grouping kernels need
   PosEntry* pos_entry;        // weighted batches: bag and weight of every position, in the original order
   int32_t K, B;
   int32_t nt_max;
+  int32_t tile_shift;         // log2 of the positions per partition tile (10 or 12)
   int32_t top_bits;           // bits of the partition digit (0..kMaxTopBits)
   int32_t fused_scan;         // 1: the scatter derives its offsets from the raw tile counts
   int32_t no_tail;            // 1: small batch, the segment and hot-row launches are left out and
@@ -214,21 +220,22 @@ struct TileInfo {
   int t0;          // global index of the table's first tile
   int nt;          // tiles of the table
   int64_t start;   // global position of the tile's first item
-  int count;       // items in the tile (1..kTile)
+  int count;       // items in the tile (1 .. tile size)
   int64_t tbl_start;
   int total_tiles; // tiles of all tables
 };
 
 // Every workgroup rebuilds the tile map from tbl_off (K is small): tables own
-// ceil(nnz_k / kTile) consecutive tiles.  All threads must call this (it synchronises).
+// ceil(nnz_k / tile) consecutive tiles.  All threads must call this (it synchronises).
 __device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti, uint32_t* smem) {
   __shared__ int res[4];
+  const int64_t tsize = (int64_t)1 << a.tile_shift;
   if (threadIdx.x == 0) res[0] = -1;
   uint32_t carry = 0;
   for (int k0 = 0; k0 < a.K; k0 += kThreads) {
     const int k = k0 + threadIdx.x;
     uint32_t nt = 0;
-    if (k < a.K) nt = (uint32_t)((a.tbl_off[k + 1] - a.tbl_off[k] + kTile - 1) / kTile);
+    if (k < a.K) nt = (uint32_t)((a.tbl_off[k + 1] - a.tbl_off[k] + tsize - 1) >> a.tile_shift);
     uint32_t total;
     const uint32_t first = carry + block_exclusive_scan<kThreads>(nt, smem, &total);
     if (k < a.K && (uint32_t)tile >= first && (uint32_t)tile < first + nt) {
@@ -246,9 +253,9 @@ __device__ inline bool find_tile(const GroupArgs& a, int tile, TileInfo& ti, uin
   ti.nt = res[2];
   ti.t = tile - ti.t0;
   ti.tbl_start = a.tbl_off[ti.k];
-  ti.start = ti.tbl_start + (int64_t)ti.t * kTile;
+  ti.start = ti.tbl_start + ((int64_t)ti.t << a.tile_shift);
   const int64_t rem = a.tbl_off[ti.k + 1] - ti.start;
-  ti.count = (int)(rem < kTile ? rem : kTile);
+  ti.count = (int)(rem < tsize ? rem : tsize);
   return true;
 }
 
@@ -499,6 +506,7 @@ inline void fill_group_args(GroupArgs& g, const dlrm_sparse_batch* s, const WsLa
   g.K = s->K;
   g.B = s->B;
   g.nt_max = (int32_t)L.nt_max;
+  g.tile_shift = tile_shift_for(s->nnz_total);
   // partition digit: one workgroup per bucket, so aim at >= ~1536 buckets when the batch is
   // large enough, with 128..1024 pairs per bucket (measured on the 8 x 1M x 64 multi-hot batch:
   // 800 pairs per bucket beat 200 by 8%); never more digits than the row ids have

@@ -73,12 +73,13 @@ __global__ __launch_bounds__(kThreads) void heads_write_kernel(GroupArgs a) {
   if (!find_tile(a, blockIdx.x, ti, smem)) return;
   const uint32_t* keys = a.keys[0];
   const uint32_t base = a.tile_heads[blockIdx.x];
-  // thread t owns the contiguous positions [t*kItems, (t+1)*kItems) so that heads keep their order
+  // thread t owns the contiguous positions [t*per, (t+1)*per) so that heads keep their order
+  const int per = 1 << (a.tile_shift - 8);   // positions per thread: tile / kThreads
   uint32_t flags = 0, cnt = 0;
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
-    const int li = threadIdx.x * kItems + j;
-    if (li < ti.count && is_head(keys, ti.start + li, ti.tbl_start)) {
+    const int li = threadIdx.x * per + j;
+    if (j < per && li < ti.count && is_head(keys, ti.start + li, ti.tbl_start)) {
       flags |= 1u << j;
       ++cnt;
     }
@@ -88,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void heads_write_kernel(GroupArgs a) {
 #pragma unroll
   for (int j = 0; j < kItems; ++j) {
     if (flags & (1u << j)) {
-      a.seg_start[pos] = (uint32_t)(ti.start + threadIdx.x * kItems + j);
+      a.seg_start[pos] = (uint32_t)(ti.start + threadIdx.x * per + j);
       a.seg_tbl[pos] = (uint32_t)ti.k;
       ++pos;
     }

@@ -39,8 +39,9 @@ __global__ __launch_bounds__(kThreads) void bucket_scan_kernel(GroupArgs a) {
   const int k = blockIdx.x;
   // first tile of table k = tiles of all earlier tables
   uint32_t t0 = 0;
-  for (int j = 0; j < k; ++j) t0 += (uint32_t)((a.tbl_off[j + 1] - a.tbl_off[j] + kTile - 1) / kTile);
-  const int nt = (int)((a.tbl_off[k + 1] - a.tbl_off[k] + kTile - 1) / kTile);
+  const int64_t tile = (int64_t)1 << a.tile_shift;
+  for (int j = 0; j < k; ++j) t0 += (uint32_t)((a.tbl_off[j + 1] - a.tbl_off[j] + tile - 1) >> a.tile_shift);
+  const int nt = (int)((a.tbl_off[k + 1] - a.tbl_off[k] + tile - 1) >> a.tile_shift);
   const int nb = 1 << a.top_bits;
   uint32_t carry = (uint32_t)a.tbl_off[k];
   if (nt <= 0) {
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scan_kernel(GroupArgs a) {
   // round costs one workgroup scan (the kernel shares the machine with the forward pass, where every
   // dependent round trip to memory is several microseconds)
   constexpr int kScanItems = 16;
-  const uint32_t n = (uint32_t)nt * (uint32_t)nb;   // < 2^31: nt <= nnz / kTile + 1, nb <= 1024
+  const uint32_t n = (uint32_t)nt * (uint32_t)nb;   // < 2^31: nt <= nnz / tile + 1 (<= 1024 + 1 with small tiles), nb <= 1024
   for (uint32_t e0 = 0; e0 < n; e0 += kThreads * kScanItems) {
     uint32_t v[kScanItems], digit[kScanItems], t[kScanItems];
     size_t addr[kScanItems];
@@ -95,12 +96,14 @@ __global__ __launch_bounds__(kThreads) void bucket_scan_kernel(GroupArgs a) {
 
 
 // --- 3. stable scatter into buckets ---------------------------------------------------
-template <typename IT>
+// ITEMS positions per thread: the tile holds kThreads * ITEMS positions (GroupArgs::tile_shift agrees)
+template <typename IT, int ITEMS>
 __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
+  constexpr int TILE = kThreads * ITEMS;
   __shared__ uint32_t wcnt[kNW][kMaxBuckets];
   __shared__ uint32_t gofs[kMaxBuckets];
-  __shared__ uint32_t skey[kTile];
-  __shared__ uint32_t sval[kTile];
+  __shared__ uint32_t skey[TILE];
+  __shared__ uint32_t sval[TILE];
   __shared__ uint32_t smem[kNW + 1];
   __shared__ int sflag[1];
   TileInfo ti;
@@ -114,11 +117,11 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
   // (wave-striped) and, for small batches, this digit's counts in all tiles of the table
   const IT* kin = static_cast<const IT*>(a.indices) + ti.start;
   const int shift = top_shift(a, ti.k);
-  uint32_t key[kItems], val[kItems], dg[kItems], rnk[kItems];
-  bool ok[kItems];
+  uint32_t key[ITEMS], val[ITEMS], dg[ITEMS], rnk[ITEMS];
+  bool ok[ITEMS];
 #pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
+  for (int j = 0; j < ITEMS; ++j) {
+    const int li = w * (DLRM_WAVE * ITEMS) + j * DLRM_WAVE + lane;
     ok[j] = li < ti.count;
     key[j] = ok[j] ? (uint32_t)kin[li] : 0xFFFFFFFFu;
     dg[j] = (key[j] >> shift) & mask;
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
     hi = nhi;
   }
   const int b0 = lo;
-  for (int i = tid; i < kTile; i += kThreads) skey[i] = 0;  // skey doubles as the bag-start counters
+  for (int i = tid; i < TILE; i += kThreads) skey[i] = 0;  // skey doubles as the bag-start counters
   for (int i = tid; i < kNW * kMaxBuckets; i += kThreads) (&wcnt[0][0])[i] = 0;
   __syncthreads();
   for (int base = b0 + 1;; base += kThreads) {  // bags that start inside the tile (after P0)
@@ -186,27 +189,27 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
     // a round whose first bag is inside may still have later bags inside, so go on
     if (done) break;
   }
-  {  // inclusive prefix of the start counters, thread t owning positions [t*kItems, (t+1)*kItems)
-    uint32_t c[kItems], s = 0;
+  {  // inclusive prefix of the start counters, thread t owning positions [t*ITEMS, (t+1)*ITEMS)
+    uint32_t c[ITEMS], s = 0;
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-      c[j] = skey[tid * kItems + j];
+    for (int j = 0; j < ITEMS; ++j) {
+      c[j] = skey[tid * ITEMS + j];
       s += c[j];
     }
     uint32_t total;
     uint32_t run = block_exclusive_scan<kThreads>(s, smem, &total);
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
+    for (int j = 0; j < ITEMS; ++j) {
       run += c[j];
-      sval[tid * kItems + j] = (uint32_t)b0 + run;
+      sval[tid * ITEMS + j] = (uint32_t)b0 + run;
     }
   }
   __syncthreads();
 
   // ---- bags of this thread's (wave-striped) positions, then rank by partition digit
 #pragma unroll
-  for (int j = 0; j < kItems; ++j) {
-    const int li = w * (DLRM_WAVE * kItems) + j * DLRM_WAVE + lane;
+  for (int j = 0; j < ITEMS; ++j) {
+    const int li = w * (DLRM_WAVE * ITEMS) + j * DLRM_WAVE + lane;
     val[j] = ok[j] ? sval[li] : 0u;
     if (a.weights != nullptr && ok[j]) {  // uniform branch: weighted batch
       PosEntry pe;
@@ -216,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
       val[j] = (uint32_t)(P0 + li);       // position inside the table
     }
   }
-  rank_items<kItems, kMaxBuckets>(dg, ok, a.top_bits, wcnt, rnk);
+  rank_items<ITEMS, kMaxBuckets>(dg, ok, a.top_bits, wcnt, rnk);
   __syncthreads();
 
   // ---- destination offsets of this tile's digits
@@ -249,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void bucket_scatter_kernel(GroupArgs a) {
 
   // ---- stage in LDS in sorted order so that one digit's global writes are contiguous
 #pragma unroll
-  for (int j = 0; j < kItems; ++j) {
+  for (int j = 0; j < ITEMS; ++j) {
     if (ok[j]) {
       const uint32_t lp = wcnt[w][dg[j]] + rnk[j];
       skey[lp] = key[j];
@@ -278,10 +281,18 @@ int enqueue_partition(const dlrm_sparse_batch* s, const GroupArgs& g, hipStream_
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(s->K), dim3(kThreads), 0, st, g);
     DLRM_CHECK_LAUNCH();
   }
-  if (g.idx32)
-    hipLaunchKernelGGL(bucket_scatter_kernel<int32_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
-  else
-    hipLaunchKernelGGL(bucket_scatter_kernel<int64_t>, dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  const bool small = g.tile_shift == 10;
+  if (g.idx32) {
+    if (small)
+      hipLaunchKernelGGL((bucket_scatter_kernel<int32_t, kSmallItems>), dim3(g.nt_max), dim3(kThreads), 0, st, g);
+    else
+      hipLaunchKernelGGL((bucket_scatter_kernel<int32_t, kItems>), dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  } else {
+    if (small)
+      hipLaunchKernelGGL((bucket_scatter_kernel<int64_t, kSmallItems>), dim3(g.nt_max), dim3(kThreads), 0, st, g);
+    else
+      hipLaunchKernelGGL((bucket_scatter_kernel<int64_t, kItems>), dim3(g.nt_max), dim3(kThreads), 0, st, g);
+  }
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }

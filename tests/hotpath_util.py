@@ -41,6 +41,20 @@ def rel_err(got: np.ndarray, ref: np.ndarray, scale: np.ndarray, floor: float = 
     return float(np.max(np.where(err == 0.0, 0.0, err / np.maximum(scale, tiny))))
 
 
+def plain_metrics(got: np.ndarray, ref: np.ndarray):
+    """The two plain figures beside the gate (reported, not gated): max |got - ref| / max(|ref|, tau) with the
+    floor tau = 1e-3 * max|ref| per tensor, and the infinity-norm ratio max|got - ref| / max|ref|."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0, 0.0
+    err = np.abs(got - ref)
+    top = float(np.abs(ref).max())
+    if top == 0.0:
+        return float(err.max()), float(err.max())
+    return float((err / np.maximum(np.abs(ref), 1e-3 * top)).max()), float(err.max() / top)
+
+
 def abs_f32_tables(host_tables, dtype):
     """|W| as fp32 arrays (exact for every storage type)."""
     return [np.abs(widen_host(t, dtype)).astype(np.float32) for t in host_tables]

@@ -557,7 +557,7 @@ def test_oversized_count_and_the_reduce_launch_alone(case):
 
 ADAGRAD_CASES = [c for c in BWD_CASES if c[0] in (
     "tiny-shape", "multi-tile-ragged", "hot-rows", "d48-nonpow2", "f16-d128-fixed32", "bf16-d64",
-    "many-hot-rows", "dominant-rows-large-rest", "dense-hot-rows-d64")]
+    "many-hot-rows", "dominant-rows-large-rest", "dense-hot-rows-d64", "one-row-table")]
 
 
 @pytest.mark.parametrize("fresh", [False, True], ids=["warm-state", "fresh-state"])
@@ -567,7 +567,8 @@ def test_emb_bag_bwd_adagrad_matches_oracle(case, fresh):
     Error model: the fp32 sum g carries |dg| <= n 2^-24 S_g (S_g = sum of |terms|); h + g^2 has only
     positive terms, so h is compared relative to h0 + S_g^2; d(step)/dg is at most lr / (sqrt(h0) + eps),
     so W is compared relative to |W| + lr S_g / (sqrt(h0) + eps).  With a fresh state (h0 = 0) that bound is
-    vacuous where g cancels to ~0 (the step is lr*sign(g) there): those elements are left out."""
+    vacuous where g cancels to ~0 (the step is lr*sign(g) there): those elements are held to |dW| <= lr and
+    to the comparison of h, which carries g."""
     name, K, B, d, dtype, rows, bag, dist = case
     _say("emb_bag_bwd_adagrad %s fresh=%s" % (name, fresh))
     w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=8)
@@ -611,10 +612,17 @@ def test_emb_bag_bwd_adagrad_matches_oracle(case, fresh):
         if fresh:
             g_ref = np.sqrt(ref_h[k][u].astype(np.float64))      # |g| (h0 = 0)
             ok = g_ref >= 1e-3 * S
-            assert ok.mean() > 0.9
             scale = w0 + lr
             err = np.abs(gw.astype(np.float64) - rw.astype(np.float64)) / np.maximum(scale, SCALE_FLOOR[dtype])
-            assert err[ok].max() <= TOL[dtype]
+            if ok.any():
+                assert err[ok].max() <= TOL[dtype]
+            # where g cancels to ~0 the step lr*g/(|g| + eps) may take either sign: no element-wise comparison,
+            # but the step is at most lr in size on both sides (plus one rounding of the stored type), and h,
+            # which carries g, has been compared above
+            ulp = np.abs(gw) * (2.0 ** -23 if dtype == gen.F32 else 2.0 ** -10 if dtype == gen.F16 else 2.0 ** -7)
+            w_before = widen_host(host[k][u], dtype)
+            assert np.all(np.abs(gw - w_before) <= lr * (1 + 1e-6) + ulp + SCALE_FLOOR[dtype])
+            assert np.all(np.abs(rw - w_before) <= lr * (1 + 1e-6) + ulp + SCALE_FLOOR[dtype])
         else:
             scale = w0 + lr * S / (np.sqrt(h0[k][u].astype(np.float64)) + eps)
             assert rel_err(gw, rw, scale, SCALE_FLOOR[dtype]) <= TOL[dtype]
