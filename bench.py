@@ -73,6 +73,15 @@ def parse_args():
     ap.add_argument("--algo", default="auto", choices=["auto", "sort", "atomic"])
     ap.add_argument("--optimizer", default="sgd", choices=["sgd", "adagrad"],
                     help="row update of the fused backward (the metric is quoted on sgd)")
+    ap.add_argument("--tables", type=int, default=0, metavar="K",
+                    help="free-form workload instead of one of the five (any of --tables --rows --dim --batch --bag "
+                         "--dist --dtype; what is not given is taken from workload 3): K tables")
+    ap.add_argument("--rows", type=int, default=0, help="free-form workload: rows per table")
+    ap.add_argument("--dim", type=int, default=0, help="free-form workload: embedding dimension")
+    ap.add_argument("--batch", type=int, default=0, help="free-form workload: mini-batch size")
+    ap.add_argument("--bag", default="", help="free-form workload: bag length, L (fixed) or LO:HI (uniform, inclusive)")
+    ap.add_argument("--dist", default="", help="free-form workload: index distribution, uniform or zipf:ALPHA")
+    ap.add_argument("--dtype", default="", choices=["", "f32", "f16", "bf16"], help="free-form workload: table storage")
     ap.add_argument("--locality", type=float, default=0.0, metavar="ALPHA",
                     help="draw the workload's indices with the stack-distance trace generator of Sec. 4.2 from the "
                          "profile of a Zipf(ALPHA) trace instead of the workload's own distribution: same shape, "
@@ -183,6 +192,25 @@ def stats(xs):
             "min": round(float(a.min()), 5), "max": round(float(a.max()), 5), "n": int(a.size)}
 
 
+def free_form_workload(args):
+    """The workload the free-form flags describe (None if none is given); defaults from workload 3."""
+    from workloads import gen
+    if not (args.tables or args.rows or args.dim or args.batch or args.bag or args.dist or args.dtype):
+        return None
+    base = gen.WORKLOADS[3]
+    bag = base.bag
+    if args.bag:
+        lo, _, hi = args.bag.partition(":")
+        bag = ("uniform", int(lo), int(hi)) if hi else ("fixed", int(lo))
+    dist = base.dist
+    if args.dist:
+        name, _, alpha = args.dist.partition(":")
+        dist = ("zipf", float(alpha)) if name == "zipf" else ("uniform",)
+    dtype = {"": base.dtype, "f32": gen.F32, "f16": gen.F16, "bf16": gen.BF16}[args.dtype]
+    return gen.custom_workload("custom", K=args.tables or base.K, B=args.batch or base.B, d=args.dim or base.d,
+                               dtype=dtype, rows=args.rows or int(base.rows[1]), bag=bag, dist=dist)
+
+
 def run_workload(args, config, steps, warmup, headline, ceil):
     """Times `steps` steps of workload `config` after `warmup`; returns the fields of its JSON object.
     headline: also the CPU-oracle baseline and the self-check; otherwise a shorter record."""
@@ -195,7 +223,10 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     from workloads import gen
 
     dev = "cuda:0"
-    w = gen.locality_workload(config, args.locality) if args.locality > 0 else gen.WORKLOADS[config]
+    w = free_form_workload(args) if config == 0 else gen.WORKLOADS[config]
+    if args.locality > 0:
+        import dataclasses
+        w = dataclasses.replace(w, name="%s_trace_a%g" % (w.name, args.locality), dist=("trace", float(args.locality)))
     print("bench.py: workload %d (%s), %d steps" % (config, w.name, steps), file=sys.stderr, flush=True)
     eb = gen.ELEM_BYTES[w.dtype]
     algo = {"auto": hot.BWD_AUTO, "sort": hot.BWD_SORT, "atomic": hot.BWD_ATOMIC}[args.algo]
@@ -673,8 +704,8 @@ def run_workload(args, config, steps, warmup, headline, ceil):
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     traffic, traffic_note = None, "no counter run on record for this workload and kernel"
     rec = measured_traffic().get((config, dom))
-    if adagrad or args.weighted or args.index32:
-        traffic_note = "counter runs are on record for sum pooling, SGD, int64 indices only"
+    if adagrad or args.weighted or args.index32 or args.locality > 0 or config == 0:
+        traffic_note = "counter runs are on record for the five workloads with sum pooling, SGD, int64 indices only"
     elif rec is not None:
         if rec[1] == source_digest():
             traffic, traffic_note = rec[0], "profiles/measured_traffic.md (rocprofv3 --pmc runs on these sources)"
@@ -848,12 +879,13 @@ def main():
         return
     # what this board sustains for plain access patterns (a few seconds, 8 GiB), before the workloads
     ceil = None if args.no_cpu_baseline else measure_ceilings(torch, ceilings)
-    config = args.config if args.config else 3
+    custom = free_form_workload(args) is not None
+    config = 0 if custom else (args.config if args.config else 3)
     out = run_workload(args, config, args.steps, args.warmup, True, ceil)
     if ceil is not None:
         out["board_ceilings"] = dict(ceil, unit="GB/s", note="plain memory kernels (libdlrm_ceilings) on this board: "
                                      "4 GiB streamed; 1.5 GB of distinct random rows of a 2 GiB table")
-    if not args.config and not args.no_extra and not args.graph and not args.locality > 0:
+    if not args.config and not custom and not args.no_extra and not args.graph and not args.locality > 0:
         keep = ("steps", "warmup", "ms_per_step", "value", "unit", "samples_per_s", "dtype", "ms_per_step_chunks",
                 "ms_per_step_same_batch", "emb_fwd_bwd", "emb_fwd_bwd_prepared", "stage_ms", "stage_ms_median",
                 "emb_interact_fwd_ms", "emb_interact_bwd_ms", "emb_bag_bwd_prepared_ms", "stage_algorithmic_GBps", "state_after_run", "roofline")

@@ -294,10 +294,14 @@ struct SplitLds {
   uint32_t nc;
 };
 
-__device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd) {
+// nc: number of candidates (uniform); most oversized buckets have one or two
+__device__ inline uint32_t class_of(uint32_t key, const uint32_t* cd, uint32_t nc) {
   uint32_t cls = (uint32_t)kCand;
 #pragma unroll
-  for (int c = 0; c < kCand; ++c) cls = key == cd[c] ? (uint32_t)c : cls;
+  for (int c = 0; c < kCand; ++c) {
+    if ((uint32_t)c >= nc) break;  // uniform
+    cls = key == cd[c] ? (uint32_t)c : cls;
+  }
   return cls;
 }
 
@@ -401,7 +405,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
     for (int q = 0; q < 8; ++q) {
       const uint32_t i = i0 + q * DLRM_WAVE + lane;
       const bool valid = i < q1;
-      const uint32_t cls = class_of(kk[q], cd);
+      const uint32_t cls = class_of(kk[q], cd, nc);
       const unsigned long long vm = __ballot(valid);
       if (vm == 0ull) continue;  // wave-uniform
       const int first = __ffsll((long long)vm) - 1;
@@ -467,7 +471,7 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
     for (int q = 0; q < 8; ++q) {
       const uint32_t i = i0 + q * DLRM_WAVE + lane;
       const bool valid = i < q1;
-      const uint32_t cls = class_of(key[q], cd);
+      const uint32_t cls = class_of(key[q], cd, nc);
       unsigned long long rem = __ballot(valid);
       uint32_t dst = 0;
       while (rem != 0ull) {  // wave-uniform: one round per class present in the step

@@ -26,3 +26,16 @@ def test_timed_step_sequence_gives_the_tables_of_the_call_by_call_sequence(extra
     assert line["n_gpus"] == 1 and line["steps"] == 8 and line["value"] > 0
     assert line["config"]["workload"].startswith("3:")
     assert "roofline" in line and line["roofline"]["frac"] > 0
+
+
+def test_free_form_workload_and_trace_locality_flags_run():
+    """bench.py on a workload described on the command line, and on workload 1 with trace-generated indices."""
+    for extra, tag in (["--tables", "3", "--rows", "5000", "--dim", "32", "--batch", "256", "--bag", "1:9", "--dist",
+                        "zipf:1.1", "--dtype", "bf16"], "0:custom"), (["--config", "1", "--locality", "1.1"], "1:tiny_trace"):
+        cmd = [sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "6", "--warmup", "2", "--no-cpu-baseline"] + extra
+        r = subprocess.run(cmd, capture_output=True, text=True, timeout=600, cwd=ROOT)
+        assert r.returncode == 0, r.stderr[-2000:]
+        line = json.loads(r.stdout.strip().splitlines()[-1])
+        assert line["config"]["workload"].startswith(tag) and line["value"] > 0
+        assert line["state_after_run"]["finite"] and line["roofline"]["traffic"] is None
+        assert "per_workload" not in line
