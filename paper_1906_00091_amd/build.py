@@ -70,5 +70,31 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(out_dir: str) -> str:
+    """The method's library once more with AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code
+    (argument checks, launch geometry, workspace layout); the device code is compiled as usual (-O1 here:
+    this build exists to be checked, not timed).  Returns the path of the library under out_dir."""
+    hipcc = _hipcc()
+    os.makedirs(out_dir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-O3"] + ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host",
+                                                       "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=all"]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(out_dir, src.replace(".hip", ".o"))
+        r = subprocess.run([hipcc] + flags + ["-c", os.path.join(CSRC, src), "-o", obj], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(compile_one, SOURCES))
+    lib = os.path.join(out_dir, "libdlrm_hot_hostsan.so")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                        "-o", lib] + objs, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return lib
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose="-v" in sys.argv))
