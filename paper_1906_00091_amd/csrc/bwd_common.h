@@ -579,6 +579,8 @@ int run_reduce_adagrad_weighted(const GroupArgs& g, const UpdArgs& u, int dtype,
                                 const dlrm_bwd_timing* tm, hipStream_t st);
 // bwd_tail.hip
 int launch_segment_sort(const GroupArgs& g, hipStream_t st);
-int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, hipStream_t st);
+// *dense_groups_used: bag groups the dense kernel wrote partial sums for (tables it took; the others: ngroups)
+int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, int* dense_groups_used,
+                    hipStream_t st);
 
 }  // namespace dlrm

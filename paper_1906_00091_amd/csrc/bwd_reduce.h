@@ -601,7 +601,7 @@ __global__ __launch_bounds__(kThreads) void segment_reduce_kernel(GroupArgs a, U
 // A lane group per hot run adds the run's partial sums in bag-group order and updates the row.
 // A launch of its own: the kernel boundary orders it after every partial, at no fence.
 template <int DT, int G, int OPT, bool WT>
-__global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdArgs u, int ngroups) {
+__global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdArgs u, int ngroups, int ngd) {
   constexpr int S = DLRM_WAVE / G;
   const int k = blockIdx.y;
   const uint32_t nruns = a.hot_cnt[k];
@@ -610,18 +610,20 @@ __global__ __launch_bounds__(kThreads) void hot_finish_kernel(GroupArgs a, UpdAr
   const int lane = lane_id();
   const int chunk = lane % G;
   if (chunk * 4 >= u.d) return;
+  // a table the dense kernel took has partial sums for its own (fewer) bag groups, in the same layout
+  const int nsum = (!WT && nruns >= (uint32_t)kDenseFrom) ? ngd : ngroups;
   char* W = static_cast<char*>(u.tables[k]);
   float* H = state_base<OPT>(u, k);
   for (uint32_t r = (blockIdx.x * kNW + wave_id()) * S + lane / G; r < nruns; r += gridDim.x * kNW * S) {
     const float* part = a.huge_part + ((size_t)(base + r) * ngroups) * u.d + chunk * 4;
     f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int g0 = 0; g0 < ngroups; g0 += 8) {
+    for (int g0 = 0; g0 < nsum; g0 += 8) {
       f32x4 v[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = loadf4(part + (size_t)(g0 + q < ngroups ? g0 + q : g0) * u.d);
+      for (int q = 0; q < 8; ++q) v[q] = loadf4(part + (size_t)(g0 + q < nsum ? g0 + q : g0) * u.d);
 #pragma unroll
       for (int q = 0; q < 8; ++q)
-        if (g0 + q < ngroups) sum += v[q];
+        if (g0 + q < nsum) sum += v[q];
     }
     row_update<DT, OPT>(W, H, u, a.huge_runs[base + r].row, chunk, sum);
   }
@@ -642,9 +644,10 @@ static int launch_reduce(const GroupArgs& g, const UpdArgs& u, int K, const dlrm
   hipLaunchKernelGGL((segment_reduce_kernel<DT, G, OPT, WT>), dim3(seg_tiles), dim3(kThreads), 0, st, g, u);
   DLRM_CHECK_LAUNCH();
   const int ng = hot_groups(g.B, u.d);
-  rc = launch_hot_rows(g, u, G, K, ng, st);
+  int ngd = ng;
+  rc = launch_hot_rows(g, u, G, K, ng, &ngd, st);
   if (rc != DLRM_OK) return rc;
-  hipLaunchKernelGGL((hot_finish_kernel<DT, G, OPT, WT>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng);
+  hipLaunchKernelGGL((hot_finish_kernel<DT, G, OPT, WT>), dim3(4, K), dim3(kThreads), 0, st, g, u, ng, ngd);
   DLRM_CHECK_LAUNCH();
   return DLRM_OK;
 }

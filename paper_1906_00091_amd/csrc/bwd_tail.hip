@@ -307,204 +307,260 @@ __global__ __launch_bounds__(kThreads) void hot_rows_kernel(GroupArgs a, UpdArgs
 // --- 5b. many hot rows in one table: the same pass as a dense product on the matrix cores -----------
 // With many hot rows per table (a skewed table: the hottest few are in nearly every bag) the kernel
 // above reads a gradient row from LDS once per (hot row, bag) that meets, and LDS reads are what it
-// spends its time on.  Here the multiplicities of kDenseRuns hot rows against the bags of a tile
-// are first counted into a small matrix C[bag][run] in LDS (integer atomics: exact, order-free);
-// then G_hot[run][col] += sum_bag C[bag][run] * dS[bag][col] is a dense contraction over the bags
-// of the tile, done with v_mfma_f32_16x16x4_f32: runs are the M index (two blocks of 16), columns
-// the N index (blocks of 16, dealt to the wavefronts), four bags per instruction.  Every gradient
-// row is read from LDS once per tile, and the accumulators are the instruction's result registers.
-// The same workgroup grid, bag groups, run lists and partial-sum layout as hot_rows_kernel (which
-// keeps the tables with few hot rows and the weighted batches); hot_finish_kernel follows.
+// spends its time on.  Here the multiplicities of kDenseRuns hot rows against a tile of bags are
+// first counted into a small matrix C[run][bag] in LDS (integer atomics: exact, order-free); then
+// G_hot[run][col] += sum_bag C[run][bag] * dS[bag][col] is a dense contraction over the bags of the
+// tile, done with v_mfma_f32_16x16x4_f32: runs are the M index (two blocks of 16), four bags per
+// instruction.
+//
+// Every wavefront works alone: it owns a quarter of the workgroup's bags, its own count matrix and
+// accumulators for all runs and columns, and takes its gradient rows straight from global memory,
+// so there is no barrier anywhere in the streaming loop and wavefronts in different phases
+// (list reads, counting, contraction) fill each other's gaps.  The four partial results are added
+// in bag order at the end.
 //   16x16x4 layout: lane l supplies A[m = l%16][k = l/16] and B[k = l/16][n = l%16] and holds
 //   D[m = 4*(l/16) + v][n = l%16] in element v of its accumulator.
-constexpr int kDenseRuns = 32;     // hot rows per pass of a workgroup
-constexpr int kDenseStage = 8;     // float4 registers per thread holding the next tile
-constexpr int kDenseTileFloats = 8192;
-constexpr int kDenseDeep = 4;      // 64-entry chunks of one run's list in flight while counting
+//   Which column the N index n stands for is free as long as B and D agree: lane l loads the 16 bytes
+//   dS[bag k][64h + 4n .. 64h + 4n + 3] with one instruction (a bag row is read as contiguous 256-byte
+//   pieces) and component c of that load is the B operand of contraction (h, c), whose result
+//   column n is gradient column 64h + 4n + c.
+// The same bag groups, run lists and partial-sum layout as hot_rows_kernel (which keeps the
+// tables with few hot rows and the weighted batches); hot_finish_kernel follows.
+// A count of zero still multiplies the bag's gradient: a non-finite gradient entry of a bag reaches
+// every hot row of this pass, not only the rows the bag looked up.
+constexpr int kDenseRuns = 32;      // hot rows per pass of a workgroup
+constexpr int kDenseTile = 64;      // bags per tile of a wavefront
+constexpr int kDenseCStride = 68;   // words per run of the count matrix: 4m + k is a different bank for all 64 lanes
+constexpr int kDensePre = 4;        // 4-bag steps of gradient rows in flight
+constexpr int kDenseHeavy = 4;      // the longest runs of a pass: 256 list entries per request instead of 64
 
-template <int G>
-__global__ __launch_bounds__(kThreads) void hot_rows_dense_kernel(GroupArgs a, UpdArgs u, int ngroups) {
-  constexpr int R = kDenseRuns;
-  constexpr int NG = kThreads / G;                 // lane groups = gradient rows staged per pass
-  constexpr int NP = G < kDenseStage ? G : kDenseStage;   // float4 staging registers: tiles of at most 256 bags
-  constexpr int TB = NG * NP;                      // bags per tile: TB * d <= kDenseTileFloats
-  constexpr int GB = NG * kHotStagePasses * kHotTilesPerGroup;  // bags per workgroup, as in hot_rows_kernel
-  constexpr int RW = R / kNW;                      // runs whose entries one wavefront counts
-  constexpr int NBLK = (G * 4 + 15) / 16;          // 16-column blocks of a gradient row (d <= 4G)
-  constexpr int NBW = (NBLK + kNW - 1) / kNW;      // of which a wavefront takes blocks w, w + kNW, ...
-  static_assert(TB * G * 4 <= kDenseTileFloats, "tile");
-  __shared__ float tile[kDenseTileFloats];
-  __shared__ uint32_t cmat[TB][R];                 // multiplicity of run r in bag tb0 + b
-  __shared__ uint32_t rpos[R], rend[R], rsrc[R];   // first entry of a run for this workgroup's bags, its end, its pair buffer
+template <int NH>   // 64-column pieces of a gradient row
+__global__ __launch_bounds__(kThreads, NH <= 2 ? 3 : 2) void hot_rows_dense_kernel(GroupArgs a, UpdArgs u, int ngroups,
+                                                                                   int group_bags) {
+  constexpr int R = kDenseRuns, TB = kDenseTile, CS = kDenseCStride, PRE = NH <= 2 ? kDensePre : kDensePre / 2;
+  static_assert(R * CS * kNW >= R * 64 * NH, "the reduction buffer aliases the count matrices");
+  __shared__ __align__(16) uint32_t cmat[kNW][R * CS];   // per wavefront: multiplicity of run r in bag tb0 + b at [r * CS + b]
   const int k = blockIdx.y, g = blockIdx.x;
   const uint32_t nruns = a.hot_cnt[k];
   if (nruns < (uint32_t)kDenseFrom) return;  // uniform: hot_rows_kernel has this table
   const uint32_t base = hot_list_base(a, k);
-  const int lane = lane_id(), w = wave_id(), tid = threadIdx.x;
-  const int chunk = lane % G;
-  const int grp = tid / G;
-  const bool col_ok = chunk * 4 < u.d;
-  const int cchunk = col_ok ? chunk : 0;  // lanes past the last column shadow column group 0, never store
-  const int bag_lo = g * GB;
-  const int bag_hi = bag_lo + GB < a.B ? bag_lo + GB : a.B;
-  if (bag_lo >= bag_hi) return;  // uniform
-  const float* gk = u.dS + (int64_t)k * u.stride_k + cchunk * 4;
+  const int lane = lane_id(), w = wave_id();
+  const int m = lane & 15, kk = lane >> 4;
+  // this wavefront's bags
+  const int quarter = group_bags / kNW;
+  int wb_lo = g * group_bags + w * quarter;
+  wb_lo = wb_lo < a.B ? wb_lo : a.B;
+  const int wb_hi = wb_lo + quarter < a.B ? wb_lo + quarter : a.B;
+  const float* gk = u.dS + (int64_t)k * u.stride_k + 4 * m;
+  // lanes whose columns lie past the row's end load piece 0 again (no branch around a load) and never store
+  bool col_ok[NH];
+  int hoff[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    col_ok[h] = 64 * h + 4 * m < u.d;
+    hoff[h] = col_ok[h] ? 64 * h : 0;
+  }
+  uint32_t* cm = cmat[w];
+  float* red = reinterpret_cast<float*>(&cmat[0][0]);
   const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
   for (uint32_t r0 = 0; r0 < nruns; r0 += R) {  // uniform
-    __syncthreads();
-    // where each run's entries for this workgroup's bags begin (one binary search per run; the tile
-    // boundaries are found on the way, a run's bags ascend) and where the run ends
-    for (int rl = tid; rl < R; rl += kThreads) {
-      const uint32_t r = r0 + (uint32_t)rl;
-      uint32_t c = 0, e = 0, src = 0;
-      if (r < nruns) {
-        const HugeRun hr = a.huge_runs[base + r];
+    // lane r keeps the state of one run of this pass: next entry for this wavefront's bags (a binary
+    // search: a run's bags ascend), end of the run, pair buffer that holds it.  The runs are dealt to
+    // the lanes by length, longest first: the first kDenseHeavy get the wide list requests.
+    uint32_t pos = 0, end = 0, src = 0, ridx = 0xFFFFFFFFu;
+    {
+      uint32_t len = 0;
+      HugeRun hr;
+      hr.start = hr.len = hr.src = 0;
+      if (lane < R && r0 + (uint32_t)lane < nruns) {
+        hr = a.huge_runs[base + r0 + (uint32_t)lane];
+        len = hr.len;
+      }
+      uint32_t rank = 0;
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        const uint32_t lj = (uint32_t)__builtin_amdgcn_readlane((int)len, j);
+        rank += (lj > len || (lj == len && j < lane)) ? 1u : 0u;
+      }
+      rank = lane < R ? rank : (uint32_t)lane;
+      uint32_t lo = 0;
+      if (len != 0 && wb_lo < wb_hi) {
         const uint32_t* bags = (hr.src ? a.vals[1] : a.vals[0]) + hr.start;
-        uint32_t lo = 0, hi = hr.len;
+        uint32_t hi = hr.len;
         while (lo < hi) {
           const uint32_t mid = (lo + hi) >> 1;
-          if (bags[mid] < (uint32_t)bag_lo) lo = mid + 1; else hi = mid;
-        }
-        c = hr.start + lo;
-        e = hr.start + hr.len;
-        src = hr.src;
-      }
-      rpos[rl] = c;   // runs past the last one: empty
-      rend[rl] = e;
-      rsrc[rl] = src;
-    }
-    __syncthreads();
-    uint32_t pos[RW], end[RW];   // wave-uniform: next entry / end of the runs this wavefront counts
-    int want[RW];                // wave-uniform: list chunks to request for the next tile
-    const uint32_t* rb[RW];
-#pragma unroll
-    for (int i = 0; i < RW; ++i) {
-      const int rl = w + kNW * i;
-      pos[i] = rpos[rl];
-      end[i] = rend[rl];
-      want[i] = 1;
-      rb[i] = rsrc[rl] ? a.vals[1] : a.vals[0];
-    }
-    f32x4 acc[2][NBW];   // [run block][column block of this wavefront]
-#pragma unroll
-    for (int j = 0; j < NBW; ++j) acc[0][j] = acc[1][j] = zero;
-    f32x4 stage[NP];
-    {
-      const int nb = bag_hi - bag_lo < TB ? bag_hi - bag_lo : TB;
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const int bb = p * NG + grp < nb ? p * NG + grp : nb - 1;
-        stage[p] = loadf4(gk + (int64_t)(bag_lo + bb) * u.stride_b);
-      }
-    }
-    int t = 0;
-    for (int tb0 = bag_lo; tb0 < bag_hi; tb0 += TB, ++t) {  // uniform
-      const int nb = bag_hi - tb0 < TB ? bag_hi - tb0 : TB;
-      __syncthreads();  // the previous tile and its counts have been consumed
-#pragma unroll
-      for (int p = 0; p < NP; ++p) {
-        const int bb = p * NG + grp;
-        if (col_ok) storef4(tile + bb * u.d + chunk * 4, bb < nb ? stage[p] : zero);  // no stale rows
-      }
-      for (int i = tid; i < TB * R; i += kThreads) (&cmat[0][0])[i] = 0u;
-      __syncthreads();
-      if (tb0 + TB < bag_hi) {  // uniform: the next tile travels while this one is used
-        const int nn = bag_hi - (tb0 + TB) < TB ? bag_hi - (tb0 + TB) : TB;
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          const int bb = p * NG + grp < nn ? p * NG + grp : nn - 1;
-          stage[p] = loadf4(gk + (int64_t)(tb0 + TB + bb) * u.stride_b);
+          if (bags[mid] < (uint32_t)wb_lo) lo = mid + 1; else hi = mid;
         }
       }
-      // count: wavefront w takes the entries of runs w, w + 4, ... that fall into this tile (a prefix
-      // of what is left of the run).  All its runs' list chunks are requested together: per run as
-      // many 64-entry chunks as the previous tile used, plus one (a run's share of a tile changes
-      // little from tile to tile), so that a tile usually costs one round trip to memory.
+      const bool live = len != 0 && wb_lo < wb_hi;
+      pos = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank * 4), (int)(live ? hr.start + lo : 0u));
+      end = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank * 4), (int)(live ? hr.start + hr.len : 0u));
+      src = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank * 4), (int)hr.src);
+      ridx = (uint32_t)__builtin_amdgcn_ds_permute((int)(rank * 4), (int)(len != 0 ? r0 + (uint32_t)lane : 0xFFFFFFFFu));
+    }
+    const int nr = nruns - r0 < (uint32_t)R ? (int)(nruns - r0) : R;  // uniform; the absent runs are the last lanes
+    f32x4 acc[2][NH][4];   // [run block][column piece][component of the 16-byte load]
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) acc[0][h][c] = acc[1][h][c] = zero;
+#pragma unroll 1
+    for (int tb0 = wb_lo; tb0 < wb_hi; tb0 += TB) {  // wave-uniform
+      const int nb = wb_hi - tb0 < TB ? wb_hi - tb0 : TB;
+      const uint32_t bound = (uint32_t)(tb0 + nb);
+      f32x4 bq[PRE][NH];
+      for (int i = lane; i < R * CS / 4; i += DLRM_WAVE) reinterpret_cast<u32x4*>(cm)[i] = u32x4{0u, 0u, 0u, 0u};
+      // count: the entries of every run that fall into this tile are a prefix of what is left of it
       {
-        const uint32_t bound = (uint32_t)(tb0 + nb);
-        uint32_t ent[RW][kDenseDeep];
+        constexpr int HV = kDenseHeavy;
+        // every run's request goes out before the first answer is used: 256 entries of each of the
+        // longest runs, 64 of the others (requests past a run's end repeat its last entry and are
+        // masked afterwards; an absent run has pos = end = 0)
+        u32x4 hent[HV];
+        uint32_t ent[R - HV];
 #pragma unroll
-        for (int i = 0; i < RW; ++i) {
+        for (int q = 0; q < R; ++q) {
+          const uint32_t pq = (uint32_t)__builtin_amdgcn_readlane((int)pos, q);
+          const uint32_t eq = (uint32_t)__builtin_amdgcn_readlane((int)end, q);
+          const uint32_t* lq = __builtin_amdgcn_readlane((int)src, q) ? a.vals[1] : a.vals[0];
+          const uint32_t last = eq ? eq - 1u : 0u;
+          if (q < HV) {
 #pragma unroll
-          for (int q = 0; q < kDenseDeep; ++q) {
-            ent[i][q] = 0xFFFFFFFFu;
-            const uint32_t e = pos[i] + (uint32_t)(q * DLRM_WAVE + lane);
-            if (q < want[i] && e < end[i]) ent[i][q] = rb[i][e];   // q < want[i]: wave-uniform
+            for (int t = 0; t < 4; ++t) {
+              const uint32_t x = pq + (uint32_t)(4 * lane + t);
+              hent[q < HV ? q : 0][t] = lq[x < last ? x : last];
+            }
+          } else {
+            const uint32_t x = pq + (uint32_t)lane;
+            ent[q >= HV ? q - HV : 0] = lq[x < last ? x : last];
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < RW; ++i) {
-          const int rl = w + kNW * i;
-          uint32_t n = 0;
+        for (int q = 0; q < R; ++q) {
+          if (q == R / 2) {
+            // the first gradient rows travel while the second half of the runs is counted (bags past
+            // the end repeat the last one; their counts stay zero)
 #pragma unroll
-          for (int q = 0; q < kDenseDeep; ++q) {   // ascending bags: those inside the tile are a prefix
-            const bool in = ent[i][q] < bound;
-            if (in) atomicAdd(&cmat[ent[i][q] - (uint32_t)tb0][rl], 1u);
-            n += (uint32_t)__popcll(__ballot(in));
+            for (int s = 0; s < PRE; ++s) {
+              const int bag = tb0 + 4 * s + kk < wb_hi ? tb0 + 4 * s + kk : wb_hi - 1;
+#pragma unroll
+              for (int h = 0; h < NH; ++h) bq[s][h] = loadf4(gk + (int64_t)bag * u.stride_b + hoff[h]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          pos[i] += n;
-          uint32_t used = n;
-          while (n == (uint32_t)(want[i] * DLRM_WAVE)) {   // wave-uniform: every requested entry was inside
-            want[i] = kDenseDeep;
-            uint32_t bag[kDenseDeep];
+          if (q >= nr) continue;  // uniform (the gradient requests above are not skipped)
+          uint32_t pq = (uint32_t)__builtin_amdgcn_readlane((int)pos, q);
+          const uint32_t eq = (uint32_t)__builtin_amdgcn_readlane((int)end, q);
+          uint32_t* crow = cm + q * CS - tb0;
+          uint32_t n = 0, full;
+          if (q < HV) {
+            full = 4u * DLRM_WAVE;
 #pragma unroll
-            for (int q = 0; q < kDenseDeep; ++q) {
-              const uint32_t e = pos[i] + (uint32_t)(q * DLRM_WAVE + lane);
-              bag[q] = 0xFFFFFFFFu;
-              if (e < end[i]) bag[q] = rb[i][e];
+            for (int t = 0; t < 4; ++t) {
+              const uint32_t x = pq + (uint32_t)(4 * lane + t);
+              const uint32_t bag = hent[q < HV ? q : 0][t];
+              const bool in = x < eq && bag < bound;
+              if (in) atomicAdd(crow + bag, 1u);
+              n += (uint32_t)__popcll(__ballot(in));
+            }
+          } else {
+            full = (uint32_t)DLRM_WAVE;
+            const uint32_t x = pq + (uint32_t)lane;
+            const uint32_t bag = ent[q >= HV ? q - HV : 0];
+            const bool in = x < eq && bag < bound;
+            if (in) atomicAdd(crow + bag, 1u);
+            n = (uint32_t)__popcll(__ballot(in));
+          }
+          pq += n;
+          while (n == full) {   // wave-uniform: every requested entry was inside the tile
+            const uint32_t* lq = __builtin_amdgcn_readlane((int)src, q) ? a.vals[1] : a.vals[0];
+            full = 4u * DLRM_WAVE;
+            uint32_t bag[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const uint32_t x = pq + (uint32_t)(t * DLRM_WAVE + lane);
+              bag[t] = 0xFFFFFFFFu;
+              if (x < eq) bag[t] = lq[x];
             }
             n = 0;
 #pragma unroll
-            for (int q = 0; q < kDenseDeep; ++q) {
-              const bool in = bag[q] < bound;
-              if (in) atomicAdd(&cmat[bag[q] - (uint32_t)tb0][rl], 1u);
+            for (int t = 0; t < 4; ++t) {   // ascending bags: those inside are a prefix
+              const bool in = bag[t] < bound;
+              if (in) atomicAdd(crow + bag[t], 1u);
               n += (uint32_t)__popcll(__ballot(in));
             }
-            pos[i] += n;
-            used += n;
+            pq += n;
           }
-          const int w1 = (int)(used / DLRM_WAVE) + 1;
-          want[i] = w1 < kDenseDeep ? w1 : kDenseDeep;
+          pos = lane == q ? pq : pos;
         }
       }
+      // contract over the bags of the tile, four per step
+#pragma unroll
+      for (int s = 0; s < TB / 4; ++s) {
+        const float a0 = (float)cm[m * CS + 4 * s + kk];
+        const float a1 = (float)cm[(16 + m) * CS + 4 * s + kk];
+        f32x4 cur[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) cur[h] = bq[s % PRE][h];
+        if (s + PRE < TB / 4) {
+          const int bag = tb0 + 4 * (s + PRE) + kk < wb_hi ? tb0 + 4 * (s + PRE) + kk : wb_hi - 1;
+#pragma unroll
+          for (int h = 0; h < NH; ++h) bq[s % PRE][h] = loadf4(gk + (int64_t)bag * u.stride_b + hoff[h]);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // the request stays PRE steps ahead of its use
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            acc[0][h][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, cur[h][c], acc[0][h][c], 0, 0, 0);
+            acc[1][h][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, cur[h][c], acc[1][h][c], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // the four wavefronts' results added in bag order: wavefront 0 takes in 1, 2, 3 through LDS
+    // (run slot r, column j at red[r * d + j]).  out[mb][h][v]: run slot 16*mb + 4*(l/16) + v, the four
+    // columns 64h + 4*(l%16) + c.
+    f32x4 out[2][NH][4];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          out[mb][h][v] = f32x4{acc[mb][h][0][v], acc[mb][h][1][v], acc[mb][h][2][v], acc[mb][h][3][v]};
+    __syncthreads();   // every count matrix has been consumed
+    for (int from = 1; from < kNW; ++from) {  // uniform
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (w == from && col_ok[h]) storef4(red + (mb * 16 + kk * 4 + v) * u.d + 64 * h + 4 * m, out[mb][h][v]);
       __syncthreads();
-      // contract over the bags of the tile, four per instruction
-      {
-        const int m = lane & 15, kk = lane >> 4;
-#pragma unroll 2
-        for (int k0 = 0; k0 < TB; k0 += 4) {
-          const float a0 = (float)cmat[k0 + kk][m];
-          const float a1 = (float)cmat[k0 + kk][16 + m];
-          const float* trow = tile + (k0 + kk) * u.d;
 #pragma unroll
-          for (int j = 0; j < NBW; ++j) {
-            const int col = (w + kNW * j) * 16 + m;
-            if ((w + kNW * j) * 16 < u.d) {  // wave-uniform
-              const float b = col < u.d ? trow[col] : 0.0f;
-              acc[0][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b, acc[0][j], 0, 0, 0);
-              acc[1][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b, acc[1][j], 0, 0, 0);
-            }
-          }
-        }
-      }
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (w == 0 && col_ok[h]) out[mb][h][v] += loadf4(red + (mb * 16 + kk * 4 + v) * u.d + 64 * h + 4 * m);
+      __syncthreads();
     }
-    // D[m = 4*(l/16) + v][n = l%16]: run r0 + 16*mb + m, column 16*(w + kNW*j) + n
-    {
-      const int n = lane & 15, mq = (lane >> 4) * 4;
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
+    for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int j = 0; j < NBW; ++j) {
-          const int col = (w + kNW * j) * 16 + n;
+      for (int v = 0; v < 4; ++v) {
+        // the run that was dealt to accumulator row mb*16 + kk*4 + v
+        const uint32_t run = (uint32_t)__shfl((int)ridx, mb * 16 + kk * 4 + v, DLRM_WAVE);
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const uint32_t run = r0 + (uint32_t)(mb * 16 + mq + v);
-            if (run < nruns && col < u.d)
-              a.huge_part[((size_t)(base + run) * ngroups + g) * u.d + col] = acc[mb][j][v];
-          }
-        }
+        for (int h = 0; h < NH; ++h)
+          if (w == 0 && run != 0xFFFFFFFFu && col_ok[h])
+            storef4(a.huge_part + ((size_t)(base + run) * ngroups + g) * u.d + 64 * h + 4 * m, out[mb][h][v]);
       }
-    }
   }
 }
 
@@ -515,13 +571,31 @@ int launch_segment_sort(const GroupArgs& g, hipStream_t st) {
   return DLRM_OK;
 }
 
+// Bag groups of the dense kernel: as few as fill the machine once (gfx950: 256 compute units, three
+// resident workgroups each, two for rows above 128 columns), never more than the partial-sum layout
+// has room for; a wavefront's quarter of a group is whole tiles.
+static void dense_groups(int B, int K, int nh, int ngroups, int* group_bags, int* ngd) {
+  const int slots = 256 * (nh <= 2 ? 3 : 2);
+  int n = slots / (K > 0 ? K : 1);
+  n = n < 1 ? 1 : (n > ngroups ? ngroups : n);
+  const int unit = kNW * kDenseTile;
+  int gb = ((B + n - 1) / n + unit - 1) / unit * unit;
+  if (gb < unit) gb = unit;
+  *group_bags = gb;
+  *ngd = (B + gb - 1) / gb;
+}
+
 template <int G>
-static int launch_hot(const GroupArgs& g, const UpdArgs& u, int K, int ngroups, hipStream_t st) {
+static int launch_hot(const GroupArgs& g, const UpdArgs& u, int K, int ngroups, int* ngd, hipStream_t st) {
+  *ngd = ngroups;
   if (g.weights != nullptr) {
     hipLaunchKernelGGL((hot_rows_kernel<G, true>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups, 0);
   } else {
     // tables with many hot rows go through the dense kernel, the others through the entry-by-entry one
-    hipLaunchKernelGGL((hot_rows_dense_kernel<G>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups);
+    constexpr int NH = G <= 16 ? 1 : G == 32 ? 2 : 4;
+    int group_bags;
+    dense_groups(g.B, K, NH, ngroups, &group_bags, ngd);
+    hipLaunchKernelGGL((hot_rows_dense_kernel<NH>), dim3(*ngd, K), dim3(kThreads), 0, st, g, u, ngroups, group_bags);
     DLRM_CHECK_LAUNCH();
     hipLaunchKernelGGL((hot_rows_kernel<G, false>), dim3(ngroups, K), dim3(kThreads), 0, st, g, u, ngroups,
                        kDenseFrom);
@@ -530,15 +604,16 @@ static int launch_hot(const GroupArgs& g, const UpdArgs& u, int K, int ngroups, 
   return DLRM_OK;
 }
 
-int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, hipStream_t st) {
+int launch_hot_rows(const GroupArgs& g, const UpdArgs& u, int G, int K, int ngroups, int* dense_groups_used,
+                    hipStream_t st) {
   switch (G) {
-    case 1: return launch_hot<1>(g, u, K, ngroups, st);
-    case 2: return launch_hot<2>(g, u, K, ngroups, st);
-    case 4: return launch_hot<4>(g, u, K, ngroups, st);
-    case 8: return launch_hot<8>(g, u, K, ngroups, st);
-    case 16: return launch_hot<16>(g, u, K, ngroups, st);
-    case 32: return launch_hot<32>(g, u, K, ngroups, st);
-    case 64: return launch_hot<64>(g, u, K, ngroups, st);
+    case 1: return launch_hot<1>(g, u, K, ngroups, dense_groups_used, st);
+    case 2: return launch_hot<2>(g, u, K, ngroups, dense_groups_used, st);
+    case 4: return launch_hot<4>(g, u, K, ngroups, dense_groups_used, st);
+    case 8: return launch_hot<8>(g, u, K, ngroups, dense_groups_used, st);
+    case 16: return launch_hot<16>(g, u, K, ngroups, dense_groups_used, st);
+    case 32: return launch_hot<32>(g, u, K, ngroups, dense_groups_used, st);
+    case 64: return launch_hot<64>(g, u, K, ngroups, dense_groups_used, st);
   }
   return DLRM_ERR_BAD_SHAPE;
 }
