@@ -190,6 +190,97 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
   }
 }
 
+// A bucket sorted in LDS (unweighted batch), reduced with the WORK, not the runs, dealt evenly: lane
+// group g takes the sorted entries [g*E, (g+1)*E), E = ceil(n / groups), whatever runs they belong
+// to, U gradient rows in flight from the first entry to the last.  An entry whose row differs from
+// its predecessor's starts a run (its table row is requested with the gradient rows of its round);
+// a run that ends inside the slab is applied at once.  What a slab holds of a run that began in an
+// earlier slab goes to LDS, and after one barrier the group where a run began adds the later slabs'
+// pieces in slab order and applies the row.  Within a run the entries are added in position order
+// inside each slab and the slabs in order: a fixed order, the same on every call.  No list of run
+// heads is needed, and a run of any length inside the bucket is covered.
+template <int DT, int G, int OPT>
+__device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, const uint32_t* skey,
+                                    const uint32_t* sval, uint32_t n, float* part, uint32_t* flags) {
+  constexpr int NG = kThreads / G;
+  constexpr int U = (OPT == kAdagrad || DT == DLRM_F32) ? 4 : 6;
+  const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
+  const bool col_ok = chunk * 4 < u.d;
+  const int cchunk = col_ok ? chunk : 0;  // lanes past the last column shadow column group 0 and never write
+  const float* g = u.dS + (int64_t)b.k * u.stride_k + cchunk * 4;
+  float* H = state_base<OPT>(u, b.k);
+  const uint32_t E = (n + NG - 1) / NG;
+  const uint32_t p0 = (uint32_t)grp * E < n ? (uint32_t)grp * E : n;
+  const uint32_t p1 = p0 + E < n ? p0 + E : n;
+  const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+  f32x4 acc = zero, headp = zero;
+  bool have = false;   // a run has begun in this slab
+  RowRef cur{nullptr, nullptr};
+  RowVal curv{};
+  for (uint32_t c0 = p0; c0 < p1; c0 += U) {
+    uint32_t key[U];
+    bool hd[U];
+    f32x4 v[U];
+    // the table rows of the runs that begin in this round (16-bit tables: 8 bytes per lane)
+    u32x2 wlo[U], whi[DT == DLRM_F32 ? U : 1];
+    f32x4 wh[OPT == kAdagrad ? U : 1];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const uint32_t p = c0 + j < p1 ? c0 + j : p1 - 1;
+      key[j] = skey[p];
+      const uint32_t prev = skey[p > 0 ? p - 1 : 0];
+      hd[j] = c0 + j < p1 && (p == 0 || key[j] != prev);
+      v[j] = loadf4(g + (int64_t)sval[p] * u.stride_b);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      wlo[j] = u32x2{0u, 0u};
+      if constexpr (DT == DLRM_F32) whi[j] = u32x2{0u, 0u};
+      if constexpr (OPT == kAdagrad) wh[j] = zero;
+      if (hd[j]) {
+        const RowVal t = row_load<DT, OPT>(row_ref<DT, OPT>(W, H, u.d, key[j], cchunk));
+        wlo[j] = u32x2{t.w.x, t.w.y};
+        if constexpr (DT == DLRM_F32) whi[j] = u32x2{t.w.z, t.w.w};
+        if constexpr (OPT == kAdagrad) wh[j] = t.h;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      if (hd[j]) {
+        if (have) {
+          if (col_ok) row_update_store<DT, OPT>(cur, curv, acc, u);
+        } else {
+          headp = acc;
+        }
+        acc = zero;
+        cur = row_ref<DT, OPT>(W, H, u.d, key[j], cchunk);
+        curv.w = u32x4{wlo[j].x, wlo[j].y, 0u, 0u};
+        if constexpr (DT == DLRM_F32) {
+          curv.w.z = whi[j].x;
+          curv.w.w = whi[j].y;
+        }
+        if constexpr (OPT == kAdagrad) curv.h = wh[j];
+        have = true;
+      }
+      if (c0 + j < p1) acc += v[j];
+    }
+  }
+  if (!have) headp = acc;   // the whole slab continues an earlier run (an empty slab: zero)
+  if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, headp);
+  if (chunk == 0) flags[grp] = p0 < p1 ? (have ? 1u : 2u) : 0u;   // empty / a run begins here / all continuation
+  __syncthreads();
+  if (have) {
+    f32x4 tot = acc;
+    for (int g2 = grp + 1; g2 < NG; ++g2) {
+      const uint32_t f = flags[g2];
+      if (f == 0u) break;
+      tot += loadf4(part + g2 * (G * 4) + cchunk * 4);
+      if (f == 1u) break;
+    }
+    if (col_ok) row_update_store<DT, OPT>(cur, curv, tot, u);
+  }
+}
+
 // Run heads of sorted keys[0..n) (LDS) into s.heads (positions, ascending) with the sentinel
 // heads[nruns] = n.  Returns nruns.  All threads call it.
 __device__ inline uint32_t compact_heads_lds(SortLds& s, int n) {
@@ -514,6 +605,10 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
     return;
   }
   sort_bucket_lds(a, rest, s, 0);
+  if constexpr (!WT) {
+    reduce_slabs<DT, G, OPT>(u, rest, W, s.skey, s.sval, rest.n, part, s.heads);
+    return;
+  }
   const uint32_t nruns = compact_heads_lds(s, (int)rest.n);
   const uint32_t nlong = collect_long_runs(s, nruns, long_run<G>());
   reduce_runs<DT, G, OPT, WT>(a, u, rest, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 0, part);
@@ -533,6 +628,10 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
   char* W = static_cast<char*>(u.tables[b.k]);
   if (b.n <= (uint32_t)kBktCap) {
     sort_bucket_lds(a, b, s);
+    if constexpr (!WT) {
+      reduce_slabs<DT, G, OPT>(u, b, W, s.skey, s.sval, b.n, part, s.heads);
+      return;
+    }
     // weighted: the gathers that resolve every sorted entry are in flight while the runs are found
     uint32_t ebag[WT ? kBktItems : 1];
     float ew[WT ? kBktItems : 1];

@@ -138,7 +138,8 @@ __device__ inline int64_t index_at(const void* indices, int is32, int64_t i) {
 }
 
 // Streaming accesses: data touched once per launch (table rows) should not push reusable data
-// (gradient rows, pair lists) out of the L2.
+// (gradient rows, pair lists) out of the L2.  (Flat accesses on purpose: the same helpers through
+// global-address-space pointers measured 2-3 % slower in the update kernels.)
 __device__ inline u32x4 load16_stream(const void* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
