@@ -37,20 +37,6 @@ struct ResolvedW {
   float* hi;  // entries [kResolvedLo, kBktCap)
   __device__ float& at(uint32_t i) const { return i < (uint32_t)kResolvedLo ? lo[i] : hi[i - kResolvedLo]; }
 };
-// RES: vals[i] is the bag and rw.at(i) the weight; otherwise the entry is looked up by vals[i].
-template <bool WT, bool RES>
-__device__ inline Entry entry_at(const GroupArgs& a, int64_t tbl, const uint32_t* vals, uint32_t i,
-                                 const ResolvedW& rw) {
-  if constexpr (WT && RES) {
-    Entry e;
-    e.bag = vals[i];
-    e.w = rw.at(i);
-    return e;
-  } else {
-    return entry_of<WT>(a, tbl, vals[i]);
-  }
-}
-
 // Runs longer than this are summed by the whole workgroup.  With many lane groups per workgroup
 // (narrow rows) a medium run left to one lane group is the critical path of the bucket sooner.
 template <int G>
@@ -61,16 +47,16 @@ __device__ constexpr uint32_t long_run() {
 // Sum (weight times) dS rows of the sorted entries [i0, i1) taking every `stride`-th entry from
 // i0 + first; U loads in flight, ascending order.  vals: LDS or global.  tbl: start of the table
 // in the batch's index array.
-template <int U, bool WT, bool RES>
+template <int U, bool WT>
 __device__ inline f32x4 sum_entries(const GroupArgs& a, int64_t tbl, const float* g, int64_t stride_b,
-                                    const uint32_t* vals, const ResolvedW& rw, uint32_t i0, uint32_t i1,
+                                    const uint32_t* vals, uint32_t i0, uint32_t i1,
                                     uint32_t first, uint32_t stride) {
   f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
   for (uint32_t i = i0 + first; i < i1; i += U * stride) {
     Entry e[U];
     f32x4 v[U];
 #pragma unroll
-    for (int t = 0; t < U; ++t) e[t] = entry_at<WT, RES>(a, tbl, vals, i + t * stride < i1 ? i + t * stride : i, rw);
+    for (int t = 0; t < U; ++t) e[t] = entry_of<WT>(a, tbl, vals[i + t * stride < i1 ? i + t * stride : i]);
 #pragma unroll
     for (int t = 0; t < U; ++t) v[t] = loadf4(g + (int64_t)e[t].bag * stride_b);
 #pragma unroll
@@ -92,11 +78,11 @@ __device__ inline f32x4 sum_entries(const GroupArgs& a, int64_t tbl, const float
 
 // keys/bags: the bucket's sorted pairs (n of them; LDS or global), heads: LDS list of run starts
 // with heads[nruns] = n.  gpos0: global position of the bucket's first pair.
-template <int DT, int G, int OPT, bool WT, bool RES = false>
+template <int DT, int G, int OPT, bool WT>
 __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const Bucket& b, char* W,
                                    const uint32_t* keys, const uint32_t* bags, const uint32_t* heads,
                                    uint32_t h0, uint32_t nruns, const uint32_t* longs, uint32_t nlong,
-                                   int src, float* part, const ResolvedW& rw = ResolvedW{nullptr, nullptr}) {
+                                   int src, float* part) {
   constexpr int NG = kThreads / G;
   // gradient rows a lane group keeps in flight while the workgroup sums a long run: few lane groups
   // (wide rows) need more each to keep the same number of bytes in flight
@@ -125,7 +111,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     }
     Entry e0[RU];
 #pragma unroll
-    for (int t = 0; t < RU; ++t) e0[t] = entry_at<WT, RES>(a, tbl, bags, i0[t], rw);
+    for (int t = 0; t < RU; ++t) e0[t] = entry_of<WT>(a, tbl, bags[i0[t]]);
 #pragma unroll
     for (int t = 0; t < RU; ++t) acc[t] = loadf4(g + (int64_t)e0[t].bag * u.stride_b);
 #pragma unroll
@@ -138,7 +124,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     for (int t = 0; t < RU; ++t) {
       const uint32_t len = i1[t] - i0[t];
       if (r0 + t >= nruns || len > long_run<G>()) continue;
-      if (len > 1) acc[t] += sum_entries<4, WT, RES>(a, tbl, g, u.stride_b, bags, rw, i0[t] + 1, i1[t], 0, 1);
+      if (len > 1) acc[t] += sum_entries<4, WT>(a, tbl, g, u.stride_b, bags, i0[t] + 1, i1[t], 0, 1);
       if (col_ok) row_update_store<DT, OPT>(wp[t], wv[t], acc[t], u);
     }
   }
@@ -167,7 +153,7 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
     RowRef wr = row_ref<DT, OPT>(W, H, u.d, keys[i0], cchunk);
     RowVal wv{};
     if (upd) wv = row_load<DT, OPT>(wr);
-    const f32x4 acc = sum_entries<kLongU, WT, RES>(a, tbl, g, u.stride_b, bags, rw, i0, i1, (uint32_t)grp, (uint32_t)NG);
+    const f32x4 acc = sum_entries<kLongU, WT>(a, tbl, g, u.stride_b, bags, i0, i1, (uint32_t)grp, (uint32_t)NG);
     __syncthreads();
     if (col_ok) storef4(part + grp * (G * 4) + chunk * 4, acc);
     __syncthreads();
@@ -199,9 +185,11 @@ __device__ inline void reduce_runs(const GroupArgs& a, const UpdArgs& u, const B
 // pieces in slab order and applies the row.  Within a run the entries are added in position order
 // inside each slab and the slabs in order: a fixed order, the same on every call.  No list of run
 // heads is needed, and a run of any length inside the bucket is covered.
-template <int DT, int G, int OPT>
+// WT: sval holds the resolved bags and rw the weights a of Eq. (2) of the sorted entries.
+template <int DT, int G, int OPT, bool WT = false>
 __device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, const uint32_t* skey,
-                                    const uint32_t* sval, uint32_t n, float* part, uint32_t* flags) {
+                                    const uint32_t* sval, uint32_t n, float* part, uint32_t* flags,
+                                    const ResolvedW& rw = ResolvedW{nullptr, nullptr}) {
   constexpr int NG = kThreads / G;
   constexpr int U = (OPT == kAdagrad || DT == DLRM_F32) ? 4 : 6;
   const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
@@ -221,6 +209,7 @@ __device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, 
     uint32_t key[U];
     bool hd[U];
     f32x4 v[U];
+    float wt[WT ? U : 1];
     // the table rows of the runs that begin in this round (16-bit tables: 8 bytes per lane)
     u32x2 wlo[U], whi[DT == DLRM_F32 ? U : 1];
     f32x4 wh[OPT == kAdagrad ? U : 1];
@@ -231,6 +220,7 @@ __device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, 
       const uint32_t prev = skey[p > 0 ? p - 1 : 0];
       hd[j] = c0 + j < p1 && (p == 0 || key[j] != prev);
       v[j] = loadf4(g + (int64_t)sval[p] * u.stride_b);
+      if constexpr (WT) wt[j] = rw.at(p);
     }
 #pragma unroll
     for (int j = 0; j < U; ++j) {
@@ -262,7 +252,16 @@ __device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, 
         if constexpr (OPT == kAdagrad) curv.h = wh[j];
         have = true;
       }
-      if (c0 + j < p1) acc += v[j];
+      if (c0 + j < p1) {
+        if constexpr (WT) {
+          acc.x = fmaf(wt[j], v[j].x, acc.x);
+          acc.y = fmaf(wt[j], v[j].y, acc.y);
+          acc.z = fmaf(wt[j], v[j].z, acc.z);
+          acc.w = fmaf(wt[j], v[j].w, acc.w);
+        } else {
+          acc += v[j];
+        }
+      }
     }
   }
   if (!have) headp = acc;   // the whole slab continues an earlier run (an empty slab: zero)
@@ -632,7 +631,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
       reduce_slabs<DT, G, OPT>(u, b, W, s.skey, s.sval, b.n, part, s.heads);
       return;
     }
-    // weighted: the gathers that resolve every sorted entry are in flight while the runs are found
+    // weighted: every sorted entry is resolved (position -> bag, weight) once, by all threads at the same time
     uint32_t ebag[WT ? kBktItems : 1];
     float ew[WT ? kBktItems : 1];
     if constexpr (WT) {
@@ -646,8 +645,6 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
         ew[j] = pe.w;
       }
     }
-    const uint32_t nruns = compact_heads_lds(s, (int)b.n);
-    const uint32_t nlong = collect_long_runs(s, nruns, long_run<G>());
     const ResolvedW rw{reinterpret_cast<float*>(&s.wcnt[0][0]), wext};
     if constexpr (WT) {
 #pragma unroll
@@ -660,7 +657,7 @@ __global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_redu
       }
       __syncthreads();
     }
-    reduce_runs<DT, G, OPT, WT, WT>(a, u, b, W, s.skey, s.sval, s.heads, 0u, nruns, s.longs, nlong, 1, part, rw);
+    reduce_slabs<DT, G, OPT, WT>(u, b, W, s.skey, s.sval, b.n, part, s.heads, rw);
     return;
   }
   if (b.low_bits == 0) {  // the bucket holds one row: a single run, already in position order
