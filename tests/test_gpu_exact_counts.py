@@ -57,6 +57,10 @@ CASES = [
      ("heavy_ranges", "oversized_ranges", "dominant_row_splits", "hot_rows", "dense_hot_tables")),
     ("bf16-zipf-d64", 3, 8192, 64, gen.BF16, 30000, ("fixed", 12), ("zipf", 1.3),
      ("oversized_ranges", "dominant_row_splits", "hot_rows")),
+    # a gradient slice of 6.3 MB per table: the update deals its row ranges to the dies by table; nine tables, so
+    # that eight go through that mapping and the ninth keeps the plain order
+    ("nine-tables-by-die", 9, 16384, 96, gen.F32, 20000, ("fixed", 3), ("zipf", 1.1),
+     ("oversized_ranges", "dominant_row_splits", "hot_rows")),
 ]
 
 MODES = ["sort", "prepared", "flat"]
