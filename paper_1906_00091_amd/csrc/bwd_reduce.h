@@ -191,9 +191,12 @@ __device__ inline void reduce_slabs(const UpdArgs& u, const Bucket& b, char* W, 
                                     const uint32_t* sval, uint32_t n, float* part, uint32_t* flags,
                                     const ResolvedW& rw = ResolvedW{nullptr, nullptr}) {
   constexpr int NG = kThreads / G;
-  // rows in flight per lane group, measured on the hot-row workload (16-bit tables: 3 / 4 / 6 / 8 / 10 -> 1.154 /
-  // 1.178 / 1.140 / 1.123 / 1.240 ms per launch, 8 with a 112-byte spill) and on the multi-hot and one-hot ones (fp32: 4)
-  constexpr int U = (OPT == kAdagrad || DT == DLRM_F32) ? 4 : 8;
+  // Gradient rows in flight per lane group, each measured with whole libraries on one box.  16-bit tables, SGD (128
+  // registers): 3 / 4 / 6 / 8 / 10 -> 1.154 / 1.178 / 1.140 / 1.123 / 1.240 ms per launch on the hot-row workload.
+  // fp32, SGD (168 registers): 4 / 8 / 12 -> 165 / 162 / 160 us on the multi-hot workload, step 135.8 / 134.3 /
+  // 132.5 us on the large one-hot one (12 spills 120 bytes; 16 spills 300).  Adagrad: 4 / 6 / 8 -> 325 / 317 / 324 us
+  // (multi-hot), 2.66 / 2.40 / 2.57 ms (hot-row).
+  constexpr int U = OPT == kAdagrad ? 6 : DT == DLRM_F32 ? 12 : 8;
   const int grp = threadIdx.x / G, chunk = threadIdx.x % G;
   const bool col_ok = chunk * 4 < u.d;
   const int cchunk = col_ok ? chunk : 0;  // lanes past the last column shadow column group 0 and never write
@@ -616,7 +619,9 @@ __device__ inline void reduce_oversized(const GroupArgs& a, const UpdArgs& u, co
 }
 
 template <int DT, int G, int OPT, bool WT>
-__global__ __launch_bounds__(kThreads, OPT == kAdagrad ? 3 : 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
+// register budget: 4 wavefronts per SIMD for 16-bit tables with SGD, 3 (168 registers) otherwise -- measured both ways
+// on the multi-hot and one-hot workloads (fp32: 3 is 2 % ahead) and on the hot-row one (fp16: 4 is 12 % ahead)
+__global__ __launch_bounds__(kThreads, (OPT == kAdagrad || DT == DLRM_F32) ? 3 : 4) void bucket_reduce_kernel(GroupArgs a, UpdArgs u) {
   __shared__ SortLds s;
   __shared__ SplitLds sp;
   __shared__ float part[kThreads * 4];
