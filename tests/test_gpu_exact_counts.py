@@ -216,3 +216,55 @@ def test_adagrad_state_equals_the_oracle_on_exact_inputs(case):
             w0 = np.abs(widen_host(comp.tables[k], dtype))
             scale = w0 + lr * sg[k].astype(np.float64) / (np.sqrt(h0[k].astype(np.float64)) + eps)
             assert rel_err(got_w, widen_host(ref_w[k], dtype), scale, SCALE_FLOOR[dtype]) <= TOL[dtype]
+
+
+def _random_shape(seed):
+    """A small seeded shape off the beaten track: row widths of any multiple of 4, tables from one row to a few
+    thousand, empty / one-hot / ragged / fixed bags, uniform or skewed indices, any of the three table types."""
+    rng = np.random.default_rng([1906, seed])
+    d = int(rng.choice([4, 8, 12, 16, 24, 32, 48, 64, 96, 128, 160, 256]))
+    K = int(rng.integers(1, 7))
+    B = int(rng.choice([1, 3, 17, 64, 257, 1000, 2048, 5000]))
+    rows = int(rng.choice([1, 2, 7, 100, 1000, 4096, 30000]))
+    bag = [("fixed", 1), ("fixed", int(rng.integers(2, 40))), ("uniform", 0, int(rng.integers(1, 60))),
+           ("uniform", 1, 3)][int(rng.integers(0, 4))]
+    dist = [("uniform",), ("zipf", 1.05), ("zipf", 1.4)][int(rng.integers(0, 3))]
+    dtype = [gen.F32, gen.F16, gen.BF16][int(rng.integers(0, 3))]
+    if dtype != gen.F32 and d % 8:
+        d *= 2          # a 16-bit row is whole 16-byte pieces
+    return K, B, d, dtype, rows, bag, dist
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_shapes_sgd_update_equals_the_oracle_on_exact_inputs(seed):
+    """Thirty-two seeded random shapes through the same exact-arithmetic comparison, sum and weighted pooling,
+    the complete call and the prepared one: whichever way the sorted entries fall into the lane groups' slabs
+    (empty slabs, a run across several slabs, a run that ends on a slab boundary, a bucket smaller than the
+    number of lane groups), every touched row must equal the oracle's and no other row may change."""
+    K, B, d, dtype, rows, bag, dist = _random_shape(seed)
+    name = "random-%d" % seed
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=100 + seed)
+    b = gen.make_batch(w)
+    _say("exact sgd %s K=%d B=%d d=%d dtype=%s rows=%d bag=%s dist=%s nnz=%d" % (name, K, B, d, dtype, rows, bag, dist, b.nnz))
+    lr = 0.5 if dtype == gen.F32 else 2.0 ** -8
+    start = _integer_tables(b.rows, d, dtype, seed=5)
+    comp = Compact(b, host_rows_of=lambda k, u: table_to_numpy(
+        start[k].index_select(0, torch.from_numpy(u).to(DEV)), dtype))
+    F = K + 1
+    for weighted in (False, True):
+        wts = _pow2_weights(b) if weighted else None
+        dS = _integer_dS(B, K, d, max(_max_run(b), 1), 2.0 if weighted else 1.0)
+        ref = [t.copy() for t in comp.tables]
+        if weighted:
+            oracle.emb_bag_bwd_weighted(ref, dtype, comp.indices, b.offsets, b.tbl_off, wts, dS, lr)
+        else:
+            oracle.emb_bag_bwd_sgd(ref, dtype, comp.indices, b.offsets, b.tbl_off, dS, lr)
+        dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+        dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+        for mode in ("sort", "prepared"):
+            tables = [t.clone() for t in start]
+            _run_update(b, tables, dT, lr, mode, weights=wts)
+            for k in range(K):
+                got = table_to_numpy(tables[k].index_select(0, torch.from_numpy(comp.uniq[k]).to(DEV)), dtype)
+                assert np.array_equal(got.view(np.uint8), ref[k].view(np.uint8)), (name, weighted, mode, k)
+                _assert_only_touched_rows_changed(start[k], tables[k], comp.uniq[k])
