@@ -268,3 +268,48 @@ def test_random_shapes_sgd_update_equals_the_oracle_on_exact_inputs(seed):
                 got = table_to_numpy(tables[k].index_select(0, torch.from_numpy(comp.uniq[k]).to(DEV)), dtype)
                 assert np.array_equal(got.view(np.uint8), ref[k].view(np.uint8)), (name, weighted, mode, k)
                 _assert_only_touched_rows_changed(start[k], tables[k], comp.uniq[k])
+
+
+def _random_hot_shape(seed):
+    """Few rows, thousands of lookups each: every row is a hot row, and a table with at least 8 of them goes
+    through the matrix-core kernel -- with bag counts that leave a last bag group, a last wavefront quarter and a
+    last 64-bag tile partly empty, row widths of one, two and four 64-column pieces, and more hot rows than one
+    pass holds."""
+    rng = np.random.default_rng([5, seed])
+    d = int(rng.choice([8, 32, 64, 96, 128, 160, 256]))
+    K = int(rng.integers(1, 4))
+    B = int(rng.choice([2500, 3000, 4096, 4099]))
+    rows = int(rng.choice([3, 9, 20, 33, 40]))
+    bag = ("fixed", int(rng.integers(25, 41)))
+    rows = max(1, min(rows, B * bag[1] // 3000))   # about 3000 lookups a row or more
+    dtype = [gen.F32, gen.F16][seed % 2]
+    return K, B, d, dtype, rows, bag, ("uniform",)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_hot_row_shapes_sgd_update_equals_the_oracle_on_exact_inputs(seed):
+    K, B, d, dtype, rows, bag, dist = _random_hot_shape(seed)
+    name = "random-hot-%d" % seed
+    w = gen.custom_workload(name, K=K, B=B, d=d, dtype=dtype, rows=rows, bag=bag, dist=dist, seed=200 + seed)
+    b = gen.make_batch(w)
+    _say("exact sgd %s K=%d B=%d d=%d dtype=%s rows=%d bag=%s nnz=%d" % (name, K, B, d, dtype, rows, bag, b.nnz))
+    lr = 0.5 if dtype == gen.F32 else 2.0 ** -8
+    start = _integer_tables(b.rows, d, dtype, seed=5)
+    comp = Compact(b, host_rows_of=lambda k, u: table_to_numpy(
+        start[k].index_select(0, torch.from_numpy(u).to(DEV)), dtype))
+    dS = _integer_dS(B, K, d, _max_run(b))
+    ref = [t.copy() for t in comp.tables]
+    oracle.emb_bag_bwd_sgd(ref, dtype, comp.indices, b.offsets, b.tbl_off, dS, lr)
+    F = K + 1
+    dT = torch.zeros((B, F, d), dtype=torch.float32, device=DEV)
+    dT[:, 1:, :] = torch.from_numpy(dS).to(DEV)
+    tables = [t.clone() for t in start]
+    counts = _run_update(b, tables, dT, lr, "sort")
+    print("        routes: " + ", ".join("%s=%d" % kv for kv in counts.items() if kv[1]), flush=True)
+    hot_per_table = [int((np.bincount(b.indices_of(k)) > 2048).sum()) for k in range(K)]
+    assert counts["hot_rows"] == sum(hot_per_table) > 0
+    assert counts["dense_hot_tables"] == sum(1 for n in hot_per_table if n >= 8)
+    for k in range(K):
+        got = table_to_numpy(tables[k].index_select(0, torch.from_numpy(comp.uniq[k]).to(DEV)), dtype)
+        assert np.array_equal(got.view(np.uint8), ref[k].view(np.uint8)), (name, k)
+        _assert_only_touched_rows_changed(start[k], tables[k], comp.uniq[k])
